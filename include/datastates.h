@@ -1,0 +1,267 @@
+/*
+ * datastates.h -- C ABI of the MI355X snapshot hot path (libdatastates_hip.so).
+ *
+ * One GPU's part of the lazy, non-blocking checkpoint snapshot of
+ * DataStates-LLM (arXiv 2601.16956): the fragmented, mixed-precision, possibly
+ * strided model/optimizer shards of one rank are coalesced into one contiguous
+ * image laid out like the checkpoint file (Sec. V-A1 "coalescing", Sec. V-A5
+ * rule (1) "fixed offsets"), the image is streamed to a pre-pinned, reused
+ * host ring (Sec. V-A1, Sec. V-B/V-C "pinned circular buffer") in chunks that
+ * need not be whole tensors (Sec. V-A4), while training continues; the
+ * mutating update phase is gated on the capture (Sec. V-A2).  Restore is the
+ * inverse scatter.
+ *
+ * Conventions
+ *   - Plain C.  No HIP or torch types: a stream is passed as `void*` holding a
+ *     hipStream_t (NULL = the null stream).  "dev" pointers are device
+ *     addresses valid on the device that was current when the plan / engine
+ *     was created; "host" pointers are ordinary host addresses.
+ *   - Every function returns an int: DS_OK (0), a positive status
+ *     (DS_NOT_READY, DS_EOF) or a negative error.  Nothing throws or aborts.
+ *     Out-parameters are written only on DS_OK (or the documented status).
+ *   - A plan is immutable once created and may be used from several threads;
+ *     calls on one engine are serialised by the caller.
+ *   - The image.  For shard i:  bytes_i = itemsize(dtype_i) * prod(shape_i)
+ *     (empty product = 1).  Image byte  file_offset_i + r*itemsize + b  is byte
+ *     b of the element of rank r in the row-major (last index fastest)
+ *     enumeration of the VIEW, which lives at
+ *     base_i + itemsize * sum_j k_j * strides_i[j].  Bytes as they are: no
+ *     dtype conversion, no byte swap (Sec. IV-D, Sec. V-A3: tensors are
+ *     byte-addressable buffers that need no serialisation).  Every image byte
+ *     that belongs to no shard is 0x00.  The image length is the end of the
+ *     last shard rounded up to the alignment.
+ */
+#ifndef DATASTATES_H
+#define DATASTATES_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define DS_MAX_DIMS 6
+
+/* element types; only the size matters to the byte mover: 4, 2, 2, 8, 1 */
+typedef enum ds_dtype { DS_F32 = 0, DS_BF16 = 1, DS_F16 = 2, DS_I64 = 3, DS_U8 = 4 } ds_dtype;
+
+/* status and error codes */
+#define DS_OK 0
+#define DS_NOT_READY 1 /* ds_event_query: snapshot still in flight               */
+#define DS_EOF 2       /* ds_snapshot_next_chunk: every chunk has been handed out */
+#define DS_EINVAL (-1)   /* null pointer, bad dtype/ndim/shape/stride/alignment value, misaligned base */
+#define DS_EALIGN (-2)   /* a file_offset is not a multiple of the alignment      */
+#define DS_EOVERLAP (-3) /* two shards intersect in the image, or a view addresses an element twice */
+#define DS_EGAP (-4)     /* DS_PLAN_STRICT: a hole that is not alignment padding  */
+#define DS_ERANGE (-5)   /* image range outside [0,total], reversed, or not a multiple of 16 */
+#define DS_ENOMEM (-6)   /* host or device allocation failed                      */
+#define DS_EHIP (-7)     /* a HIP call failed; see ds_last_hip_error()            */
+#define DS_EBUSY (-8)    /* object still has work in flight / chunk not released  */
+#define DS_ESTATE (-9)   /* call not valid in this state (e.g. release of a chunk never handed out) */
+
+/*
+ * One shard: a view into device memory plus its place in the file.
+ * (The "many independently owned tensor shards per rank whose boundaries are
+ * dictated by TP/PP/DP and optimizer sharding", Sec. IV-C.)
+ */
+typedef struct ds_shard_desc {
+  const void *base;               /* DEVICE address of element (0,...,0); multiple of the itemsize */
+  uint32_t dtype;                 /* ds_dtype                                                     */
+  uint32_t ndim;                  /* 0..DS_MAX_DIMS; 0 = exactly one element                      */
+  int64_t shape[DS_MAX_DIMS];     /* extents >= 0 (a zero extent = empty shard, 0 bytes)          */
+  int64_t strides[DS_MAX_DIMS];   /* in ELEMENTS, > 0 for every extent > 1; the view must not
+                                     address any element twice                                    */
+  uint64_t tensor_id;             /* logical tensor this shard is a slice of; kept in the plan's
+                                     manifest, never touches the bytes                            */
+  uint64_t file_offset;           /* byte offset of the shard in the image; multiple of `align`   */
+} ds_shard_desc;
+
+typedef struct ds_plan ds_plan;
+typedef struct ds_engine ds_engine;
+typedef struct ds_event ds_event;
+
+/* ---- layout and plan (Sec. V-A3 composite provider, duty (a): sizes and
+ *      offsets in the stream; Sec. V-A5 rule (1)) ---------------------------- */
+
+/* Size of one element in bytes, 0 for an unknown dtype. */
+int ds_itemsize(uint32_t dtype);
+
+/*
+ * Canonical layout: writes file_offset of desc[0..n) in table order, each at
+ * the next multiple of `align` after the end of the one before; *total = image
+ * length (a multiple of `align`).  Host-only, touches no device.
+ * `align` must be a power of two >= 16.  Errors: DS_EINVAL.
+ */
+int ds_layout_assign(ds_shard_desc *desc, size_t n, uint64_t align, uint64_t *total);
+
+#define DS_PLAN_STRICT 1u    /* reject holes larger than alignment padding (DS_EGAP)           */
+#define DS_PLAN_HOST_ONLY 2u /* validate and build tables on the host only; such a plan can be
+                                inspected but not passed to ds_pack/ds_unpack/ds_snapshot_async */
+
+/*
+ * Validates the table (any order of offsets; shards must be disjoint in the
+ * image), normalises every view (merges dimensions that are contiguous with
+ * each other, splits off the innermost contiguous run), cuts the image into
+ * work-group chunks and uploads the tables to the current device.  The
+ * descriptors are copied: the caller may free `desc` afterwards.  The tensors
+ * themselves stay owned by the caller and must stay allocated while the plan
+ * is used.  The plan is reused by every snapshot of the same shard set (the
+ * paper's "reused for all checkpoint requests", Sec. V-A1).
+ * Errors: DS_EINVAL, DS_EALIGN, DS_EOVERLAP, DS_EGAP, DS_ENOMEM, DS_EHIP.
+ */
+int ds_plan_create(const ds_shard_desc *desc, size_t n, uint64_t align, uint32_t flags, ds_plan **out);
+
+/* Frees host and device tables.  The caller makes sure no kernel that uses
+ * the plan is still running (synchronise the streams it was used on). */
+int ds_plan_destroy(ds_plan *plan);
+
+typedef struct ds_plan_stats {
+  uint64_t total_bytes;   /* image length T                                       */
+  uint64_t payload_bytes; /* sum of bytes_i; T - payload = padding                */
+  uint64_t n_shards;      /* descriptors given                                    */
+  uint64_t n_tiles;       /* non-empty shards (+1 if the image starts with a hole)*/
+  uint64_t n_chunks;      /* work-group chunks over the whole image               */
+  uint64_t chunk_bytes;   /* image bytes per work-group chunk                     */
+  uint64_t n_strided;     /* shards that are not one contiguous run               */
+  uint64_t align;
+} ds_plan_stats;
+
+int ds_plan_info(const ds_plan *plan, ds_plan_stats *out);
+
+/* Manifest entry i (table order as given): what a file header would record
+ * (Sec. V-A5 rule (3)).  Any out pointer may be NULL. */
+int ds_plan_shard(const ds_plan *plan, size_t i, uint64_t *tensor_id, uint32_t *dtype,
+                  uint64_t *file_offset, uint64_t *nbytes);
+
+/* ---- the kernels (gather = Sec. V-A1 coalescing done on the device; scatter
+ *      = recovery, Sec. V-A5 rule (3)) -------------------------------------- */
+
+/*
+ * Gather: writes image bytes [img_lo, img_hi) to dst_dev[0 .. img_hi-img_lo),
+ * i.e. dst_dev points at where image byte img_lo goes (a staging slot, or the
+ * start of a full-size buffer with img_lo = 0).  Padding bytes are written as
+ * zero, so the destination need not be cleared.  img_lo <= img_hi <= total,
+ * both multiples of 16; dst_dev 16-byte aligned.  Asynchronous: enqueued on
+ * `stream`; the tensors must not change until it has run.
+ * Errors: DS_EINVAL, DS_ERANGE, DS_EHIP.
+ */
+int ds_pack(const ds_plan *plan, void *dst_dev, uint64_t img_lo, uint64_t img_hi, void *stream);
+
+/*
+ * Scatter, the exact inverse: every addressed element of every shard whose
+ * image bytes lie in [img_lo, img_hi) is overwritten with src_dev[offset -
+ * img_lo ...]; elements are written whole only if all their bytes are in the
+ * range (ranges are multiples of 16 and itemsizes divide 16, so an element is
+ * never cut).  No other byte of the tensors' memory is written.
+ */
+int ds_unpack(const ds_plan *plan, const void *src_dev, uint64_t img_lo, uint64_t img_hi, void *stream);
+
+/* ---- the snapshot engine (Sec. V-A1 pre-pinned reused pool, Sec. V-A2 lazy
+ *      capture, Sec. V-A4 chunked streaming, Sec. V-C dedicated streams) ----- */
+
+#define DS_ENGINE_AUTO_RELEASE 1u /* no consumer: a ring slot is reusable as soon as its copy is done */
+
+typedef struct ds_engine_opts {
+  uint64_t host_ring_bytes;  /* pinned host ring capacity, allocated and pinned once; the paper's
+                                single tunable (Sec. V-B).  0 = 2 GiB                              */
+  uint64_t d2h_chunk_bytes;  /* size of one ring slot = one device-to-host copy; multiple of 4096.
+                                0 = 32 MiB                                                          */
+  uint64_t stage_slot_bytes; /* device staging slot = image bytes per gather launch; multiple of
+                                d2h_chunk_bytes.  0 = 1 GiB                                         */
+  uint32_t stage_slots;      /* number of device staging slots (>= 1).  0 = 2                       */
+  uint32_t pack_grid_limit;  /* max work-groups resident per gather launch; 0 = one per chunk       */
+  uint32_t flags;            /* DS_ENGINE_*                                                         */
+  uint32_t copy_streams;     /* copy streams the chunks alternate over: 1 or 2.  0 = 1              */
+} ds_engine_opts;
+
+/* Allocates the pinned ring, the device staging slots, two side streams
+ * (gather, copy; default priority) and a host thread that issues the work.
+ * Uses the current device.  Errors: DS_EINVAL, DS_ENOMEM, DS_EHIP. */
+int ds_engine_create(const ds_engine_opts *opts, ds_engine **out);
+
+/* Waits for all snapshots in flight, then frees everything.  Events created
+ * from the engine must have been destroyed.  Errors: DS_EBUSY, DS_EHIP. */
+int ds_engine_destroy(ds_engine *engine);
+
+/*
+ * Checkpoint request (Sec. V-A2): records the point of consistency on
+ * `compute_stream` and returns at once; gather launches and device-to-host
+ * copies are issued by the engine's thread on its own streams and overlap
+ * with whatever the caller enqueues next.  Between this call and the gate
+ * (ds_event_wait_on_stream / ds_event_wait_captured) the caller must not
+ * enqueue work that writes the tensors.  Snapshots on one engine run in the
+ * order requested.  *out is owned by the caller (ds_event_destroy).
+ */
+int ds_snapshot_async(ds_engine *engine, const ds_plan *plan, void *compute_stream, ds_event **out);
+
+/*
+ * The lazy gate (Sec. V-A2: the update phase is delayed only if the copies
+ * have not finished): makes `stream` wait until every source byte has been
+ * read into staging.  Returns when the wait has been enqueued; blocks the
+ * host only while the engine has not yet issued the last gather (e.g. the
+ * host ring is full and the consumer is behind: the paper's back-pressure).
+ */
+int ds_event_wait_on_stream(ds_event *ev, void *stream);
+
+/* Host-side form of the gate: returns when every source byte has been read. */
+int ds_event_wait_captured(ds_event *ev);
+
+/* DS_OK when the whole image has reached the host ring, else DS_NOT_READY. */
+int ds_event_query(ds_event *ev);
+
+/* Blocks the host until the whole image has reached the host ring (with a
+ * consumer: until the last chunk's copy is done, which needs ring slots). */
+int ds_event_wait(ds_event *ev);
+
+/*
+ * Consumer side (Sec. V-A3: "the next chunk in the stream: how many bytes from
+ * where"): blocks until the next chunk of the image is resident in the ring,
+ * then returns its host address, its offset in the file and its length.
+ * Chunks come in file order.  DS_EOF after the last.  The memory stays valid
+ * until ds_snapshot_release_chunk.  Not used with DS_ENGINE_AUTO_RELEASE.
+ */
+int ds_snapshot_next_chunk(ds_event *ev, const void **host_ptr, uint64_t *file_off, uint64_t *len);
+
+/* Gives the ring slot back (Sec. V-A2: eviction after flush lets the next
+ * request proceed).  Errors: DS_ESTATE if host_ptr is not a chunk handed out. */
+int ds_snapshot_release_chunk(ds_event *ev, const void *host_ptr);
+
+typedef struct ds_snapshot_stats {
+  uint64_t image_bytes;
+  uint64_t payload_bytes;
+  uint32_t n_pack_launches;
+  uint32_t n_copies;
+  double pack_ms;       /* sum of gather kernel durations (HIP events on the gather stream)   */
+  double copy_ms;       /* sum of device-to-host copy durations (HIP events on the copy stream) */
+  double capture_ms;    /* request -> last source byte read                                   */
+  double total_ms;      /* request -> last byte in the host ring                              */
+  double submit_host_ms;/* host time spent inside ds_snapshot_async                           */
+} ds_snapshot_stats;
+
+/* Valid after ds_event_wait returned DS_OK. */
+int ds_event_stats(ds_event *ev, ds_snapshot_stats *out);
+
+/* Waits for the snapshot, releases chunks still held, frees the event. */
+int ds_event_destroy(ds_event *ev);
+
+/* ---- misc ---------------------------------------------------------------- */
+
+const char *ds_strerror(int code);
+
+/* hipError_t of the HIP call that last produced DS_EHIP on this thread. */
+int ds_last_hip_error(void);
+
+/*
+ * Tunables for experiments, read when a plan is created / a kernel launched:
+ *   "chunk_bytes"   image bytes per work-group chunk (power of two, 4 KiB..4 MiB)
+ *   "variant"       gather/scatter kernel variant (see ds_kernels.hip)
+ * Returns DS_EINVAL for an unknown key or a value out of range.
+ */
+int ds_config_set(const char *key, uint64_t value);
+int ds_config_get(const char *key, uint64_t *value);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DATASTATES_H */

@@ -1,0 +1,274 @@
+"""Thin Python binding of libdatastates_hip.so (argument marshalling only).
+
+Every function has the name of the C entry point it calls (include/datastates.h)
+and does nothing but convert arguments, call it, and turn a negative return
+code into `DsError`.  All of the method runs in the HIP library; if the library
+has not been built the import fails loudly -- there is no fallback.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import List, Optional, Sequence, Tuple
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libdatastates_hip.so")
+
+DS_MAX_DIMS = 6
+DS_F32, DS_BF16, DS_F16, DS_I64, DS_U8 = 0, 1, 2, 3, 4
+DS_OK, DS_NOT_READY, DS_EOF = 0, 1, 2
+DS_EINVAL, DS_EALIGN, DS_EOVERLAP, DS_EGAP, DS_ERANGE, DS_ENOMEM, DS_EHIP, DS_EBUSY, DS_ESTATE = (
+    -1, -2, -3, -4, -5, -6, -7, -8, -9)
+DS_PLAN_STRICT, DS_PLAN_HOST_ONLY = 1, 2
+DS_ENGINE_AUTO_RELEASE = 1
+
+# every symbol include/datastates.h declares
+EXPORTS = [
+    "ds_itemsize", "ds_layout_assign", "ds_plan_create", "ds_plan_destroy", "ds_plan_info", "ds_plan_shard",
+    "ds_pack", "ds_unpack", "ds_engine_create", "ds_engine_destroy", "ds_snapshot_async",
+    "ds_event_wait_on_stream", "ds_event_wait_captured", "ds_event_query", "ds_event_wait",
+    "ds_snapshot_next_chunk", "ds_snapshot_release_chunk", "ds_event_stats", "ds_event_destroy",
+    "ds_strerror", "ds_last_hip_error", "ds_config_set", "ds_config_get",
+]
+
+
+class ds_shard_desc(ctypes.Structure):
+    _fields_ = [
+        ("base", ctypes.c_void_p),
+        ("dtype", ctypes.c_uint32),
+        ("ndim", ctypes.c_uint32),
+        ("shape", ctypes.c_int64 * DS_MAX_DIMS),
+        ("strides", ctypes.c_int64 * DS_MAX_DIMS),
+        ("tensor_id", ctypes.c_uint64),
+        ("file_offset", ctypes.c_uint64),
+    ]
+
+
+class ds_plan_stats(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_uint64) for n in (
+        "total_bytes", "payload_bytes", "n_shards", "n_tiles", "n_chunks", "chunk_bytes", "n_strided", "align")]
+
+
+class ds_engine_opts(ctypes.Structure):
+    _fields_ = [
+        ("host_ring_bytes", ctypes.c_uint64),
+        ("d2h_chunk_bytes", ctypes.c_uint64),
+        ("stage_slot_bytes", ctypes.c_uint64),
+        ("stage_slots", ctypes.c_uint32),
+        ("pack_grid_limit", ctypes.c_uint32),
+        ("flags", ctypes.c_uint32),
+        ("copy_streams", ctypes.c_uint32),
+    ]
+
+
+class ds_snapshot_stats(ctypes.Structure):
+    _fields_ = [
+        ("image_bytes", ctypes.c_uint64),
+        ("payload_bytes", ctypes.c_uint64),
+        ("n_pack_launches", ctypes.c_uint32),
+        ("n_copies", ctypes.c_uint32),
+        ("pack_ms", ctypes.c_double),
+        ("copy_ms", ctypes.c_double),
+        ("capture_ms", ctypes.c_double),
+        ("total_ms", ctypes.c_double),
+        ("submit_host_ms", ctypes.c_double),
+    ]
+
+
+class DsError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        msg = _lib.ds_strerror(code).decode()
+        if code == DS_EHIP:
+            msg += f" [hipError {_lib.ds_last_hip_error()}]"
+        super().__init__(f"{where}: {msg} ({code})")
+
+
+def _load() -> ctypes.CDLL:
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(
+            f"{LIB_PATH} is missing: build it first (python -m paper_2601_16956_amd.build, or "
+            "__graft_entry__.build()).  There is no CPU fallback.")
+    L = ctypes.CDLL(LIB_PATH)
+    vp, u64, u32, sz = ctypes.c_void_p, ctypes.c_uint64, ctypes.c_uint32, ctypes.c_size_t
+    P = ctypes.POINTER
+    sig = {
+        "ds_itemsize": ([u32], ctypes.c_int),
+        "ds_layout_assign": ([P(ds_shard_desc), sz, u64, P(u64)], ctypes.c_int),
+        "ds_plan_create": ([P(ds_shard_desc), sz, u64, u32, P(vp)], ctypes.c_int),
+        "ds_plan_destroy": ([vp], ctypes.c_int),
+        "ds_plan_info": ([vp, P(ds_plan_stats)], ctypes.c_int),
+        "ds_plan_shard": ([vp, sz, P(u64), P(u32), P(u64), P(u64)], ctypes.c_int),
+        "ds_pack": ([vp, vp, u64, u64, vp], ctypes.c_int),
+        "ds_unpack": ([vp, vp, u64, u64, vp], ctypes.c_int),
+        "ds_engine_create": ([P(ds_engine_opts), P(vp)], ctypes.c_int),
+        "ds_engine_destroy": ([vp], ctypes.c_int),
+        "ds_snapshot_async": ([vp, vp, vp, P(vp)], ctypes.c_int),
+        "ds_event_wait_on_stream": ([vp, vp], ctypes.c_int),
+        "ds_event_wait_captured": ([vp], ctypes.c_int),
+        "ds_event_query": ([vp], ctypes.c_int),
+        "ds_event_wait": ([vp], ctypes.c_int),
+        "ds_snapshot_next_chunk": ([vp, P(vp), P(u64), P(u64)], ctypes.c_int),
+        "ds_snapshot_release_chunk": ([vp, vp], ctypes.c_int),
+        "ds_event_stats": ([vp, P(ds_snapshot_stats)], ctypes.c_int),
+        "ds_event_destroy": ([vp], ctypes.c_int),
+        "ds_strerror": ([ctypes.c_int], ctypes.c_char_p),
+        "ds_last_hip_error": ([], ctypes.c_int),
+        "ds_config_set": ([ctypes.c_char_p, u64], ctypes.c_int),
+        "ds_config_get": ([ctypes.c_char_p, P(u64)], ctypes.c_int),
+    }
+    for name, (args, res) in sig.items():
+        fn = getattr(L, name)
+        fn.argtypes = args
+        fn.restype = res
+    return L
+
+
+_lib = _load()
+
+
+def _check(rc: int, where: str) -> int:
+    if rc < 0:
+        raise DsError(rc, where)
+    return rc
+
+
+# ---- descriptor tables ------------------------------------------------------
+
+def make_descs(shards: Sequence, base_address: int):
+    """ctypes table from entries with .dtype (name or code) .shape .strides
+    .byte_offset .tensor_id; `base_address` is the device address the byte
+    offsets are relative to.  file_offset is left 0."""
+    codes = {"f32": DS_F32, "bf16": DS_BF16, "f16": DS_F16, "i64": DS_I64, "u8": DS_U8}
+    arr = (ds_shard_desc * max(len(shards), 1))()
+    for i, s in enumerate(shards):
+        d = arr[i]
+        d.base = base_address + s.byte_offset
+        d.dtype = codes[s.dtype] if isinstance(s.dtype, str) else int(s.dtype)
+        d.ndim = len(s.shape)
+        for j, (e, st) in enumerate(zip(s.shape, s.strides)):
+            d.shape[j] = e
+            d.strides[j] = st
+        d.tensor_id = s.tensor_id
+        d.file_offset = 0
+    return arr
+
+
+# ---- the entry points, same names as the C ABI -------------------------------
+
+def ds_itemsize(dtype: int) -> int:
+    return int(_lib.ds_itemsize(dtype))
+
+
+def ds_layout_assign(descs, n: int, align: int) -> int:
+    total = ctypes.c_uint64(0)
+    _check(_lib.ds_layout_assign(descs, n, align, ctypes.byref(total)), "ds_layout_assign")
+    return int(total.value)
+
+
+def ds_plan_create(descs, n: int, align: int, flags: int = 0) -> int:
+    out = ctypes.c_void_p(0)
+    _check(_lib.ds_plan_create(descs, n, align, flags, ctypes.byref(out)), "ds_plan_create")
+    return int(out.value)
+
+
+def ds_plan_destroy(plan: int) -> None:
+    _check(_lib.ds_plan_destroy(plan), "ds_plan_destroy")
+
+
+def ds_plan_info(plan: int) -> dict:
+    st = ds_plan_stats()
+    _check(_lib.ds_plan_info(plan, ctypes.byref(st)), "ds_plan_info")
+    return {n: int(getattr(st, n)) for n, _ in ds_plan_stats._fields_}
+
+
+def ds_plan_shard(plan: int, i: int) -> Tuple[int, int, int, int]:
+    tid, dt, off, nb = ctypes.c_uint64(), ctypes.c_uint32(), ctypes.c_uint64(), ctypes.c_uint64()
+    _check(_lib.ds_plan_shard(plan, i, ctypes.byref(tid), ctypes.byref(dt), ctypes.byref(off), ctypes.byref(nb)),
+           "ds_plan_shard")
+    return int(tid.value), int(dt.value), int(off.value), int(nb.value)
+
+
+def ds_pack(plan: int, dst_dev: int, img_lo: int, img_hi: int, stream: int = 0) -> None:
+    _check(_lib.ds_pack(plan, dst_dev, img_lo, img_hi, stream), "ds_pack")
+
+
+def ds_unpack(plan: int, src_dev: int, img_lo: int, img_hi: int, stream: int = 0) -> None:
+    _check(_lib.ds_unpack(plan, src_dev, img_lo, img_hi, stream), "ds_unpack")
+
+
+def ds_engine_create(host_ring_bytes: int = 0, d2h_chunk_bytes: int = 0, stage_slot_bytes: int = 0,
+                     stage_slots: int = 0, pack_grid_limit: int = 0, flags: int = 0, copy_streams: int = 0) -> int:
+    opts = ds_engine_opts(host_ring_bytes, d2h_chunk_bytes, stage_slot_bytes, stage_slots, pack_grid_limit, flags,
+                          copy_streams)
+    out = ctypes.c_void_p(0)
+    _check(_lib.ds_engine_create(ctypes.byref(opts), ctypes.byref(out)), "ds_engine_create")
+    return int(out.value)
+
+
+def ds_engine_destroy(engine: int) -> None:
+    _check(_lib.ds_engine_destroy(engine), "ds_engine_destroy")
+
+
+def ds_snapshot_async(engine: int, plan: int, compute_stream: int = 0) -> int:
+    out = ctypes.c_void_p(0)
+    _check(_lib.ds_snapshot_async(engine, plan, compute_stream, ctypes.byref(out)), "ds_snapshot_async")
+    return int(out.value)
+
+
+def ds_event_wait_on_stream(ev: int, stream: int = 0) -> None:
+    _check(_lib.ds_event_wait_on_stream(ev, stream), "ds_event_wait_on_stream")
+
+
+def ds_event_wait_captured(ev: int) -> None:
+    _check(_lib.ds_event_wait_captured(ev), "ds_event_wait_captured")
+
+
+def ds_event_query(ev: int) -> int:
+    return _check(_lib.ds_event_query(ev), "ds_event_query")
+
+
+def ds_event_wait(ev: int) -> None:
+    _check(_lib.ds_event_wait(ev), "ds_event_wait")
+
+
+def ds_snapshot_next_chunk(ev: int) -> Optional[Tuple[int, int, int]]:
+    """(host address, file offset, length) of the next chunk, or None at the end."""
+    ptr, off, ln = ctypes.c_void_p(0), ctypes.c_uint64(0), ctypes.c_uint64(0)
+    rc = _check(_lib.ds_snapshot_next_chunk(ev, ctypes.byref(ptr), ctypes.byref(off), ctypes.byref(ln)),
+                "ds_snapshot_next_chunk")
+    if rc == DS_EOF:
+        return None
+    return int(ptr.value), int(off.value), int(ln.value)
+
+
+def ds_snapshot_release_chunk(ev: int, host_ptr: int) -> None:
+    _check(_lib.ds_snapshot_release_chunk(ev, host_ptr), "ds_snapshot_release_chunk")
+
+
+def ds_event_stats(ev: int) -> dict:
+    st = ds_snapshot_stats()
+    _check(_lib.ds_event_stats(ev, ctypes.byref(st)), "ds_event_stats")
+    return {n: getattr(st, n) for n, _ in ds_snapshot_stats._fields_}
+
+
+def ds_event_destroy(ev: int) -> None:
+    _check(_lib.ds_event_destroy(ev), "ds_event_destroy")
+
+
+def ds_strerror(code: int) -> str:
+    return _lib.ds_strerror(code).decode()
+
+
+def ds_last_hip_error() -> int:
+    return int(_lib.ds_last_hip_error())
+
+
+def ds_config_set(key: str, value: int) -> None:
+    _check(_lib.ds_config_set(key.encode(), value), f"ds_config_set({key})")
+
+
+def ds_config_get(key: str) -> int:
+    v = ctypes.c_uint64(0)
+    _check(_lib.ds_config_get(key.encode(), ctypes.byref(v)), f"ds_config_get({key})")
+    return int(v.value)

@@ -1,0 +1,503 @@
+// The snapshot engine: lazy, non-blocking capture of one GPU's shards into a
+// pre-pinned host ring (DataStates-LLM Sec. V-A1, V-A2, V-A4; implementation
+// notes of Sec. V-C: pinned circular buffer, dedicated streams, background
+// host thread).
+//
+// Data path of one snapshot, image bytes [0, T):
+//
+//   compute stream --E_requested--> gather stream: one gather launch per staging
+//   slot (the first launch covers just the first copy chunk so that the link
+//   starts working at once)  --E_packed--> copy stream(s): one hipMemcpyAsync per
+//   ring slot, device staging -> pinned ring  --E_done[slot]--> consumer.
+//
+// The caller's stream is touched twice only: the record at the request and the
+// wait at the gate.  The gate waits for the LAST GATHER, not for the last
+// copy: once every source byte sits in staging the tensors may be mutated.
+// MI355X has HBM to spare (288 GB), so staging as large as the image is an
+// ordinary setting and the update phase is then delayed by the gather time
+// only (a fraction of a millisecond per GB), not by the link.
+#include <chrono>
+#include <condition_variable>
+#include <deque>
+#include <mutex>
+#include <new>
+#include <thread>
+
+#include "ds_internal.h"
+
+namespace {
+constexpr int kMaxCopyStreams = 2;
+}
+
+struct ds_event;
+
+struct ds_engine {
+  int device = 0;
+  uint32_t flags = 0;
+  uint32_t grid_limit = 0;
+  uint64_t chunk_bytes = 0;       // ring slot = one copy
+  uint64_t stage_slot_bytes = 0;  // image bytes per gather launch
+  uint32_t stage_slots = 0;
+  uint32_t ring_slots = 0;
+  int n_copy_streams = 1;
+  hipStream_t pack_stream = nullptr;
+  hipStream_t copy_stream[kMaxCopyStreams] = {nullptr, nullptr};
+  uint8_t *stage = nullptr;  // device
+  uint8_t *ring = nullptr;   // pinned host
+  // engine-owned events, reused by every snapshot
+  std::vector<hipEvent_t> ring_done;                    // copy into ring slot r finished
+  std::vector<hipEvent_t> stage_free[kMaxCopyStreams];  // copies out of staging slot s finished (per copy stream)
+  std::vector<bool> stage_used;
+  std::vector<uint8_t> ring_busy;  // consumer mode: slot holds data not yet released
+  uint32_t ring_next = 0;
+  uint64_t copies_issued = 0;
+
+  std::mutex mu;
+  std::condition_variable cv;
+  std::deque<ds_event *> queue;
+  bool stop = false;
+  int live_events = 0;
+  std::thread worker;
+};
+
+struct DsChunk {
+  uint64_t file_off = 0, len = 0;
+  uint32_t ring_slot = 0;
+  int state = 0;  // 0 not issued, 1 copy issued, 2 handed to the consumer, 3 released
+};
+
+struct ds_event {
+  ds_engine *eng = nullptr;
+  const ds_plan *plan = nullptr;
+  hipEvent_t requested = nullptr, captured = nullptr, final_ev = nullptr, copy_begin = nullptr;
+  std::vector<hipEvent_t> pack_begin, pack_end;
+  std::vector<DsChunk> chunks;
+  uint32_t cursor = 0;  // next chunk the consumer gets
+  bool all_issued = false;
+  int error = DS_OK;
+  double submit_host_ms = 0;
+};
+
+namespace {
+
+int hip_fail(hipError_t e) {
+  ds_set_hip_error(e);
+  return DS_EHIP;
+}
+
+#define W_TRY(expr)                          \
+  do {                                       \
+    hipError_t _e = (expr);                  \
+    if (_e != hipSuccess) return hip_fail(_e); \
+  } while (0)
+
+// Issues every launch and copy of one snapshot.  Runs on the engine's thread.
+int issue_snapshot(ds_engine *g, ds_event *ev) {
+  const ds_plan *plan = ev->plan;
+  const uint64_t T = plan->total_bytes;
+  W_TRY(hipStreamWaitEvent(g->pack_stream, ev->requested, 0));
+  W_TRY(hipEventCreate(&ev->captured));
+  W_TRY(hipEventCreate(&ev->final_ev));
+  W_TRY(hipEventCreate(&ev->copy_begin));
+  uint64_t at = 0;
+  uint32_t group = 0, k = 0;
+  while (at < T) {
+    // the first launch is one copy chunk long, the others fill a staging slot
+    const uint64_t want = group == 0 ? g->chunk_bytes : g->stage_slot_bytes;
+    const uint64_t hi = at + want < T ? at + want : T;
+    const uint32_t s = group % g->stage_slots;
+    uint8_t *slot = g->stage + (uint64_t)s * g->stage_slot_bytes;
+    if (g->stage_used[s])
+      for (int c = 0; c < g->n_copy_streams; ++c) W_TRY(hipStreamWaitEvent(g->pack_stream, g->stage_free[c][s], 0));
+    hipEvent_t b, e;
+    W_TRY(hipEventCreate(&b));
+    ev->pack_begin.push_back(b);
+    W_TRY(hipEventCreate(&e));
+    ev->pack_end.push_back(e);
+    W_TRY(hipEventRecord(b, g->pack_stream));
+    int rc = ds_launch_move(plan, true, slot, at, hi, g->grid_limit, g->pack_stream);
+    if (rc != DS_OK) return rc;
+    W_TRY(hipEventRecord(e, g->pack_stream));
+    for (int c = 0; c < g->n_copy_streams; ++c) W_TRY(hipStreamWaitEvent(g->copy_stream[c], e, 0));
+    if (group == 0) W_TRY(hipEventRecord(ev->copy_begin, g->copy_stream[0]));
+    for (uint64_t lo = at; lo < hi; lo += g->chunk_bytes, ++k) {
+      const uint64_t len = lo + g->chunk_bytes < hi ? g->chunk_bytes : hi - lo;
+      uint32_t r;
+      {
+        std::unique_lock<std::mutex> lk(g->mu);
+        r = g->ring_next;
+        if (!(g->flags & DS_ENGINE_AUTO_RELEASE)) {
+          // back-pressure: the ring is full until the consumer releases a slot
+          g->cv.wait(lk, [&] { return !g->ring_busy[r]; });
+          g->ring_busy[r] = 1;
+        }
+        g->ring_next = (r + 1) % g->ring_slots;
+      }
+      const int c = (int)(g->copies_issued++ % (uint64_t)g->n_copy_streams);
+      hipStream_t cs = g->copy_stream[c];
+      // the slot's previous copy may have run on the other copy stream
+      if (g->n_copy_streams > 1) W_TRY(hipStreamWaitEvent(cs, g->ring_done[r], 0));
+      W_TRY(hipMemcpyAsync(g->ring + (uint64_t)r * g->chunk_bytes, slot + (lo - at), len, hipMemcpyDeviceToHost, cs));
+      W_TRY(hipEventRecord(g->ring_done[r], cs));
+      {
+        std::lock_guard<std::mutex> lk(g->mu);
+        ev->chunks[k].ring_slot = r;
+        ev->chunks[k].state = 1;
+      }
+      g->cv.notify_all();
+    }
+    for (int c = 0; c < g->n_copy_streams; ++c) W_TRY(hipEventRecord(g->stage_free[c][s], g->copy_stream[c]));
+    g->stage_used[s] = true;
+    at = hi;
+    ++group;
+  }
+  W_TRY(hipEventRecord(ev->captured, g->pack_stream));
+  W_TRY(hipStreamWaitEvent(g->copy_stream[0], ev->captured, 0));
+  if (g->n_copy_streams > 1 && !ev->chunks.empty()) {
+    hipEvent_t tail;
+    W_TRY(hipEventCreate(&tail));
+    ev->pack_begin.push_back(tail);  // kept only so that it is destroyed with the event
+    ev->pack_end.push_back(nullptr);
+    W_TRY(hipEventRecord(tail, g->copy_stream[1]));
+    W_TRY(hipStreamWaitEvent(g->copy_stream[0], tail, 0));
+  }
+  if (T == 0) W_TRY(hipEventRecord(ev->copy_begin, g->copy_stream[0]));
+  W_TRY(hipEventRecord(ev->final_ev, g->copy_stream[0]));
+  return DS_OK;
+}
+
+void worker_main(ds_engine *g) {
+  (void)hipSetDevice(g->device);
+  for (;;) {
+    ds_event *ev = nullptr;
+    {
+      std::unique_lock<std::mutex> lk(g->mu);
+      g->cv.wait(lk, [&] { return g->stop || !g->queue.empty(); });
+      if (g->queue.empty()) return;  // stop requested and nothing left
+      ev = g->queue.front();
+      g->queue.pop_front();
+    }
+    int rc = issue_snapshot(g, ev);
+    {
+      std::lock_guard<std::mutex> lk(g->mu);
+      ev->error = rc;
+      ev->all_issued = true;
+    }
+    g->cv.notify_all();
+  }
+}
+
+// waits until the engine thread has issued everything of this snapshot
+int wait_issued(ds_event *ev) {
+  ds_engine *g = ev->eng;
+  std::unique_lock<std::mutex> lk(g->mu);
+  g->cv.wait(lk, [&] { return ev->all_issued; });
+  return ev->error;
+}
+
+void destroy_events(std::vector<hipEvent_t> &v) {
+  for (hipEvent_t e : v)
+    if (e) (void)hipEventDestroy(e);
+  v.clear();
+}
+
+void free_engine(ds_engine *g) {
+  for (int c = 0; c < kMaxCopyStreams; ++c) {
+    destroy_events(g->stage_free[c]);
+    if (g->copy_stream[c]) (void)hipStreamDestroy(g->copy_stream[c]);
+  }
+  destroy_events(g->ring_done);
+  if (g->pack_stream) (void)hipStreamDestroy(g->pack_stream);
+  if (g->stage) (void)hipFree(g->stage);
+  if (g->ring) (void)hipHostFree(g->ring);
+  delete g;
+}
+
+}  // namespace
+
+extern "C" {
+
+int ds_engine_create(const ds_engine_opts *o, ds_engine **out) {
+  if (!o || !out) return DS_EINVAL;
+  if (o->flags & ~DS_ENGINE_AUTO_RELEASE) return DS_EINVAL;
+  const uint64_t chunk = o->d2h_chunk_bytes ? o->d2h_chunk_bytes : (32ull << 20);
+  const uint64_t ring_bytes = o->host_ring_bytes ? o->host_ring_bytes : (2ull << 30);
+  const uint64_t slot = o->stage_slot_bytes ? o->stage_slot_bytes : (1ull << 30);
+  const uint32_t slots = o->stage_slots ? o->stage_slots : 2;
+  const uint32_t ncs = o->copy_streams ? o->copy_streams : 1;
+  if ((chunk & 4095) || slot % chunk || ring_bytes < chunk || ncs > (uint32_t)kMaxCopyStreams || slots > 1024)
+    return DS_EINVAL;
+  ds_engine *g = new (std::nothrow) ds_engine;
+  if (!g) return DS_ENOMEM;
+  g->flags = o->flags;
+  g->grid_limit = o->pack_grid_limit;
+  g->chunk_bytes = chunk;
+  g->stage_slot_bytes = slot;
+  g->stage_slots = slots;
+  g->ring_slots = (uint32_t)(ring_bytes / chunk);
+  g->n_copy_streams = (int)ncs;
+  hipError_t e = hipGetDevice(&g->device);
+  if (e == hipSuccess) e = hipStreamCreateWithFlags(&g->pack_stream, hipStreamNonBlocking);
+  for (int c = 0; c < g->n_copy_streams && e == hipSuccess; ++c)
+    e = hipStreamCreateWithFlags(&g->copy_stream[c], hipStreamNonBlocking);
+  if (e == hipSuccess) {
+    e = hipMalloc((void **)&g->stage, slot * slots);
+    if (e == hipErrorOutOfMemory) { free_engine(g); return DS_ENOMEM; }
+  }
+  if (e == hipSuccess) {
+    // allocated and pinned once, reused by every snapshot (Sec. V-A1)
+    e = hipHostMalloc((void **)&g->ring, (uint64_t)g->ring_slots * chunk, hipHostMallocDefault);
+    if (e == hipErrorOutOfMemory) { free_engine(g); return DS_ENOMEM; }
+  }
+  try {
+    g->ring_done.assign(g->ring_slots, nullptr);
+    g->ring_busy.assign(g->ring_slots, 0);
+    g->stage_used.assign(slots, false);
+    for (int c = 0; c < g->n_copy_streams; ++c) g->stage_free[c].assign(slots, nullptr);
+  } catch (const std::bad_alloc &) {
+    free_engine(g);
+    return DS_ENOMEM;
+  }
+  for (uint32_t r = 0; r < g->ring_slots && e == hipSuccess; ++r) {
+    e = hipEventCreate(&g->ring_done[r]);
+    // recorded once so that a wait on a never-used slot is a no-op by construction
+    if (e == hipSuccess) e = hipEventRecord(g->ring_done[r], g->copy_stream[0]);
+  }
+  for (int c = 0; c < g->n_copy_streams; ++c)
+    for (uint32_t s = 0; s < slots && e == hipSuccess; ++s) e = hipEventCreate(&g->stage_free[c][s]);
+  if (e != hipSuccess) {
+    ds_set_hip_error(e);
+    free_engine(g);
+    return DS_EHIP;
+  }
+  try {
+    g->worker = std::thread(worker_main, g);
+  } catch (...) {
+    free_engine(g);
+    return DS_ENOMEM;
+  }
+  *out = g;
+  return DS_OK;
+}
+
+int ds_engine_destroy(ds_engine *g) {
+  if (!g) return DS_EINVAL;
+  {
+    std::lock_guard<std::mutex> lk(g->mu);
+    if (g->live_events > 0) return DS_EBUSY;
+    g->stop = true;
+  }
+  g->cv.notify_all();
+  if (g->worker.joinable()) g->worker.join();
+  int rc = DS_OK;
+  hipError_t e = hipStreamSynchronize(g->pack_stream);
+  for (int c = 0; c < g->n_copy_streams && e == hipSuccess; ++c) e = hipStreamSynchronize(g->copy_stream[c]);
+  if (e != hipSuccess) rc = hip_fail(e);
+  free_engine(g);
+  return rc;
+}
+
+int ds_snapshot_async(ds_engine *g, const ds_plan *plan, void *compute_stream, ds_event **out) {
+  if (!g || !plan || !out || !plan->dev_blob) return DS_EINVAL;
+  const auto t0 = std::chrono::steady_clock::now();
+  ds_event *ev = new (std::nothrow) ds_event;
+  if (!ev) return DS_ENOMEM;
+  ev->eng = g;
+  ev->plan = plan;
+  try {
+    const uint64_t T = plan->total_bytes;
+    const uint64_t n = (T + g->chunk_bytes - 1) / g->chunk_bytes;
+    ev->chunks.resize(n);
+    // chunk boundaries restart at every staging group, so walk the groups
+    uint64_t at = 0, k = 0;
+    uint32_t group = 0;
+    while (at < T) {
+      const uint64_t want = group == 0 ? g->chunk_bytes : g->stage_slot_bytes;
+      const uint64_t hi = at + want < T ? at + want : T;
+      for (uint64_t lo = at; lo < hi; lo += g->chunk_bytes, ++k) {
+        ev->chunks[k].file_off = lo;
+        ev->chunks[k].len = lo + g->chunk_bytes < hi ? g->chunk_bytes : hi - lo;
+      }
+      at = hi;
+      ++group;
+    }
+    ev->chunks.resize(k);
+  } catch (const std::bad_alloc &) {
+    delete ev;
+    return DS_ENOMEM;
+  }
+  hipError_t e = hipEventCreate(&ev->requested);
+  // the point of consistency: everything enqueued so far on the caller's stream
+  if (e == hipSuccess) e = hipEventRecord(ev->requested, (hipStream_t)compute_stream);
+  if (e != hipSuccess) {
+    if (ev->requested) (void)hipEventDestroy(ev->requested);
+    delete ev;
+    return hip_fail(e);
+  }
+  {
+    std::lock_guard<std::mutex> lk(g->mu);
+    g->queue.push_back(ev);
+    ++g->live_events;
+  }
+  g->cv.notify_all();
+  ev->submit_host_ms = std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - t0).count();
+  *out = ev;
+  return DS_OK;
+}
+
+int ds_event_wait_on_stream(ds_event *ev, void *stream) {
+  if (!ev) return DS_EINVAL;
+  int rc = wait_issued(ev);
+  if (rc != DS_OK) return rc;
+  DS_HIP_TRY(hipStreamWaitEvent((hipStream_t)stream, ev->captured, 0));
+  return DS_OK;
+}
+
+int ds_event_wait_captured(ds_event *ev) {
+  if (!ev) return DS_EINVAL;
+  int rc = wait_issued(ev);
+  if (rc != DS_OK) return rc;
+  DS_HIP_TRY(hipEventSynchronize(ev->captured));
+  return DS_OK;
+}
+
+int ds_event_query(ds_event *ev) {
+  if (!ev) return DS_EINVAL;
+  {
+    std::lock_guard<std::mutex> lk(ev->eng->mu);
+    if (!ev->all_issued) return DS_NOT_READY;
+    if (ev->error != DS_OK) return ev->error;
+  }
+  hipError_t e = hipEventQuery(ev->final_ev);
+  if (e == hipSuccess) return DS_OK;
+  if (e == hipErrorNotReady) return DS_NOT_READY;
+  return hip_fail(e);
+}
+
+int ds_event_wait(ds_event *ev) {
+  if (!ev) return DS_EINVAL;
+  int rc = wait_issued(ev);
+  if (rc != DS_OK) return rc;
+  DS_HIP_TRY(hipEventSynchronize(ev->final_ev));
+  return DS_OK;
+}
+
+int ds_snapshot_next_chunk(ds_event *ev, const void **host_ptr, uint64_t *file_off, uint64_t *len) {
+  if (!ev || !host_ptr || !file_off || !len) return DS_EINVAL;
+  ds_engine *g = ev->eng;
+  if (g->flags & DS_ENGINE_AUTO_RELEASE) return DS_ESTATE;
+  uint32_t k, r;
+  {
+    std::unique_lock<std::mutex> lk(g->mu);
+    if (ev->cursor >= ev->chunks.size()) return DS_EOF;
+    k = ev->cursor;
+    g->cv.wait(lk, [&] { return ev->chunks[k].state >= 1 || (ev->all_issued && ev->error != DS_OK); });
+    if (ev->chunks[k].state < 1) return ev->error;
+    r = ev->chunks[k].ring_slot;
+  }
+  DS_HIP_TRY(hipEventSynchronize(g->ring_done[r]));
+  {
+    std::lock_guard<std::mutex> lk(g->mu);
+    ev->chunks[k].state = 2;
+    ev->cursor = k + 1;
+  }
+  *host_ptr = g->ring + (uint64_t)r * g->chunk_bytes;
+  *file_off = ev->chunks[k].file_off;
+  *len = ev->chunks[k].len;
+  return DS_OK;
+}
+
+int ds_snapshot_release_chunk(ds_event *ev, const void *host_ptr) {
+  if (!ev || !host_ptr) return DS_EINVAL;
+  ds_engine *g = ev->eng;
+  const uint8_t *p = (const uint8_t *)host_ptr;
+  if (p < g->ring || p >= g->ring + (uint64_t)g->ring_slots * g->chunk_bytes || (uint64_t)(p - g->ring) % g->chunk_bytes)
+    return DS_ESTATE;
+  const uint32_t r = (uint32_t)((uint64_t)(p - g->ring) / g->chunk_bytes);
+  {
+    std::lock_guard<std::mutex> lk(g->mu);
+    DsChunk *hit = nullptr;
+    for (uint32_t k = 0; k < ev->cursor && !hit; ++k)
+      if (ev->chunks[k].state == 2 && ev->chunks[k].ring_slot == r) hit = &ev->chunks[k];
+    if (!hit) return DS_ESTATE;
+    hit->state = 3;
+    g->ring_busy[r] = 0;
+  }
+  g->cv.notify_all();
+  return DS_OK;
+}
+
+int ds_event_stats(ds_event *ev, ds_snapshot_stats *out) {
+  if (!ev || !out) return DS_EINVAL;
+  int rc = ds_event_query(ev);
+  if (rc == DS_NOT_READY) return DS_EBUSY;
+  if (rc != DS_OK) return rc;
+  out->image_bytes = ev->plan->total_bytes;
+  out->payload_bytes = ev->plan->payload_bytes;
+  out->n_copies = (uint32_t)ev->chunks.size();
+  out->n_pack_launches = 0;
+  out->pack_ms = 0;
+  for (size_t i = 0; i < ev->pack_begin.size(); ++i) {
+    if (!ev->pack_end[i]) continue;
+    float ms = 0;
+    DS_HIP_TRY(hipEventElapsedTime(&ms, ev->pack_begin[i], ev->pack_end[i]));
+    out->pack_ms += ms;
+    ++out->n_pack_launches;
+  }
+  float ms = 0;
+  DS_HIP_TRY(hipEventElapsedTime(&ms, ev->copy_begin, ev->final_ev));
+  out->copy_ms = ms;
+  DS_HIP_TRY(hipEventElapsedTime(&ms, ev->requested, ev->captured));
+  out->capture_ms = ms;
+  DS_HIP_TRY(hipEventElapsedTime(&ms, ev->requested, ev->final_ev));
+  out->total_ms = ms;
+  out->submit_host_ms = ev->submit_host_ms;
+  return DS_OK;
+}
+
+int ds_event_destroy(ds_event *ev) {
+  if (!ev) return DS_EINVAL;
+  ds_engine *g = ev->eng;
+  int rc = DS_OK;
+  if (!(g->flags & DS_ENGINE_AUTO_RELEASE)) {
+    // hand back what the consumer still holds, then drain what it never took
+    for (;;) {
+      const void *p = nullptr;
+      {
+        std::lock_guard<std::mutex> lk(g->mu);
+        for (uint32_t k = 0; k < ev->cursor && !p; ++k)
+          if (ev->chunks[k].state == 2) p = g->ring + (uint64_t)ev->chunks[k].ring_slot * g->chunk_bytes;
+      }
+      if (!p) break;
+      (void)ds_snapshot_release_chunk(ev, p);
+    }
+    for (;;) {
+      const void *p;
+      uint64_t off, len;
+      int r = ds_snapshot_next_chunk(ev, &p, &off, &len);
+      if (r != DS_OK) break;
+      (void)ds_snapshot_release_chunk(ev, p);
+    }
+  }
+  int w = wait_issued(ev);
+  if (w == DS_OK && ev->final_ev) {
+    hipError_t e = hipEventSynchronize(ev->final_ev);
+    if (e != hipSuccess) rc = hip_fail(e);
+  } else if (w != DS_OK) {
+    // issuing failed half-way: make sure nothing of it is still running
+    (void)hipStreamSynchronize(g->pack_stream);
+    for (int c = 0; c < g->n_copy_streams; ++c) (void)hipStreamSynchronize(g->copy_stream[c]);
+  }
+  destroy_events(ev->pack_begin);
+  destroy_events(ev->pack_end);
+  for (hipEvent_t e : {ev->requested, ev->captured, ev->final_ev, ev->copy_begin})
+    if (e) (void)hipEventDestroy(e);
+  {
+    std::lock_guard<std::mutex> lk(g->mu);
+    --g->live_events;
+  }
+  delete ev;
+  return rc;
+}
+
+}  // extern "C"

@@ -1,0 +1,73 @@
+// Internal definitions shared by the host side and the kernels of
+// libdatastates_hip.so.  Not part of the ABI.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <vector>
+
+#include "datastates.h"
+
+// A tile is one non-empty shard in device form: the view is normalised to
+// "outer index -> start of a contiguous run of run_bytes".  Its place in the
+// image is [tile_off[t], tile_off[t+1]): payload first, then padding.
+struct DsTile {
+  uint64_t src;        // device address of element (0,...,0)
+  uint64_t nbytes;     // payload bytes
+  uint64_t run_bytes;  // length of the innermost contiguous run; == nbytes when n_outer == 0
+  uint32_t n_outer;    // outer dimensions left after merging; 0 = the whole shard is one run
+  uint32_t es_log2;    // log2(itemsize)
+  uint64_t extent[DS_MAX_DIMS];  // outer extents, slowest first
+  uint64_t stride[DS_MAX_DIMS];  // outer strides in BYTES
+};
+static_assert(sizeof(DsTile) == 128, "DsTile is one 128-byte line");
+
+struct DsManifestEntry {
+  uint64_t tensor_id;
+  uint32_t dtype;
+  uint64_t file_offset;
+  uint64_t nbytes;
+};
+
+struct ds_plan {
+  uint64_t align = 0;
+  uint64_t total_bytes = 0;
+  uint64_t payload_bytes = 0;
+  uint64_t n_shards = 0;
+  uint64_t n_strided = 0;
+  uint32_t chunk_log2 = 0;
+  std::vector<DsManifestEntry> manifest;   // table order as given
+  std::vector<DsTile> tiles;               // image order
+  std::vector<uint64_t> tile_off;          // n_tiles + 1 entries, last = total_bytes
+  std::vector<uint32_t> first_tile;        // n_chunks + 1 entries, last = n_tiles
+  // device copies (one allocation)
+  int device = -1;
+  void *dev_blob = nullptr;
+  const DsTile *d_tiles = nullptr;
+  const uint64_t *d_tile_off = nullptr;
+  const uint32_t *d_first_tile = nullptr;
+  uint64_t n_chunks() const { return first_tile.empty() ? 0 : first_tile.size() - 1; }
+};
+
+// ---- error plumbing ---------------------------------------------------------
+void ds_set_hip_error(hipError_t e);
+#define DS_HIP_TRY(expr)                 \
+  do {                                   \
+    hipError_t _e = (expr);              \
+    if (_e != hipSuccess) {              \
+      ds_set_hip_error(_e);              \
+      return DS_EHIP;                    \
+    }                                    \
+  } while (0)
+
+// ---- tunables ---------------------------------------------------------------
+uint64_t ds_cfg_chunk_bytes();
+uint64_t ds_cfg_variant();
+
+// ---- kernel launchers (ds_kernels.hip) ---------------------------------------
+// Moves image bytes [img_lo, img_hi) between the tensors of `plan` and `img`
+// (which points at image byte img_lo).  pack: tensors -> img; else img -> tensors.
+// grid_limit 0 = one work-group per chunk.
+int ds_launch_move(const ds_plan *plan, bool pack, uint8_t *img, uint64_t img_lo, uint64_t img_hi,
+                   uint32_t grid_limit, hipStream_t stream);

@@ -1,0 +1,379 @@
+// Gather (pack) and scatter (unpack) kernels for gfx950.
+//
+// The image is cut into chunks of 2^chunk_log2 bytes; one work-group moves one
+// chunk (DataStates-LLM Sec. V-A1 coalesces the shards of a checkpoint into
+// one region; Sec. V-A4: a chunk need not be a whole tensor).  Work is laid
+// out in DESTINATION space: thread -> 16-byte unit of the image, so image
+// accesses are aligned, contiguous 16-byte vector accesses whatever the
+// shards look like, and every work-group moves the same number of bytes
+// however fragmented its part of the image is.
+//
+//   - A chunk that holds a few tiles (the usual case: tensors are much larger
+//     than a chunk) walks them one after the other with the whole work-group
+//     ("direct" path, unrolled so that several 16-byte loads are in flight per
+//     lane).
+//   - A chunk that holds many small tiles takes them 64 at a time: every lane
+//     reads one tile's extent, a wavefront inclusive scan over the unit counts
+//     turns the 64 tiles into one dense index space, and the threads of the
+//     work-group share that space evenly; a binary search over the scan (in
+//     LDS) maps a unit back to (tile, offset).  Tiles that are large anyway
+//     are taken out of the scan and go through the direct path.
+//
+// Tensor-side addresses are only element-aligned.  gfx950 runs with unaligned
+// global access enabled, so a 16-byte unit that lies inside one contiguous run
+// is one (possibly unaligned) dwordx4 access; a unit that is cut by the end of
+// a run or of the payload is moved element by element with exact bounds, so no
+// byte outside the described views is ever read or written.
+#include "ds_internal.h"
+
+namespace {
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef u32x4 u32x4_unaligned __attribute__((aligned(1)));
+
+constexpr int kWave = 64;
+constexpr uint32_t kDirectMaxTiles = 4;   // chunks with at most this many tiles skip the scan
+constexpr uint32_t kBigUnits = 512;       // tiles of >= 8 KiB inside a chunk leave the scan
+
+struct MoveArgs {
+  const DsTile *tiles;
+  const uint64_t *tile_off;
+  const uint32_t *first_tile;
+  uint8_t *img;        // points at image byte img_lo
+  uint64_t img_lo, img_hi;
+  uint64_t total;      // image length
+  uint32_t chunk_log2;
+  uint32_t c_lo;       // first chunk of this launch
+  uint32_t n_chunks;   // chunks of this launch
+};
+
+// ---- 16-byte accesses -------------------------------------------------------
+template <bool NT>
+__device__ __forceinline__ u32x4 ld16_aligned(const uint8_t *p) {
+  if (NT) return __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p));
+  return *reinterpret_cast<const u32x4 *>(p);
+}
+template <bool NT>
+__device__ __forceinline__ void st16_aligned(uint8_t *p, u32x4 v) {
+  if (NT) __builtin_nontemporal_store(v, reinterpret_cast<u32x4 *>(p));
+  else *reinterpret_cast<u32x4 *>(p) = v;
+}
+template <bool NT>
+__device__ __forceinline__ u32x4 ld16_any(const uint8_t *p) {
+  if (NT) return __builtin_nontemporal_load(reinterpret_cast<const u32x4_unaligned *>(p));
+  return *reinterpret_cast<const u32x4_unaligned *>(p);
+}
+template <bool NT>
+__device__ __forceinline__ void st16_any(uint8_t *p, u32x4 v) {
+  if (NT) __builtin_nontemporal_store(v, reinterpret_cast<u32x4_unaligned *>(p));
+  else *reinterpret_cast<u32x4_unaligned *>(p) = v;
+}
+
+// ---- index arithmetic -------------------------------------------------------
+__device__ __forceinline__ void divmod(uint64_t a, uint64_t b, uint64_t &q, uint64_t &r) {
+  if (((a | b) >> 32) == 0) {
+    uint32_t qq = (uint32_t)a / (uint32_t)b;
+    q = qq;
+    r = (uint32_t)a - qq * (uint32_t)b;
+  } else {
+    q = a / b;
+    r = a - q * b;
+  }
+}
+
+// address of the first byte of run number `row` (runs counted in row-major
+// order of the outer dimensions)
+__device__ __forceinline__ uint64_t run_address(const DsTile *t, uint64_t row) {
+  const uint32_t m = t->n_outer;
+  if (m == 0) return t->src;
+  if (m == 1) return t->src + row * t->stride[0];
+  uint64_t a = t->src;
+  for (int j = (int)m - 1; j > 0; --j) {
+    uint64_t q, r;
+    divmod(row, t->extent[j], q, r);
+    a += r * t->stride[j];
+    row = q;
+  }
+  return a + row * t->stride[0];
+}
+
+// ---- element-wise move of (part of) one unit, exact bounds -------------------
+template <int ES> struct ElemType;
+template <> struct ElemType<1> { typedef uint8_t type; };
+template <> struct ElemType<2> { typedef uint16_t type; };
+template <> struct ElemType<4> { typedef uint32_t type; };
+template <> struct ElemType<8> { typedef uint64_t type; };
+
+union Unit {
+  u32x4 q;
+  uint8_t b[16];
+  uint16_t h[8];
+  uint32_t w[4];
+  uint64_t d[2];
+};
+
+template <int ES> __device__ __forceinline__ typename ElemType<ES>::type unit_get(const Unit &u, int e);
+template <> __device__ __forceinline__ uint8_t unit_get<1>(const Unit &u, int e) { return u.b[e]; }
+template <> __device__ __forceinline__ uint16_t unit_get<2>(const Unit &u, int e) { return u.h[e]; }
+template <> __device__ __forceinline__ uint32_t unit_get<4>(const Unit &u, int e) { return u.w[e]; }
+template <> __device__ __forceinline__ uint64_t unit_get<8>(const Unit &u, int e) { return u.d[e]; }
+template <int ES> __device__ __forceinline__ void unit_set(Unit &u, int e, typename ElemType<ES>::type x);
+template <> __device__ __forceinline__ void unit_set<1>(Unit &u, int e, uint8_t x) { u.b[e] = x; }
+template <> __device__ __forceinline__ void unit_set<2>(Unit &u, int e, uint16_t x) { u.h[e] = x; }
+template <> __device__ __forceinline__ void unit_set<4>(Unit &u, int e, uint32_t x) { u.w[e] = x; }
+template <> __device__ __forceinline__ void unit_set<8>(Unit &u, int e, uint64_t x) { u.d[e] = x; }
+
+// Moves the first `valid` bytes (a multiple of ES, <= 16) of a unit whose first
+// byte is byte `col` of run `row`.  PACK: tensor -> val (rest stays 0);
+// else val -> tensor.
+template <int ES, bool PACK>
+__device__ __forceinline__ void move_elements(const DsTile *t, uint64_t row, uint64_t col, uint32_t valid, Unit &val) {
+  typedef typename ElemType<ES>::type E;
+  const uint64_t L = t->run_bytes;
+  uint64_t ra = run_address(t, row);
+#pragma unroll
+  for (int e = 0; e < 16 / ES; ++e) {
+    if ((uint32_t)(e * ES) < valid) {
+      if (col >= L) {  // the run ended exactly here: go on in the next one
+        col = 0;
+        ++row;
+        ra = run_address(t, row);
+      }
+      E *p = reinterpret_cast<E *>(ra + col);
+      if (PACK) unit_set<ES>(val, e, *p);
+      else *p = unit_get<ES>(val, e);
+      col += ES;
+    }
+  }
+}
+
+// Kept out of line: it is the rare path, and inlining its four instantiations
+// at every call site multiplies code size and build time.
+// The unit travels by value (in registers), not through the stack.
+template <bool PACK>
+__device__ __noinline__ u32x4 move_elements_any(const DsTile *t, uint64_t row, uint64_t col, uint32_t valid, u32x4 in) {
+  Unit val;
+  val.q = in;
+  switch (t->es_log2) {
+    case 0: move_elements<1, PACK>(t, row, col, valid, val); break;
+    case 1: move_elements<2, PACK>(t, row, col, valid, val); break;
+    case 2: move_elements<4, PACK>(t, row, col, valid, val); break;
+    default: move_elements<8, PACK>(t, row, col, valid, val); break;
+  }
+  return val.q;
+}
+
+// ---- one unit, any tile, any position (the general routine) ------------------
+// x: image offset of the unit (multiple of 16) inside tile t's range; imgp: its
+// address in the image buffer.
+template <bool PACK, bool NTL, bool NTS>
+__device__ __forceinline__ void move_unit(const DsTile *t, uint64_t tile_begin, uint64_t x, uint8_t *imgp) {
+  const uint64_t nbytes = t->nbytes;
+  const uint64_t b = x - tile_begin;
+  if (b >= nbytes) {  // padding
+    if (PACK) st16_aligned<NTS>(imgp, u32x4{0, 0, 0, 0});
+    return;
+  }
+  const uint64_t left = nbytes - b;
+  const uint32_t valid = left < 16 ? (uint32_t)left : 16u;
+  const uint64_t L = t->run_bytes;
+  uint64_t row = 0, col = b;
+  if (t->n_outer) divmod(b, L, row, col);
+  if (valid == 16 && col + 16 <= L) {
+    uint8_t *p = reinterpret_cast<uint8_t *>(run_address(t, row) + col);
+    if (PACK) st16_aligned<NTS>(imgp, ld16_any<NTL>(p));
+    else st16_any<NTS>(p, ld16_aligned<NTL>(imgp));
+    return;
+  }
+  if (PACK) st16_aligned<NTS>(imgp, move_elements_any<true>(t, row, col, valid, u32x4{0, 0, 0, 0}));
+  else (void)move_elements_any<false>(t, row, col, valid, ld16_aligned<NTL>(imgp));
+}
+
+// ---- direct path: one tile range, whole work-group ---------------------------
+// [lo, hi): image range of the tile clipped to the chunk, multiples of 16.
+template <bool PACK, int NT, int UNROLL, bool NTL, bool NTS>
+__device__ __forceinline__ void move_tile_direct(const DsTile *t, uint64_t tile_begin, uint64_t lo, uint64_t hi,
+                                                 uint8_t *img, uint64_t img_lo) {
+  const uint32_t tid = threadIdx.x;
+  const uint64_t nbytes = t->nbytes;
+  const uint64_t full_end = tile_begin + (nbytes & ~(uint64_t)15);  // image offset where whole payload units end
+  const uint32_t n_all = (uint32_t)((hi - lo) >> 4);
+  uint32_t n_full = 0;
+  if (full_end > lo) n_full = (uint32_t)(((full_end < hi ? full_end : hi) - lo) >> 4);
+  uint8_t *imgp = img + (lo - img_lo);
+  const uint64_t b0 = lo - tile_begin;
+  const uint32_t m = t->n_outer;
+
+  if (m == 0) {
+    uint8_t *s = reinterpret_cast<uint8_t *>(t->src + b0);
+    for (uint32_t base = 0; base < n_full; base += NT * UNROLL) {
+      u32x4 v[UNROLL];
+#pragma unroll
+      for (int i = 0; i < UNROLL; ++i) {
+        const uint32_t u = base + i * NT + tid;
+        if (u < n_full) v[i] = PACK ? ld16_any<NTL>(s + 16ull * u) : ld16_aligned<NTL>(imgp + 16ull * u);
+      }
+#pragma unroll
+      for (int i = 0; i < UNROLL; ++i) {
+        const uint32_t u = base + i * NT + tid;
+        if (u < n_full) {
+          if (PACK) st16_aligned<NTS>(imgp + 16ull * u, v[i]);
+          else st16_any<NTS>(s + 16ull * u, v[i]);
+        }
+      }
+    }
+  } else {
+    const uint64_t L = t->run_bytes;
+    uint64_t row0, col0;
+    divmod(b0, L, row0, col0);
+    if (L < (1ull << 31)) {
+      const uint32_t L32 = (uint32_t)L, c32 = (uint32_t)col0;
+      for (uint32_t base = 0; base < n_full; base += NT * UNROLL) {
+#pragma unroll
+        for (int i = 0; i < UNROLL; ++i) {
+          const uint32_t u = base + i * NT + tid;
+          if (u < n_full) {
+            const uint32_t tt = c32 + 16u * u;        // < 2^31 + 2^22
+            const uint32_t q = tt / L32;
+            const uint32_t col = tt - q * L32;
+            const uint64_t row = row0 + q;
+            uint8_t *ip = imgp + 16ull * u;
+            if (col + 16u <= L32) {
+              uint8_t *p = reinterpret_cast<uint8_t *>(run_address(t, row) + col);
+              if (PACK) st16_aligned<NTS>(ip, ld16_any<NTL>(p));
+              else st16_any<NTS>(p, ld16_aligned<NTL>(ip));
+            } else {
+              if (PACK) st16_aligned<NTS>(ip, move_elements_any<true>(t, row, col, 16, u32x4{0, 0, 0, 0}));
+              else (void)move_elements_any<false>(t, row, col, 16, ld16_aligned<NTL>(ip));
+            }
+          }
+        }
+      }
+    } else {
+      for (uint32_t u = tid; u < n_full; u += NT)
+        move_unit<PACK, NTL, NTS>(t, tile_begin, lo + 16ull * u, imgp + 16ull * u);
+    }
+  }
+  // the unit cut by the end of the payload, then padding
+  for (uint32_t u = n_full + tid; u < n_all; u += NT)
+    move_unit<PACK, NTL, NTS>(t, tile_begin, lo + 16ull * u, imgp + 16ull * u);
+}
+
+__device__ __forceinline__ uint32_t wave_inclusive_scan(uint32_t x, uint32_t lane) {
+#pragma unroll
+  for (int d = 1; d < kWave; d <<= 1) {
+    const uint32_t y = __shfl_up(x, d, kWave);
+    if (lane >= (uint32_t)d) x += y;
+  }
+  return x;
+}
+
+template <bool PACK, int NT, int UNROLL, bool NTL, bool NTS>
+__global__ __launch_bounds__(NT) void ds_move_kernel(MoveArgs a) {
+  __shared__ uint32_t s_incl[kWave];   // inclusive scan of unit counts of the 64 tiles of a batch
+  __shared__ uint32_t s_begin[kWave];  // where each tile's clipped range starts, relative to the chunk
+  const uint32_t tid = threadIdx.x;
+  const uint32_t lane = tid & (kWave - 1);
+
+  for (uint32_t ci = blockIdx.x; ci < a.n_chunks; ci += gridDim.x) {
+    const uint64_t c = (uint64_t)a.c_lo + ci;
+    const uint64_t c_begin = c << a.chunk_log2;
+    uint64_t c_end = (c + 1) << a.chunk_log2;
+    if (c_end > a.total) c_end = a.total;
+    const uint64_t cb = c_begin > a.img_lo ? c_begin : a.img_lo;
+    const uint64_t ce = c_end < a.img_hi ? c_end : a.img_hi;
+    if (cb >= ce) continue;
+    const uint32_t t0 = a.first_tile[c];
+    uint32_t t1 = a.first_tile[c + 1];
+    if (a.tile_off[t1] >= c_end) --t1;  // that tile starts where this chunk ends
+
+    if (t1 - t0 < kDirectMaxTiles) {
+      for (uint32_t t = t0; t <= t1; ++t) {
+        const uint64_t tb = a.tile_off[t], te = a.tile_off[t + 1];
+        const uint64_t lo = tb > cb ? tb : cb, hi = te < ce ? te : ce;
+        if (lo < hi) move_tile_direct<PACK, NT, UNROLL, NTL, NTS>(a.tiles + t, tb, lo, hi, a.img, a.img_lo);
+      }
+      continue;
+    }
+
+    for (uint32_t bt = t0; bt <= t1; bt += kWave) {
+      const uint32_t ti = bt + lane;
+      uint64_t lo = cb, hi = cb;
+      if (ti <= t1) {
+        const uint64_t tb = a.tile_off[ti], te = a.tile_off[ti + 1];
+        lo = tb > cb ? tb : cb;
+        hi = te < ce ? te : ce;
+        if (hi < lo) hi = lo;
+      }
+      const uint32_t units = (uint32_t)((hi - lo) >> 4);
+      const bool big = units >= kBigUnits;
+      uint64_t big_mask = __ballot(big);
+      const uint32_t incl = wave_inclusive_scan(big ? 0u : units, lane);
+      const uint32_t n_small = __shfl(incl, kWave - 1, kWave);
+      __syncthreads();  // readers of the previous batch are done
+      if (tid < kWave) {
+        s_incl[lane] = incl;
+        s_begin[lane] = (uint32_t)(lo - cb);
+      }
+      __syncthreads();
+      for (uint32_t j = tid; j < n_small; j += NT) {
+        uint32_t p = 0;  // smallest p with s_incl[p] > j
+#pragma unroll
+        for (int step = kWave / 2; step > 0; step >>= 1)
+          if (s_incl[p + step - 1] <= j) p += step;
+        const uint32_t before = p ? s_incl[p - 1] : 0u;
+        const uint64_t x = cb + s_begin[p] + 16ull * (j - before);
+        move_unit<PACK, NTL, NTS>(a.tiles + bt + p, a.tile_off[bt + p], x, a.img + (x - a.img_lo));
+      }
+      while (big_mask) {
+        const uint32_t p = (uint32_t)__builtin_ctzll(big_mask);
+        big_mask &= big_mask - 1;
+        const uint32_t t = bt + p;
+        const uint64_t tb = a.tile_off[t], te = a.tile_off[t + 1];
+        const uint64_t lo2 = tb > cb ? tb : cb, hi2 = te < ce ? te : ce;
+        move_tile_direct<PACK, NT, UNROLL, NTL, NTS>(a.tiles + t, tb, lo2, hi2, a.img, a.img_lo);
+      }
+    }
+  }
+}
+
+template <bool PACK, int NT, int UNROLL, bool NTL, bool NTS>
+int launch(const MoveArgs &a, uint32_t grid, hipStream_t stream) {
+  hipLaunchKernelGGL((ds_move_kernel<PACK, NT, UNROLL, NTL, NTS>), dim3(grid), dim3(NT), 0, stream, a);
+  DS_HIP_TRY(hipGetLastError());
+  return DS_OK;
+}
+
+template <bool PACK>
+int launch_variant(uint64_t variant, const MoveArgs &a, uint32_t grid, hipStream_t stream) {
+  switch (variant) {
+    case 1: return launch<PACK, 256, 4, false, false>(a, grid, stream);  // plain loads and stores
+    case 2: return launch<PACK, 256, 8, true, true>(a, grid, stream);
+    case 3: return launch<PACK, 512, 4, true, true>(a, grid, stream);
+    default: return launch<PACK, 256, 4, true, true>(a, grid, stream);
+  }
+}
+
+}  // namespace
+
+int ds_launch_move(const ds_plan *plan, bool pack, uint8_t *img, uint64_t img_lo, uint64_t img_hi,
+                   uint32_t grid_limit, hipStream_t stream) {
+  MoveArgs a;
+  a.tiles = plan->d_tiles;
+  a.tile_off = plan->d_tile_off;
+  a.first_tile = plan->d_first_tile;
+  a.img = img;
+  a.img_lo = img_lo;
+  a.img_hi = img_hi;
+  a.total = plan->total_bytes;
+  a.chunk_log2 = plan->chunk_log2;
+  const uint64_t c_lo = img_lo >> plan->chunk_log2;
+  const uint64_t c_hi = (img_hi + ((uint64_t)1 << plan->chunk_log2) - 1) >> plan->chunk_log2;
+  if (c_hi > plan->n_chunks() || c_hi <= c_lo) return DS_ERANGE;
+  a.c_lo = (uint32_t)c_lo;
+  a.n_chunks = (uint32_t)(c_hi - c_lo);
+  uint32_t grid = a.n_chunks;
+  if (grid_limit && grid > grid_limit) grid = grid_limit;
+  const uint64_t variant = ds_cfg_variant();
+  return pack ? launch_variant<true>(variant, a, grid, stream) : launch_variant<false>(variant, a, grid, stream);
+}

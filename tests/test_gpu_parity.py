@@ -1,0 +1,196 @@
+"""GPU parity: the HIP gather/scatter (through the C ABI) against the CPU
+oracle, byte for byte, on the same seeded inputs.  Integer/byte work: the bar
+is bit-exact (memcmp), never a float comparison -- the fragmentation inputs
+contain NaN bit patterns."""
+import numpy as np
+import pytest
+
+import workloads as W
+from workloads.configs import Shard, Workload
+
+pytestmark = pytest.mark.gpu
+
+
+def _mods():
+    import paper_2601_16956_amd as ds
+    from oracle import ds_oracle as orc
+    import gpu_util
+    return ds, orc, gpu_util
+
+
+SMALL = {
+    "tiny_gpt": lambda: W.tiny_gpt(),
+    "frag_small": lambda: W.fragmentation(3000, max_bytes=1 << 18, seed=101),
+    "frag_tiny_only": lambda: W.fragmentation(5000, max_bytes=2048, seed=102),
+    "frag_all_strided": lambda: W.fragmentation(800, max_bytes=1 << 19, strided_fraction=1.0, seed=103),
+    "llama_mini": lambda: W.llama_rank("mini", 256, 704, 4, 2, 1024, 2, 4, 8, seed=5, workers=4),
+    "frag_align16": lambda: W.fragmentation(2000, max_bytes=1 << 14, align=16, seed=104),
+}
+
+
+@pytest.mark.parametrize("name", list(SMALL))
+def test_pack_matches_oracle(name):
+    ds, orc, gu = _mods()
+    w = SMALL[name]()
+    print(f"[case] pack {name} shards={len(w.shards)} payload={w.payload_bytes}", flush=True)
+    want, offs, _ = gu.oracle_image(w)
+    dw = gu.DeviceWorkload(w)
+    try:
+        assert dw.offsets == offs and dw.total == want.size
+        assert dw.info["payload_bytes"] == w.payload_bytes
+        got = dw.pack()
+        assert gu.first_mismatch(got, want) is None, gu.first_mismatch(got, want)
+    finally:
+        dw.close()
+
+
+@pytest.mark.parametrize("name", list(SMALL))
+def test_unpack_matches_oracle(name):
+    """Restore into an arena of 0xA5: addressed elements get the image's bytes,
+    every other byte keeps 0xA5 -- compared over the WHOLE arena."""
+    ds, orc, gu = _mods()
+    w = SMALL[name]()
+    print(f"[case] unpack {name}", flush=True)
+    img, offs, tab = gu.oracle_image(w)
+    dw = gu.DeviceWorkload(w, arena_fill=0xA5)
+    try:
+        dw.unpack(img)
+        got = dw.arena_host()
+        w.arena[:] = 0xA5
+        orc.unpack(tab, len(w.shards), img)
+        assert gu.first_mismatch(got, w.arena) is None, gu.first_mismatch(got, w.arena)
+    finally:
+        dw.close()
+
+
+@pytest.mark.parametrize("chunk_bytes", [4096, 65536, 1 << 20])
+@pytest.mark.parametrize("variant", [0, 1, 2, 3])
+def test_chunk_sizes_and_kernel_variants(chunk_bytes, variant):
+    ds, orc, gu = _mods()
+    w = W.fragmentation(1500, max_bytes=1 << 19, seed=77)
+    print(f"[case] chunk={chunk_bytes} variant={variant}", flush=True)
+    want, offs, tab = gu.oracle_image(w)
+    old_c, old_v = ds.ds_config_get("chunk_bytes"), ds.ds_config_get("variant")
+    ds.ds_config_set("chunk_bytes", chunk_bytes)
+    ds.ds_config_set("variant", variant)
+    try:
+        dw = gu.DeviceWorkload(w)
+        assert dw.info["chunk_bytes"] == chunk_bytes
+        got = dw.pack()
+        assert gu.first_mismatch(got, want) is None, gu.first_mismatch(got, want)
+        dw.arena.fill_(0xA5)
+        dw.unpack(want)
+        back = dw.arena_host()
+        w.arena[:] = 0xA5
+        orc.unpack(tab, len(w.shards), want)
+        assert gu.first_mismatch(back, w.arena) is None
+        dw.close()
+    finally:
+        ds.ds_config_set("chunk_bytes", old_c)
+        ds.ds_config_set("variant", old_v)
+
+
+def test_image_ranges_concatenate_to_the_whole():
+    """Sec. V-A4: a chunk need not be a whole object -- any partition of the
+    image into ranges (multiples of 16) gives the same bytes."""
+    ds, orc, gu = _mods()
+    w = W.fragmentation(1200, max_bytes=1 << 18, seed=55)
+    want, _, _ = gu.oracle_image(w)
+    dw = gu.DeviceWorkload(w)
+    rng = np.random.default_rng(1)
+    try:
+        for trial in range(4):
+            cuts = sorted(set(int(x) * 16 for x in rng.integers(0, dw.total // 16, size=int(rng.integers(1, 40)))))
+            edges = [0] + cuts + [dw.total]
+            print(f"[case] ranges trial={trial} n={len(edges) - 1}", flush=True)
+            parts = [dw.pack(lo, hi) for lo, hi in zip(edges[:-1], edges[1:]) if hi > lo]
+            got = np.concatenate(parts)
+            assert gu.first_mismatch(got, want) is None, gu.first_mismatch(got, want)
+        # scatter by ranges too
+        dw.arena.fill_(0xA5)
+        for lo, hi in zip(edges[:-1], edges[1:]):
+            if hi > lo:
+                dw.unpack(want, lo, hi)
+        tab = orc.table(w.shards, w.arena.ctypes.data)
+        for i, off in enumerate(dw.offsets):
+            tab[i].file_offset = off
+        w.arena[:] = 0xA5
+        orc.unpack(tab, len(w.shards), want)
+        assert gu.first_mismatch(dw.arena_host(), w.arena) is None
+    finally:
+        dw.close()
+
+
+def _adhoc(arena, shards, align):
+    return Workload("adhoc", align, 0, arena, shards)
+
+
+def test_edge_cases_given_offsets_holes_empty_scalar_6d():
+    ds, orc, gu = _mods()
+    rng = np.random.default_rng(9)
+    arena = rng.integers(0, 256, size=1 << 16, dtype=np.uint8)
+    shards = [
+        Shard("scalar", "i64", (), (), 8, 0),
+        Shard("empty", "f32", (0, 5), (5, 1), 64, 1),
+        Shard("six_d", "bf16", (2, 2, 2, 2, 2, 3), (400, 190, 90, 40, 16, 2), 1024, 2),
+        Shard("transposed", "f32", (7, 5), (1, 9), 8192, 3),
+        Shard("odd_tail", "u8", (1001,), (1,), 12001, 4),
+        Shard("strided_1d", "f16", (333,), (5,), 20000, 5),
+        Shard("ones", "u8", (1, 1, 13), (7, 7, 1), 30003, 6),
+        Shard("rows_short", "u8", (40, 6), (9, 1), 31001, 7),
+    ]
+    w = _adhoc(arena, shards, 64)
+    # caller-given offsets: any order, a hole at the start, a big hole in the middle
+    offsets = [4096, 128, 256, 64 * 100, 64 * 300, 64 * 20, 64 * 500, 64 * 40]
+    print("[case] edge cases", flush=True)
+    want, offs, tab = gu.oracle_image(w, offsets=offsets)
+    dw = gu.DeviceWorkload(w, offsets=offsets)
+    try:
+        assert dw.total == want.size
+        got = dw.pack()
+        assert gu.first_mismatch(got, want) is None, gu.first_mismatch(got, want)
+        dw.arena.fill_(0xA5)
+        dw.unpack(want)
+        w.arena[:] = 0xA5
+        orc.unpack(tab, len(shards), want)
+        assert gu.first_mismatch(dw.arena_host(), w.arena) is None
+    finally:
+        dw.close()
+
+
+def test_empty_table_and_all_empty_shards():
+    ds, orc, gu = _mods()
+    arena = np.zeros(4096, dtype=np.uint8)
+    dw = gu.DeviceWorkload(_adhoc(arena, [], 256))
+    assert dw.total == 0 and dw.info["n_chunks"] == 0
+    ds.ds_pack(dw.plan, 0, 0, 0, 0)          # a no-op, not an error
+    dw.close()
+    w = _adhoc(arena, [Shard("e0", "u8", (0,), (1,), 0, 0), Shard("e1", "f32", (3, 0), (1, 1), 0, 1)], 256)
+    dw = gu.DeviceWorkload(w, offsets=[0, 512])
+    try:
+        assert dw.total == 512                 # an empty shard still claims its offset
+        got = dw.pack()
+        assert not got.any() and got.size == 512
+    finally:
+        dw.close()
+
+
+def test_range_and_argument_errors_on_device_plan():
+    ds, orc, gu = _mods()
+    w = W.fragmentation(10, max_bytes=4096, seed=3)
+    dw = gu.DeviceWorkload(w)
+    import torch
+    buf = torch.zeros(dw.total + 64, dtype=torch.uint8, device="cuda")
+    try:
+        for lo, hi in [(16, 0), (0, dw.total + 16), (8, 32), (0, 24)]:
+            with pytest.raises(ds.DsError) as e:
+                ds.ds_pack(dw.plan, buf.data_ptr(), lo, hi, 0)
+            assert e.value.code == ds.DS_ERANGE
+        with pytest.raises(ds.DsError) as e:
+            ds.ds_pack(dw.plan, buf.data_ptr() + 8, 0, dw.total, 0)
+        assert e.value.code == ds.DS_EINVAL
+        with pytest.raises(ds.DsError) as e:
+            ds.ds_unpack(dw.plan, 0, 0, dw.total, 0)
+        assert e.value.code == ds.DS_EINVAL
+    finally:
+        dw.close()

@@ -1,0 +1,145 @@
+"""CPU-only tests of the library's host side: the shared object loads and
+exports every declared symbol; layout and plan validation (no device calls:
+plans are created with DS_PLAN_HOST_ONLY)."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_2601_16956_amd as ds
+import workloads as W
+from oracle import ds_oracle as orc
+from workloads.configs import Shard
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "datastates.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(ds_[a-z0-9_]+)\s*\(", header))
+    assert declared == set(ds.EXPORTS), declared ^ set(ds.EXPORTS)
+    L = ctypes.CDLL(ds.LIB_PATH)
+    for name in declared:
+        assert getattr(L, name) is not None
+
+
+def test_struct_sizes_match_the_header():
+    assert ctypes.sizeof(ds.ds_shard_desc) == 8 + 4 + 4 + 48 + 48 + 8 + 8
+    assert ctypes.sizeof(ds.ds_engine_opts) == 40
+    assert ctypes.sizeof(ds.ds_plan_stats) == 64
+
+
+def test_strerror_covers_all_codes():
+    for code in (0, 1, 2, -1, -2, -3, -4, -5, -6, -7, -8, -9):
+        assert "unknown" not in ds.ds_strerror(code)
+    assert "unknown" in ds.ds_strerror(-99)
+
+
+def _descs(shards, base=0x10000):
+    return ds.make_descs(shards, base)
+
+
+@pytest.mark.parametrize("maker", [
+    lambda: W.tiny_gpt(),
+    lambda: W.fragmentation(2000, max_bytes=1 << 16, seed=8),
+    lambda: W.llama_rank("mini", 128, 352, 4, 2, 512, 2, 4, 8, seed=5, workers=1),
+])
+def test_layout_assign_agrees_with_oracle_layout(maker):
+    w = maker()
+    n = len(w.shards)
+    d = _descs(w.shards)
+    total = ds.ds_layout_assign(d, n, w.align)
+    tab = orc.table(w.shards, w.arena.ctypes.data)
+    assert total == orc.layout(tab, n, w.align)
+    assert [int(d[i].file_offset) for i in range(n)] == [int(tab[i].file_offset) for i in range(n)]
+    plan = ds.ds_plan_create(d, n, w.align, ds.DS_PLAN_HOST_ONLY | ds.DS_PLAN_STRICT)
+    info = ds.ds_plan_info(plan)
+    assert info["total_bytes"] == total and info["payload_bytes"] == w.payload_bytes
+    assert info["n_shards"] == n and info["align"] == w.align
+    assert info["n_chunks"] == -(-total // info["chunk_bytes"])
+    for i, s in enumerate(w.shards):
+        tid, dt, off, nb = ds.ds_plan_shard(plan, i)
+        assert (tid, off, nb) == (s.tensor_id, int(d[i].file_offset), s.nbytes)
+    ds.ds_plan_destroy(plan)
+
+
+def _plan_rc(shards, align, offsets=None, flags=0, base=0x10000):
+    d = _descs(shards, base)
+    n = len(shards)
+    try:
+        if offsets is None:
+            ds.ds_layout_assign(d, n, align)
+        else:
+            for i, off in enumerate(offsets):
+                d[i].file_offset = off
+        plan = ds.ds_plan_create(d, n, align, flags | ds.DS_PLAN_HOST_ONLY)
+    except ds.DsError as e:
+        return e.code
+    ds.ds_plan_destroy(plan)
+    return 0
+
+
+def test_plan_validation_codes():
+    ok = [Shard("a", "f32", (4, 4), (4, 1), 0, 0), Shard("b", "u8", (100,), (1,), 256, 1)]
+    assert _plan_rc(ok, 64) == 0
+    assert _plan_rc(ok, 48) == ds.DS_EINVAL                       # not a power of two
+    assert _plan_rc(ok, 8) == ds.DS_EINVAL                        # below 16
+    assert _plan_rc(ok, 64, offsets=[0, 32]) == ds.DS_EALIGN
+    assert _plan_rc(ok, 64, offsets=[0, 0]) == ds.DS_EOVERLAP
+    assert _plan_rc(ok, 16, offsets=[0, 48]) == ds.DS_EOVERLAP    # a is 64 bytes
+    assert _plan_rc(ok, 64, offsets=[0, 128], flags=ds.DS_PLAN_STRICT) == ds.DS_EGAP
+    assert _plan_rc(ok, 64, offsets=[0, 128]) == 0                # holes allowed unless strict
+    assert _plan_rc(ok, 64, offsets=[64, 128], flags=ds.DS_PLAN_STRICT) == ds.DS_EGAP   # hole at the start
+    assert _plan_rc(ok, 64, offsets=[128, 0]) == 0                # any order
+    bad_dtype = [Shard("x", 7, (4,), (1,), 0, 0)]
+    assert _plan_rc(bad_dtype, 64) == ds.DS_EINVAL
+    assert _plan_rc([Shard("x", "f32", (4, -1), (1, 1), 0, 0)], 64, offsets=[0]) == ds.DS_EINVAL
+    assert _plan_rc([Shard("x", "f32", (4, 4), (0, 1), 0, 0)], 64) == ds.DS_EINVAL      # zero stride
+    assert _plan_rc([Shard("x", "f32", (4, 4), (-4, 1), 0, 0)], 64) == ds.DS_EINVAL     # negative stride
+    assert _plan_rc([Shard("x", "f32", (4, 4), (3, 1), 0, 0)], 64) == ds.DS_EOVERLAP    # rows overlap
+    assert _plan_rc([Shard("x", "f32", (4, 4), (1, 1), 0, 0)], 64) == ds.DS_EOVERLAP
+    assert _plan_rc([Shard("x", "f32", (4, 4), (1, 4), 0, 0)], 64) == 0                 # transposed is fine
+    assert _plan_rc([Shard("x", "f32", (1, 4), (0, 1), 0, 0)], 64) == 0                 # stride of an extent 1 is free
+    assert _plan_rc([Shard("x", "f32", (4,), (1,), 2, 0)], 64) == ds.DS_EINVAL          # base not element-aligned
+    assert _plan_rc([Shard("x", "f32", (4,), (1,), 0, 0)], 64, base=0) == ds.DS_EINVAL  # null base
+    assert _plan_rc([Shard("x", "f32", (0,), (1,), 0, 0)], 64, base=0) == 0             # ... unless empty
+    assert _plan_rc([], 64) == 0
+
+
+def test_seven_dims_rejected():
+    d = (ds.ds_shard_desc * 1)()
+    d[0].base = 0x1000
+    d[0].dtype = ds.DS_U8
+    d[0].ndim = 7
+    out = ctypes.c_void_p()
+    assert ds._lib.ds_plan_create(d, 1, 64, ds.DS_PLAN_HOST_ONLY, ctypes.byref(out)) == ds.DS_EINVAL
+    assert out.value is None                                      # untouched on failure
+
+
+def test_host_only_plan_cannot_be_packed():
+    d = _descs([Shard("a", "u8", (64,), (1,), 0, 0)])
+    ds.ds_layout_assign(d, 1, 64)
+    plan = ds.ds_plan_create(d, 1, 64, ds.DS_PLAN_HOST_ONLY)
+    with pytest.raises(ds.DsError) as e:
+        ds.ds_pack(plan, 0x1000, 0, 64, 0)
+    assert e.value.code == ds.DS_EINVAL
+    ds.ds_plan_destroy(plan)
+
+
+def test_config_keys():
+    assert ds.ds_config_get("chunk_bytes") == 128 << 10
+    for bad in (1000, 2048, 8 << 20):
+        with pytest.raises(ds.DsError):
+            ds.ds_config_set("chunk_bytes", bad)
+    with pytest.raises(ds.DsError):
+        ds.ds_config_set("no_such_key", 1)
+    ds.ds_config_set("chunk_bytes", 64 << 10)
+    d = _descs([Shard("a", "u8", (1 << 20,), (1,), 0, 0)])
+    ds.ds_layout_assign(d, 1, 64)
+    plan = ds.ds_plan_create(d, 1, 64, ds.DS_PLAN_HOST_ONLY)
+    assert ds.ds_plan_info(plan)["n_chunks"] == 16
+    ds.ds_plan_destroy(plan)
+    ds.ds_config_set("chunk_bytes", 128 << 10)
