@@ -1,0 +1,190 @@
+"""GPU tests of the snapshot engine (request -> gather -> chunked copies into
+the pinned ring -> consumer), against the CPU oracle byte for byte."""
+import ctypes
+import threading
+import time
+
+import numpy as np
+import pytest
+
+import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+MiB = 1 << 20
+
+
+def _mods():
+    import paper_2601_16956_amd as ds
+    from oracle import ds_oracle as orc
+    import gpu_util
+    import torch
+    return ds, orc, gpu_util, torch
+
+
+def _drain(ds, ev, total, delay=0.0, hold=1):
+    """Consumer: copies every chunk out of the ring into a host image.  `hold`
+    chunks are kept unreleased at a time (1 = release at once)."""
+    img = np.empty(total, dtype=np.uint8)
+    held = []
+    seen = 0
+    while True:
+        got = ds.ds_snapshot_next_chunk(ev)
+        if got is None:
+            break
+        ptr, off, ln = got
+        assert off == seen, "chunks must come in file order"
+        img[off:off + ln] = np.ctypeslib.as_array((ctypes.c_uint8 * ln).from_address(ptr))
+        seen += ln
+        held.append(ptr)
+        if delay:
+            time.sleep(delay)
+        while len(held) >= hold:
+            ds.ds_snapshot_release_chunk(ev, held.pop(0))
+    for p in held:
+        ds.ds_snapshot_release_chunk(ev, p)
+    assert seen == total
+    return img
+
+
+@pytest.mark.parametrize("cfg", [
+    dict(ring=4 * MiB, chunk=1 * MiB, slot=4 * MiB, slots=2, copy_streams=1),
+    dict(ring=2 * MiB, chunk=1 * MiB, slot=1 * MiB, slots=1, copy_streams=1),
+    dict(ring=8 * MiB, chunk=2 * MiB, slot=8 * MiB, slots=3, copy_streams=2),
+    dict(ring=64 * MiB, chunk=32 * MiB, slot=64 * MiB, slots=1, copy_streams=1),   # image fits one slot
+])
+def test_snapshot_with_consumer_matches_oracle(cfg):
+    ds, orc, gu, torch = _mods()
+    w = W.tiny_gpt()
+    print(f"[case] snapshot consumer {cfg}", flush=True)
+    want, _, _ = gu.oracle_image(w)
+    dw = gu.DeviceWorkload(w)
+    eng = ds.ds_engine_create(cfg["ring"], cfg["chunk"], cfg["slot"], cfg["slots"], 0, 0, cfg["copy_streams"])
+    try:
+        for rep in range(2):                                  # the second run reuses ring, staging, events
+            ev = ds.ds_snapshot_async(eng, dw.plan, torch.cuda.current_stream().cuda_stream)
+            got = _drain(ds, ev, dw.total, hold=1 + rep)
+            ds.ds_event_wait(ev)
+            assert ds.ds_event_query(ev) == ds.DS_OK
+            st = ds.ds_event_stats(ev)
+            assert st["image_bytes"] == dw.total and st["n_copies"] == -(-dw.total // cfg["chunk"])
+            assert st["n_pack_launches"] >= 1 and st["total_ms"] >= st["capture_ms"] > 0
+            ds.ds_event_destroy(ev)
+            assert gu.first_mismatch(got, want) is None, gu.first_mismatch(got, want)
+    finally:
+        ds.ds_engine_destroy(eng)
+        dw.close()
+
+
+def test_gate_keeps_the_snapshot_consistent_while_state_mutates():
+    """Sec. V-A2: the next iteration starts right after the request; the update
+    phase is gated.  Here the 'update' adds 1 to every byte of device memory,
+    enqueued directly behind the gate, with no host synchronisation; every
+    snapshot must still show the state at its own request."""
+    ds, orc, gu, torch = _mods()
+    w = W.fragmentation(1500, max_bytes=1 << 18, seed=31)
+    dw = gu.DeviceWorkload(w)
+    eng = ds.ds_engine_create(16 * MiB, 4 * MiB, 16 * MiB, 2, 0, 0, 1)
+    s = torch.cuda.current_stream().cuda_stream
+    busy = torch.randn(2048, 2048, device="cuda")
+    try:
+        events, wants = [], []
+        mirror = w.arena.copy()
+        for it in range(3):
+            print(f"[case] gate iteration {it}", flush=True)
+            w.arena[:] = mirror
+            wants.append(gu.oracle_image(w)[0].copy())
+            ev = ds.ds_snapshot_async(eng, dw.plan, s)
+            for _ in range(4):                                 # "forward/backward": state is only read
+                busy = busy @ busy * 1e-3
+            # consumer runs concurrently so that ring slots come back
+            box = {}
+            th = threading.Thread(target=lambda: box.setdefault("img", _drain(ds, ev, dw.total)))
+            th.start()
+            ds.ds_event_wait_on_stream(ev, s)                  # the lazy gate
+            dw.arena.add_(1)                                   # the mutating "update"
+            mirror = mirror + np.uint8(1)
+            th.join()
+            events.append((ev, box["img"]))
+        torch.cuda.synchronize()
+        for it, ((ev, got), want) in enumerate(zip(events, wants)):
+            ds.ds_event_wait(ev)
+            assert gu.first_mismatch(got, want) is None, (it, gu.first_mismatch(got, want))
+            ds.ds_event_destroy(ev)
+        assert np.array_equal(dw.arena_host(), mirror)
+    finally:
+        ds.ds_engine_destroy(eng)
+        dw.close()
+
+
+def test_back_pressure_slow_consumer_and_queued_snapshots():
+    """Sec. V-A2 last paragraph: with the ring full the next request waits for
+    eviction.  Two snapshots are requested back to back on a 2-slot ring; the
+    consumer is slow; nothing is lost or torn."""
+    ds, orc, gu, torch = _mods()
+    w = W.tiny_gpt()
+    want, _, _ = gu.oracle_image(w)
+    dw = gu.DeviceWorkload(w)
+    eng = ds.ds_engine_create(2 * MiB, 1 * MiB, 2 * MiB, 2, 0, 0, 1)
+    s = torch.cuda.current_stream().cuda_stream
+    try:
+        ev1 = ds.ds_snapshot_async(eng, dw.plan, s)
+        ev2 = ds.ds_snapshot_async(eng, dw.plan, s)
+        time.sleep(0.2)
+        # the ring holds 2 of ~26 chunks: neither snapshot can be complete yet
+        assert ds.ds_event_query(ev1) == ds.DS_NOT_READY
+        assert ds.ds_event_query(ev2) == ds.DS_NOT_READY
+        print("[case] back-pressure drain 1", flush=True)
+        got1 = _drain(ds, ev1, dw.total, delay=0.002)
+        print("[case] back-pressure drain 2", flush=True)
+        got2 = _drain(ds, ev2, dw.total)
+        ds.ds_event_wait(ev1)
+        ds.ds_event_wait(ev2)
+        assert gu.first_mismatch(got1, want) is None
+        assert gu.first_mismatch(got2, want) is None
+        ds.ds_event_destroy(ev1)
+        ds.ds_event_destroy(ev2)
+    finally:
+        ds.ds_engine_destroy(eng)
+        dw.close()
+
+
+def test_auto_release_and_state_errors():
+    ds, orc, gu, torch = _mods()
+    w = W.tiny_gpt()
+    dw = gu.DeviceWorkload(w)
+    s = torch.cuda.current_stream().cuda_stream
+    eng = ds.ds_engine_create(4 * MiB, 1 * MiB, 4 * MiB, 2, 0, ds.DS_ENGINE_AUTO_RELEASE, 1)
+    try:
+        print("[case] auto release", flush=True)
+        ev = ds.ds_snapshot_async(eng, dw.plan, s)
+        with pytest.raises(ds.DsError) as e:
+            ds.ds_snapshot_next_chunk(ev)
+        assert e.value.code == ds.DS_ESTATE
+        with pytest.raises(ds.DsError) as e:
+            ds.ds_engine_destroy(eng)                          # an event is still alive
+        assert e.value.code == ds.DS_EBUSY
+        ds.ds_event_wait_captured(ev)
+        ds.ds_event_wait(ev)
+        st = ds.ds_event_stats(ev)
+        assert st["payload_bytes"] == w.payload_bytes and st["pack_ms"] > 0 and st["copy_ms"] > 0
+        ds.ds_event_destroy(ev)
+    finally:
+        ds.ds_engine_destroy(eng)
+    eng = ds.ds_engine_create(4 * MiB, 1 * MiB, 4 * MiB, 2, 0, 0, 1)
+    try:
+        print("[case] destroy drains an unconsumed snapshot", flush=True)
+        ev = ds.ds_snapshot_async(eng, dw.plan, s)
+        got = ds.ds_snapshot_next_chunk(ev)
+        with pytest.raises(ds.DsError) as e:
+            ds.ds_snapshot_release_chunk(ev, got[0] + 4096)    # not a slot address
+        assert e.value.code == ds.DS_ESTATE
+        ds.ds_event_destroy(ev)                                # gives back what is held, drains the rest
+    finally:
+        ds.ds_engine_destroy(eng)
+        dw.close()
+    for bad in [dict(d2h_chunk_bytes=1000), dict(d2h_chunk_bytes=MiB, stage_slot_bytes=MiB + 4096),
+                dict(host_ring_bytes=MiB, d2h_chunk_bytes=2 * MiB), dict(copy_streams=3)]:
+        with pytest.raises(ds.DsError) as e:
+            ds.ds_engine_create(**bad)
+        assert e.value.code == ds.DS_EINVAL
