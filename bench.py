@@ -1,0 +1,324 @@
+#!/usr/bin/env python3
+"""Benchmark of the snapshot hot path on one MI355X.
+
+A step = one lazy snapshot of one rank's state: request on the compute stream,
+gather into device staging, chunked copies into the pinned host ring, and the
+gate before the (here empty) update phase.  Steps are issued the way a training
+loop checkpointing every iteration issues them: back to back, each gated, the
+engine pipelining the gather of step i+1 under the copies of step i.  The
+inputs are resident in HBM before the timed region.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload llama7b]
+
+Prints ONE JSON line.  `value` is payload GB/s of the whole step (link-bound);
+`roofline` is the gather kernel against the HBM peak, timed with HIP events on
+the stream it runs on; `cpu_baseline` is the CPU oracle's pack of the same
+workload on this machine's host cores.
+"""
+from __future__ import annotations
+
+import argparse
+import ctypes
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published
+MiB = 1 << 20
+GiB = 1 << 30
+
+WORKLOADS = {
+    "tiny_gpt": "configs[0] tiny GPT-style state, 118 shards",
+    "llama7b": "configs[1] Llama-7B rank (TP=4, PP=4, ZeRO-1 DP=8), 76 shards",
+    "fragmentation": "configs[2] fragmentation stress, 20000 shards",
+    "llama70b": "configs[3] Llama-2-70B rank (TP=8, PP=4, ZeRO-1 DP=8), 184 shards",
+}
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="llama7b", choices=list(WORKLOADS))
+    ap.add_argument("--ring-bytes", type=int, default=2 * GiB, help="pinned host ring (configs[4] caps it at 2 GiB)")
+    ap.add_argument("--chunk-bytes", type=int, default=32 * MiB, help="one device-to-host copy / ring slot")
+    ap.add_argument("--stage-slot-bytes", type=int, default=2 * GiB, help="device staging slot = bytes per gather launch")
+    ap.add_argument("--stage-slots", type=int, default=2)
+    ap.add_argument("--copy-streams", type=int, default=1)
+    ap.add_argument("--no-overlap", action="store_true", help="skip the concurrent-GEMM leg (configs[4])")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--gemm-iters", type=int, default=12, help="iterations of the overlap leg")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        log("bench.py: this build is the one-GPU hot path; it has no multi-GPU leg (run with --gpus 1).")
+        return 2
+
+    import numpy as np
+    import torch
+
+    import paper_2601_16956_amd as ds
+    import workloads as W
+
+    assert torch.cuda.is_available(), "needs the MI355X"
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    cores = len(os.sched_getaffinity(0))
+    cores = min(cores, int(os.environ.get("OMP_NUM_THREADS", cores)))
+
+    t0 = time.time()
+    w = W.by_name(args.workload, workers=cores)
+    log(f"[bench] generated {w.name}: {len(w.shards)} shards, payload {w.payload_bytes / 1e9:.3f} GB, "
+        f"arena {w.arena.size / 1e9:.3f} GB in {time.time() - t0:.1f}s")
+    arena = torch.from_numpy(w.arena).to(dev)
+    n = len(w.shards)
+    descs = ds.make_descs(w.shards, arena.data_ptr())
+    total = ds.ds_layout_assign(descs, n, w.align)
+    t0 = time.perf_counter()
+    plan = ds.ds_plan_create(descs, n, w.align, ds.DS_PLAN_STRICT)
+    plan_ms = (time.perf_counter() - t0) * 1e3
+    info = ds.ds_plan_info(plan)
+    payload = info["payload_bytes"]
+    stream = torch.cuda.current_stream().cuda_stream
+
+    # ---- measured link peak: best of 10 x 1 GiB contiguous device -> pinned host -------------
+    probe_dev = torch.empty(GiB, dtype=torch.uint8, device=dev).random_(0, 255)
+    probe_host = torch.empty(GiB, dtype=torch.uint8, pin_memory=True)
+    link_best = 0.0
+    for i in range(12):
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        probe_host.copy_(probe_dev, non_blocking=True)
+        b.record()
+        torch.cuda.synchronize()
+        if i >= 2:
+            link_best = max(link_best, GiB / (a.elapsed_time(b) * 1e-3) / 1e9)
+    del probe_dev, probe_host
+    log(f"[bench] measured D2H link peak {link_best:.1f} GB/s")
+
+    # ---- the timed region: K snapshots, back to back, each gated ------------------------------
+    eng = ds.ds_engine_create(args.ring_bytes, args.chunk_bytes, args.stage_slot_bytes, args.stage_slots, 0,
+                              ds.DS_ENGINE_AUTO_RELEASE, args.copy_streams)
+
+    def run_steps(k):
+        evs = []
+        for _ in range(k):
+            ev = ds.ds_snapshot_async(eng, plan, stream)
+            ds.ds_event_wait_on_stream(ev, stream)       # gate before the (empty) update phase
+            evs.append(ev)
+        for ev in evs:
+            ds.ds_event_wait(ev)
+        return evs
+
+    for ev in run_steps(args.warmup):
+        ds.ds_event_destroy(ev)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    evs = run_steps(args.steps)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    pack_ms = copy_ms = capture_ms = submit_ms = 0.0
+    launches = 0
+    for ev in evs:
+        st = ds.ds_event_stats(ev)
+        pack_ms += st["pack_ms"]
+        copy_ms += st["copy_ms"]
+        capture_ms += st["capture_ms"]
+        submit_ms += st["submit_host_ms"]
+        launches += st["n_pack_launches"]
+        ds.ds_event_destroy(ev)
+    ms_per_step = elapsed * 1e3 / args.steps
+    value = payload * args.steps / elapsed / 1e9
+
+    # one isolated snapshot: request -> whole image resident in the host ring
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    ev = ds.ds_snapshot_async(eng, plan, stream)
+    ds.ds_event_wait(ev)
+    latency_ms = (time.perf_counter() - t0) * 1e3
+    one = ds.ds_event_stats(ev)
+    ds.ds_event_destroy(ev)
+
+    # ---- gather and scatter alone, whole image, device to device ------------------------------
+    image_dev = torch.empty(max(total, 16), dtype=torch.uint8, device=dev)
+
+    def timed(fn, reps=10, warm=2):
+        for _ in range(warm):
+            fn()
+        torch.cuda.synchronize()
+        pairs = []
+        for _ in range(reps):
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            fn()
+            b.record()
+            pairs.append((a, b))
+        torch.cuda.synchronize()
+        ts = sorted(a.elapsed_time(b) for a, b in pairs)
+        return ts[len(ts) // 2], ts[0]
+
+    pack_med, pack_best = timed(lambda: ds.ds_pack(plan, image_dev.data_ptr(), 0, total, stream))
+    unpack_med, unpack_best = timed(lambda: ds.ds_unpack(plan, image_dev.data_ptr(), 0, total, stream))
+    copy_src = torch.empty_like(image_dev)
+    d2d_med, _ = timed(lambda: image_dev.copy_(copy_src))
+    del copy_src
+
+    # ---- parity of this very run against the CPU oracle + the CPU baseline --------------------
+    parity = "not checked"
+    cpu_baseline = None
+    if not args.no_cpu_baseline:
+        from oracle import ds_oracle as orc
+        tab = orc.table(w.shards, w.arena.ctypes.data)
+        assert orc.layout(tab, n, w.align) == total
+        want = np.empty(total, dtype=np.uint8)
+        orc.pack(tab, n, total, threads=cores, out=want)          # also faults the pages in
+        runs = []
+        for _ in range(3):
+            t0 = time.perf_counter()
+            orc.pack(tab, n, total, threads=cores, out=want)
+            runs.append(time.perf_counter() - t0)
+        t0 = time.perf_counter()
+        orc.pack(tab, n, total, threads=1, out=want)
+        single = time.perf_counter() - t0
+        cpu_baseline = {
+            "value": round(payload / sorted(runs)[1] / 1e9, 2), "unit": "GB/s", "cores": cores, "kind": "oracle",
+            "sample": f"dso_pack_mt of the whole {args.workload} image ({payload / 1e9:.2f} GB), median of 3 runs "
+                      f"after 1 warm-up, {cores} threads; single thread: {payload / single / 1e9:.2f} GB/s",
+        }
+        ds.ds_pack(plan, image_dev.data_ptr(), 0, total, stream)
+        torch.cuda.synchronize()
+        got = image_dev[:total].cpu().numpy()
+        same = all(np.array_equal(got[lo:lo + (1 << 28)], want[lo:lo + (1 << 28)]) for lo in range(0, total, 1 << 28))
+        parity = "byte-exact vs CPU oracle" if same else "MISMATCH vs CPU oracle"
+        # restore: scatter the oracle's image back into a wiped arena, compare the whole arena
+        keep = arena.clone()
+        arena.fill_(0xA5)
+        image_dev[:total].copy_(torch.from_numpy(want))
+        ds.ds_unpack(plan, image_dev.data_ptr(), 0, total, stream)
+        torch.cuda.synchronize()
+        back = arena.cpu().numpy()
+        w.arena[:] = 0xA5
+        orc.unpack(tab, n, want)
+        same_r = all(np.array_equal(back[lo:lo + (1 << 28)], w.arena[lo:lo + (1 << 28)])
+                     for lo in range(0, back.size, 1 << 28))
+        parity += "; restore byte-exact" if same_r else "; restore MISMATCH"
+        arena.copy_(keep)
+        del keep, got, back, want
+
+    # ---- configs[4]: snapshots under a concurrent bf16 GEMM stream -----------------------------
+    overlap = None
+    if not args.no_overlap:
+        M = 8192
+        A = torch.randn(M, M, device=dev, dtype=torch.bfloat16)
+        B = torch.randn(M, M, device=dev, dtype=torch.bfloat16)
+        C = torch.empty(M, M, device=dev, dtype=torch.bfloat16)
+        for _ in range(5):
+            torch.matmul(A, B, out=C)
+        torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(20):
+            torch.matmul(A, B, out=C)
+        b.record()
+        torch.cuda.synchronize()
+        gemm_ms = a.elapsed_time(b) / 20
+        G = max(4, int(round(1.5 * one["total_ms"] / gemm_ms)))   # forward/backward ~1.5x one snapshot
+
+        def loop(with_snapshots: bool):
+            evs = []
+            prev = None
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            torch.cuda.synchronize()
+            a.record()
+            for _ in range(args.gemm_iters):
+                for _ in range(G):                                # state is only read here
+                    torch.matmul(A, B, out=C)
+                if prev is not None:
+                    ds.ds_event_wait_on_stream(prev, stream)      # the lazy gate
+                arena.add_(1)                                     # the mutating update phase
+                if with_snapshots:
+                    prev = ds.ds_snapshot_async(eng, plan, stream)
+                    evs.append(prev)
+            b.record()
+            torch.cuda.synchronize()
+            for ev in evs:
+                ds.ds_event_wait(ev)
+                ds.ds_event_destroy(ev)
+            return a.elapsed_time(b)
+
+        loop(True)
+        base = min(loop(False) for _ in range(2))
+        with_s = min(loop(True) for _ in range(2))
+        overlap = {
+            "gemm": "bf16 8192x8192x8192 (torch.matmul)", "gemm_ms": round(gemm_ms, 3),
+            "gemm_tflops": round(2 * M ** 3 / gemm_ms / 1e9, 1), "gemms_per_iter": G, "iters": args.gemm_iters,
+            "ms_without_snapshots": round(base, 2), "ms_with_snapshots": round(with_s, 2),
+            "slowdown_pct": round(100.0 * (with_s - base) / base, 2),
+            "ring_bytes": args.ring_bytes,
+        }
+        del A, B, C
+
+    ds.ds_engine_destroy(eng)
+    torch.cuda.synchronize()
+    ds.ds_plan_destroy(plan)
+
+    # algorithmic bytes of one gather launch: every payload byte read once, every image byte
+    # (payload + padding) written once
+    algo_bytes = payload + total
+    achieved = algo_bytes * args.steps / (pack_ms * 1e-3) / 1e9 if pack_ms > 0 else 0.0
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "traffic.json")
+    if os.path.exists(tpath):
+        try:
+            traffic = json.load(open(tpath)).get(args.workload)
+        except Exception:
+            traffic = None
+    out = {
+        "metric": "snapshot GB/s/GPU (pack+D2H to pinned host)",
+        "value": round(value, 3), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 3), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "u8", "data": "synthetic",
+        "config": {
+            "workload": f"{args.workload}: {WORKLOADS[args.workload]}", "payload_bytes": payload,
+            "image_bytes": total, "shards": n, "align": w.align, "host_ring_bytes": args.ring_bytes,
+            "d2h_chunk_bytes": args.chunk_bytes, "stage_slot_bytes": args.stage_slot_bytes,
+            "stage_slots": args.stage_slots, "copy_streams": args.copy_streams,
+            "workgroup_chunk_bytes": info["chunk_bytes"],
+        },
+        "roofline": {
+            "bound": "hbm", "kernel": "ds_move_kernel<pack>", "achieved": round(achieved, 1),
+            "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic,
+            "launches": launches, "avg_launch_ms": round(pack_ms / max(launches, 1), 4),
+            "algorithmic_bytes_per_step": algo_bytes,
+        },
+        "cpu_baseline": cpu_baseline,
+        "parity": parity,
+        "d2h": {"achieved_GBps": round(total * args.steps / (copy_ms * 1e-3) / 1e9, 2),
+                "link_peak_measured_GBps": round(link_best, 2),
+                "frac": round(total * args.steps / (copy_ms * 1e-3) / 1e9 / link_best, 4)},
+        "snapshot_latency_ms": round(latency_ms, 3),
+        "capture_ms": round(capture_ms / args.steps, 3),          # request -> tensors may be mutated
+        "submit_host_ms": round(submit_ms / args.steps, 4),       # host time inside ds_snapshot_async
+        "plan_create_ms": round(plan_ms, 3),
+        "standalone": {
+            "pack_ms": round(pack_med, 4), "pack_GBps": round(algo_bytes / pack_med / 1e6, 1),
+            "pack_best_GBps": round(algo_bytes / pack_best / 1e6, 1),
+            "unpack_ms": round(unpack_med, 4), "unpack_GBps": round(2 * payload / unpack_med / 1e6, 1),
+            "torch_d2d_copy_GBps": round(2 * total / d2d_med / 1e6, 1),
+        },
+        "overlap": overlap,
+    }
+    print(json.dumps(out), flush=True)
+    return 0 if "MISMATCH" not in parity else 1
+
+
+if __name__ == "__main__":
+    sys.exit(main())

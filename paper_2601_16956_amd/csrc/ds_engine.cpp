@@ -51,6 +51,7 @@ struct ds_engine {
   std::vector<uint8_t> ring_busy;  // consumer mode: slot holds data not yet released
   uint32_t ring_next = 0;
   uint64_t copies_issued = 0;
+  uint64_t groups_issued = 0;  // staging slots rotate across snapshots
 
   std::mutex mu;
   std::condition_variable cv;
@@ -73,6 +74,7 @@ struct ds_event {
   std::vector<hipEvent_t> pack_begin, pack_end;
   std::vector<DsChunk> chunks;
   uint32_t cursor = 0;  // next chunk the consumer gets
+  bool capture_issued = false;  // the last gather (and the `captured` event) is enqueued
   bool all_issued = false;
   int error = DS_OK;
   double submit_host_ms = 0;
@@ -92,6 +94,10 @@ int hip_fail(hipError_t e) {
   } while (0)
 
 // Issues every launch and copy of one snapshot.  Runs on the engine's thread.
+// Gathers are issued as far ahead as staging allows (a gather into a slot may be
+// enqueued once the copies that last read that slot have been enqueued), so with
+// staging as large as the image every gather -- and with it the gate -- is out
+// before the first wait for a ring slot.
 int issue_snapshot(ds_engine *g, ds_event *ev) {
   const ds_plan *plan = ev->plan;
   const uint64_t T = plan->total_bytes;
@@ -99,29 +105,55 @@ int issue_snapshot(ds_engine *g, ds_event *ev) {
   W_TRY(hipEventCreate(&ev->captured));
   W_TRY(hipEventCreate(&ev->final_ev));
   W_TRY(hipEventCreate(&ev->copy_begin));
-  uint64_t at = 0;
-  uint32_t group = 0, k = 0;
-  while (at < T) {
+
+  struct Group { uint64_t lo, hi; uint32_t slot; };
+  std::vector<Group> groups;
+  for (uint64_t at = 0; at < T;) {
     // the first launch is one copy chunk long, the others fill a staging slot
-    const uint64_t want = group == 0 ? g->chunk_bytes : g->stage_slot_bytes;
+    const uint64_t want = groups.empty() ? g->chunk_bytes : g->stage_slot_bytes;
     const uint64_t hi = at + want < T ? at + want : T;
-    const uint32_t s = group % g->stage_slots;
-    uint8_t *slot = g->stage + (uint64_t)s * g->stage_slot_bytes;
-    if (g->stage_used[s])
-      for (int c = 0; c < g->n_copy_streams; ++c) W_TRY(hipStreamWaitEvent(g->pack_stream, g->stage_free[c][s], 0));
+    groups.push_back({at, hi, (uint32_t)(g->groups_issued++ % g->stage_slots)});
+    at = hi;
+  }
+  const size_t G = groups.size();
+
+  auto mark_captured = [&]() -> int {
+    W_TRY(hipEventRecord(ev->captured, g->pack_stream));
+    {
+      std::lock_guard<std::mutex> lk(g->mu);
+      ev->capture_issued = true;
+    }
+    g->cv.notify_all();
+    return DS_OK;
+  };
+
+  auto issue_pack = [&](size_t gi) -> int {
+    const Group &gr = groups[gi];
+    uint8_t *slot = g->stage + (uint64_t)gr.slot * g->stage_slot_bytes;
+    if (g->stage_used[gr.slot])
+      for (int c = 0; c < g->n_copy_streams; ++c)
+        W_TRY(hipStreamWaitEvent(g->pack_stream, g->stage_free[c][gr.slot], 0));
     hipEvent_t b, e;
     W_TRY(hipEventCreate(&b));
     ev->pack_begin.push_back(b);
     W_TRY(hipEventCreate(&e));
     ev->pack_end.push_back(e);
     W_TRY(hipEventRecord(b, g->pack_stream));
-    int rc = ds_launch_move(plan, true, slot, at, hi, g->grid_limit, g->pack_stream);
+    int rc = ds_launch_move(plan, true, slot, gr.lo, gr.hi, g->grid_limit, g->pack_stream);
     if (rc != DS_OK) return rc;
     W_TRY(hipEventRecord(e, g->pack_stream));
-    for (int c = 0; c < g->n_copy_streams; ++c) W_TRY(hipStreamWaitEvent(g->copy_stream[c], e, 0));
-    if (group == 0) W_TRY(hipEventRecord(ev->copy_begin, g->copy_stream[0]));
-    for (uint64_t lo = at; lo < hi; lo += g->chunk_bytes, ++k) {
-      const uint64_t len = lo + g->chunk_bytes < hi ? g->chunk_bytes : hi - lo;
+    if (gi + 1 == G) return mark_captured();
+    return DS_OK;
+  };
+
+  uint32_t k = 0;
+  auto issue_copies = [&](size_t gi) -> int {
+    const Group &gr = groups[gi];
+    uint8_t *slot = g->stage + (uint64_t)gr.slot * g->stage_slot_bytes;
+    for (int c = 0; c < g->n_copy_streams; ++c) W_TRY(hipStreamWaitEvent(g->copy_stream[c], ev->pack_end[gi], 0));
+    if (gi == 0) W_TRY(hipEventRecord(ev->copy_begin, g->copy_stream[0]));
+    for (uint64_t lo = gr.lo; lo < gr.hi; lo += g->chunk_bytes, ++k) {
+      const uint64_t len = lo + g->chunk_bytes < gr.hi ? g->chunk_bytes : gr.hi - lo;
       uint32_t r;
       {
         std::unique_lock<std::mutex> lk(g->mu);
@@ -137,7 +169,7 @@ int issue_snapshot(ds_engine *g, ds_event *ev) {
       hipStream_t cs = g->copy_stream[c];
       // the slot's previous copy may have run on the other copy stream
       if (g->n_copy_streams > 1) W_TRY(hipStreamWaitEvent(cs, g->ring_done[r], 0));
-      W_TRY(hipMemcpyAsync(g->ring + (uint64_t)r * g->chunk_bytes, slot + (lo - at), len, hipMemcpyDeviceToHost, cs));
+      W_TRY(hipMemcpyAsync(g->ring + (uint64_t)r * g->chunk_bytes, slot + (lo - gr.lo), len, hipMemcpyDeviceToHost, cs));
       W_TRY(hipEventRecord(g->ring_done[r], cs));
       {
         std::lock_guard<std::mutex> lk(g->mu);
@@ -146,12 +178,24 @@ int issue_snapshot(ds_engine *g, ds_event *ev) {
       }
       g->cv.notify_all();
     }
-    for (int c = 0; c < g->n_copy_streams; ++c) W_TRY(hipEventRecord(g->stage_free[c][s], g->copy_stream[c]));
-    g->stage_used[s] = true;
-    at = hi;
-    ++group;
+    for (int c = 0; c < g->n_copy_streams; ++c) W_TRY(hipEventRecord(g->stage_free[c][gr.slot], g->copy_stream[c]));
+    g->stage_used[gr.slot] = true;
+    return DS_OK;
+  };
+
+  if (G == 0) {
+    int rc = mark_captured();
+    if (rc != DS_OK) return rc;
   }
-  W_TRY(hipEventRecord(ev->captured, g->pack_stream));
+  size_t np = 0;
+  for (size_t nc = 0; nc < G; ++nc) {
+    for (; np < G && np < nc + g->stage_slots; ++np) {
+      int rc = issue_pack(np);
+      if (rc != DS_OK) return rc;
+    }
+    int rc = issue_copies(nc);
+    if (rc != DS_OK) return rc;
+  }
   W_TRY(hipStreamWaitEvent(g->copy_stream[0], ev->captured, 0));
   if (g->n_copy_streams > 1 && !ev->chunks.empty()) {
     hipEvent_t tail;
@@ -185,6 +229,14 @@ void worker_main(ds_engine *g) {
     }
     g->cv.notify_all();
   }
+}
+
+// waits until the engine thread has enqueued the last gather of this snapshot
+int wait_capture_issued(ds_event *ev) {
+  ds_engine *g = ev->eng;
+  std::unique_lock<std::mutex> lk(g->mu);
+  g->cv.wait(lk, [&] { return ev->capture_issued || ev->all_issued; });
+  return ev->capture_issued ? DS_OK : ev->error;
 }
 
 // waits until the engine thread has issued everything of this snapshot
@@ -347,7 +399,7 @@ int ds_snapshot_async(ds_engine *g, const ds_plan *plan, void *compute_stream, d
 
 int ds_event_wait_on_stream(ds_event *ev, void *stream) {
   if (!ev) return DS_EINVAL;
-  int rc = wait_issued(ev);
+  int rc = wait_capture_issued(ev);
   if (rc != DS_OK) return rc;
   DS_HIP_TRY(hipStreamWaitEvent((hipStream_t)stream, ev->captured, 0));
   return DS_OK;
@@ -355,7 +407,7 @@ int ds_event_wait_on_stream(ds_event *ev, void *stream) {
 
 int ds_event_wait_captured(ds_event *ev) {
   if (!ev) return DS_EINVAL;
-  int rc = wait_issued(ev);
+  int rc = wait_capture_issued(ev);
   if (rc != DS_OK) return rc;
   DS_HIP_TRY(hipEventSynchronize(ev->captured));
   return DS_OK;
