@@ -62,10 +62,10 @@ def main() -> int:
         log("bench.py: this build is the one-GPU hot path; it has no multi-GPU leg (run with --gpus 1).")
         return 2
 
+    import paper_2601_16956_amd as ds      # before torch (see _preload_system_rocm)
     import numpy as np
     import torch
 
-    import paper_2601_16956_amd as ds
     import workloads as W
 
     assert torch.cuda.is_available(), "needs the MI355X"
@@ -315,6 +315,7 @@ def main() -> int:
             "torch_d2d_copy_GBps": round(2 * total / d2d_med / 1e6, 1),
         },
         "overlap": overlap,
+        "hip_runtime": ds.hip_runtime_in_use(),
     }
     print(json.dumps(out), flush=True)
     return 0 if "MISMATCH" not in parity else 1

@@ -84,7 +84,38 @@ class DsError(RuntimeError):
         super().__init__(f"{where}: {msg} ({code})")
 
 
+def _preload_system_rocm() -> None:
+    """Opt-in (DS_ROCM_PRELOAD=1, and only effective if this package is imported
+    before torch): load the system ROCm runtime (/opt/rocm) ahead of the older
+    copy bundled inside the PyTorch wheel.  Measured on MI355X: under the bundled
+    runtime every pinned device-to-host hipMemcpyAsync runs as a blit KERNEL
+    (256 work-groups x 512 threads on the CUs for the whole transfer); under the
+    system runtime it runs on the SDMA copy engines, off the CUs.  Link rate and
+    the slowdown of a concurrent GEMM stream came out the same within noise, so
+    the default leaves the process alone."""
+    if os.environ.get("DS_ROCM_PRELOAD") != "1":
+        return
+    root = os.environ.get("ROCM_PATH", "/opt/rocm")
+    for name in ("libhsa-runtime64.so.1", "libamdhip64.so.7"):
+        path = os.path.join(root, "lib", name)
+        if os.path.exists(path):
+            try:
+                ctypes.CDLL(path, mode=ctypes.RTLD_GLOBAL)
+            except OSError:
+                return
+
+
+def hip_runtime_in_use() -> List[str]:
+    """Paths of the HIP / HSA runtime libraries mapped into this process."""
+    try:
+        with open("/proc/self/maps") as f:
+            return sorted({ln.split()[-1] for ln in f if "libamdhip64" in ln or "libhsa-runtime64" in ln})
+    except OSError:
+        return []
+
+
 def _load() -> ctypes.CDLL:
+    _preload_system_rocm()
     if not os.path.exists(LIB_PATH):
         raise ImportError(
             f"{LIB_PATH} is missing: build it first (python -m paper_2601_16956_amd.build, or "
