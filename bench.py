@@ -62,9 +62,10 @@ def main() -> int:
         log("bench.py: this build is the one-GPU hot path; it has no multi-GPU leg (run with --gpus 1).")
         return 2
 
-    import paper_2601_16956_amd as ds      # before torch (see _preload_system_rocm)
     import numpy as np
     import torch
+
+    import paper_2601_16956_amd as ds
 
     import workloads as W
 

@@ -84,27 +84,6 @@ class DsError(RuntimeError):
         super().__init__(f"{where}: {msg} ({code})")
 
 
-def _preload_system_rocm() -> None:
-    """Opt-in (DS_ROCM_PRELOAD=1, and only effective if this package is imported
-    before torch): load the system ROCm runtime (/opt/rocm) ahead of the older
-    copy bundled inside the PyTorch wheel.  Measured on MI355X: under the bundled
-    runtime every pinned device-to-host hipMemcpyAsync runs as a blit KERNEL
-    (256 work-groups x 512 threads on the CUs for the whole transfer); under the
-    system runtime it runs on the SDMA copy engines, off the CUs.  Link rate and
-    the slowdown of a concurrent GEMM stream came out the same within noise, so
-    the default leaves the process alone."""
-    if os.environ.get("DS_ROCM_PRELOAD") != "1":
-        return
-    root = os.environ.get("ROCM_PATH", "/opt/rocm")
-    for name in ("libhsa-runtime64.so.1", "libamdhip64.so.7"):
-        path = os.path.join(root, "lib", name)
-        if os.path.exists(path):
-            try:
-                ctypes.CDLL(path, mode=ctypes.RTLD_GLOBAL)
-            except OSError:
-                return
-
-
 def hip_runtime_in_use() -> List[str]:
     """Paths of the HIP / HSA runtime libraries mapped into this process."""
     try:
@@ -115,7 +94,13 @@ def hip_runtime_in_use() -> List[str]:
 
 
 def _load() -> ctypes.CDLL:
-    _preload_system_rocm()
+    # One HIP runtime per process.  The PyTorch wheel bundles its own copy of
+    # libamdhip64 (soname libamdhip64.so.7, looked up by torch under the name
+    # libamdhip64.so); if this library were loaded first it would pull in the
+    # system copy and torch would then load a SECOND runtime, after which
+    # streams and pointers could not be shared.  Loading torch first makes the
+    # loader resolve this library's libamdhip64.so.7 to the copy torch brought.
+    import torch  # noqa: F401
     if not os.path.exists(LIB_PATH):
         raise ImportError(
             f"{LIB_PATH} is missing: build it first (python -m paper_2601_16956_amd.build, or "

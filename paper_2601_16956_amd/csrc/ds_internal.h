@@ -23,6 +23,22 @@ struct DsTile {
 };
 static_assert(sizeof(DsTile) == 128, "DsTile is one 128-byte line");
 
+// What the lean kernel needs to move one whole chunk, in one 32-byte load.
+// Chunks that are not "simple" (a tile boundary, the end of a payload or
+// padding inside the chunk, more than one outer dimension, rows whose length
+// is not a multiple of 16) are of kind DS_CHUNK_GENERAL and go to the general
+// kernel, which finds its tiles through first_tile[].
+enum : uint32_t { DS_CHUNK_CONTIG = 0, DS_CHUNK_ROWS = 1, DS_CHUNK_GENERAL = 2 };
+struct DsChunkRec {
+  uint64_t addr;   // CONTIG: tensor address of the chunk's first byte; ROWS: address of the run that holds it
+  uint64_t pitch;  // ROWS: distance between runs in bytes
+  uint32_t col0;   // ROWS: position of the chunk's first byte inside its run
+  uint32_t run;    // ROWS: run length in bytes (multiple of 16)
+  uint32_t kind;
+  uint32_t tile;
+};
+static_assert(sizeof(DsChunkRec) == 32, "two records per 64 bytes");
+
 struct DsManifestEntry {
   uint64_t tensor_id;
   uint32_t dtype;
@@ -41,12 +57,16 @@ struct ds_plan {
   std::vector<DsTile> tiles;               // image order
   std::vector<uint64_t> tile_off;          // n_tiles + 1 entries, last = total_bytes
   std::vector<uint32_t> first_tile;        // n_chunks + 1 entries, last = n_tiles
+  std::vector<DsChunkRec> recs;            // one per chunk
+  std::vector<uint32_t> general_ids;       // chunks of kind DS_CHUNK_GENERAL, ascending
   // device copies (one allocation)
   int device = -1;
   void *dev_blob = nullptr;
   const DsTile *d_tiles = nullptr;
   const uint64_t *d_tile_off = nullptr;
   const uint32_t *d_first_tile = nullptr;
+  const DsChunkRec *d_recs = nullptr;
+  const uint32_t *d_general_ids = nullptr;
   uint64_t n_chunks() const { return first_tile.empty() ? 0 : first_tile.size() - 1; }
 };
 

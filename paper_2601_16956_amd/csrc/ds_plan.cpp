@@ -14,7 +14,7 @@ namespace {
 
 thread_local int g_last_hip_error = 0;
 
-std::atomic<uint64_t> g_chunk_bytes{128u << 10};
+std::atomic<uint64_t> g_chunk_bytes{16u << 10};
 std::atomic<uint64_t> g_variant{0};
 
 inline bool is_pow2(uint64_t x) { return x && !(x & (x - 1)); }
@@ -111,7 +111,9 @@ int upload(ds_plan *p) {
   const size_t b_tiles = p->tiles.size() * sizeof(DsTile);
   const size_t b_off = round_up(p->tile_off.size() * sizeof(uint64_t), 128);
   const size_t b_first = round_up(p->first_tile.size() * sizeof(uint32_t), 128);
-  const size_t total = std::max<size_t>(b_tiles + b_off + b_first, 128);
+  const size_t b_recs = round_up(p->recs.size() * sizeof(DsChunkRec), 128);
+  const size_t b_gen = round_up(p->general_ids.size() * sizeof(uint32_t), 128);
+  const size_t total = std::max<size_t>(b_tiles + b_off + b_first + b_recs + b_gen, 128);
   DS_HIP_TRY(hipMalloc(&p->dev_blob, total));
   uint8_t *base = (uint8_t *)p->dev_blob;
   p->d_tiles = (const DsTile *)base;
@@ -122,6 +124,14 @@ int upload(ds_plan *p) {
                        hipMemcpyHostToDevice));
   DS_HIP_TRY(hipMemcpy(base + b_tiles + b_off, p->first_tile.data(), p->first_tile.size() * sizeof(uint32_t),
                        hipMemcpyHostToDevice));
+  p->d_recs = (const DsChunkRec *)(base + b_tiles + b_off + b_first);
+  p->d_general_ids = (const uint32_t *)(base + b_tiles + b_off + b_first + b_recs);
+  if (!p->recs.empty())
+    DS_HIP_TRY(hipMemcpy(base + b_tiles + b_off + b_first, p->recs.data(), p->recs.size() * sizeof(DsChunkRec),
+                         hipMemcpyHostToDevice));
+  if (!p->general_ids.empty())
+    DS_HIP_TRY(hipMemcpy(base + b_tiles + b_off + b_first + b_recs, p->general_ids.data(),
+                         p->general_ids.size() * sizeof(uint32_t), hipMemcpyHostToDevice));
   return DS_OK;
 }
 
@@ -167,7 +177,7 @@ const char *ds_strerror(int code) {
 int ds_config_set(const char *key, uint64_t value) {
   if (!key) return DS_EINVAL;
   if (!std::strcmp(key, "chunk_bytes")) {
-    if (!is_pow2(value) || value < 4096 || value > (4u << 20)) return DS_EINVAL;
+    if (value != (8u << 10) && value != (16u << 10) && value != (32u << 10) && value != (64u << 10)) return DS_EINVAL;
     g_chunk_bytes.store(value);
     return DS_OK;
   }
@@ -272,6 +282,34 @@ int ds_plan_create(const ds_shard_desc *desc, size_t n, uint64_t align, uint32_t
             p->first_tile[c] = (uint32_t)t;
           }
           p->first_tile[n_chunks] = (uint32_t)p->tiles.size();
+          // classify every chunk for the lean kernel
+          p->recs.resize(n_chunks);
+          for (uint64_t c = 0; c < n_chunks; ++c) {
+            DsChunkRec &r = p->recs[c];
+            std::memset(&r, 0, sizeof(r));
+            const uint64_t cb = c << p->chunk_log2, ce = cb + chunk;
+            const uint32_t ti = p->first_tile[c];
+            const DsTile &tl = p->tiles[ti];
+            const uint64_t tb = p->tile_off[ti];
+            r.tile = ti;
+            r.kind = DS_CHUNK_GENERAL;
+            // simple = the whole chunk is whole 16-byte units of ONE tile's payload
+            if (ce <= p->total_bytes && ce <= tb + (tl.nbytes & ~(uint64_t)15)) {
+              const uint64_t b0 = cb - tb;
+              if (tl.n_outer == 0) {
+                r.kind = DS_CHUNK_CONTIG;
+                r.addr = tl.src + b0;
+              } else if (tl.n_outer == 1 && (tl.run_bytes & 15) == 0 && tl.run_bytes < ((uint64_t)1 << 31)) {
+                const uint64_t row0 = b0 / tl.run_bytes;
+                r.kind = DS_CHUNK_ROWS;
+                r.addr = tl.src + row0 * tl.stride[0];
+                r.pitch = tl.stride[0];
+                r.col0 = (uint32_t)(b0 - row0 * tl.run_bytes);
+                r.run = (uint32_t)tl.run_bytes;
+              }
+            }
+            if (r.kind == DS_CHUNK_GENERAL) p->general_ids.push_back((uint32_t)c);
+          }
         }
       }
     }

@@ -7,11 +7,6 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-try:  # before anything imports torch (see the binding's _preload_system_rocm)
-    import paper_2601_16956_amd  # noqa: F401
-except ImportError:
-    pass  # not built yet: the oracle's own tests still run
-
 
 def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")

@@ -63,8 +63,8 @@ def test_unpack_matches_oracle(name):
         dw.close()
 
 
-@pytest.mark.parametrize("chunk_bytes", [4096, 65536, 1 << 20])
-@pytest.mark.parametrize("variant", [0, 1, 2, 3])
+@pytest.mark.parametrize("chunk_bytes", [8192, 16384, 32768, 65536])
+@pytest.mark.parametrize("variant", [0, 1])
 def test_chunk_sizes_and_kernel_variants(chunk_bytes, variant):
     ds, orc, gu = _mods()
     w = W.fragmentation(1500, max_bytes=1 << 19, seed=77)

@@ -130,8 +130,8 @@ def test_host_only_plan_cannot_be_packed():
 
 
 def test_config_keys():
-    assert ds.ds_config_get("chunk_bytes") == 128 << 10
-    for bad in (1000, 2048, 8 << 20):
+    assert ds.ds_config_get("chunk_bytes") == 16 << 10
+    for bad in (1000, 4096, 128 << 10):
         with pytest.raises(ds.DsError):
             ds.ds_config_set("chunk_bytes", bad)
     with pytest.raises(ds.DsError):
@@ -142,4 +142,4 @@ def test_config_keys():
     plan = ds.ds_plan_create(d, 1, 64, ds.DS_PLAN_HOST_ONLY)
     assert ds.ds_plan_info(plan)["n_chunks"] == 16
     ds.ds_plan_destroy(plan)
-    ds.ds_config_set("chunk_bytes", 128 << 10)
+    ds.ds_config_set("chunk_bytes", 16 << 10)
