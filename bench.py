@@ -3,10 +3,12 @@
 
 A step = one lazy snapshot of one rank's state: request on the compute stream,
 gather into device staging, chunked copies into the pinned host ring, and the
-gate before the (here empty) update phase.  Steps are issued the way a training
-loop checkpointing every iteration issues them: back to back, each gated, the
-engine pipelining the gather of step i+1 under the copies of step i.  The
-inputs are resident in HBM before the timed region.
+gate before the (here empty) update phase; the step ends when the whole image
+is resident in the host ring.  Steps run one after the other, so the gather
+kernel of a step runs alone on the GPU (as it does in training, where an
+iteration is longer than a snapshot).  `pipelined_GBps` reports the same loop
+without the per-step wait (the gather of step i+1 under the copies of step i).
+The inputs are resident in HBM before the timed region.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload llama7b]
 
@@ -54,9 +56,14 @@ def main() -> int:
     ap.add_argument("--stage-slot-bytes", type=int, default=2 * GiB, help="device staging slot = bytes per gather launch")
     ap.add_argument("--stage-slots", type=int, default=2)
     ap.add_argument("--copy-streams", type=int, default=1)
+    ap.add_argument("--first-launch-bytes", type=int, default=0, help="short first gather launch (0 = none)")
     ap.add_argument("--no-overlap", action="store_true", help="skip the concurrent-GEMM leg (configs[4])")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--gemm-iters", type=int, default=12, help="iterations of the overlap leg")
+    ap.add_argument("--timed-only", action="store_true",
+                    help="stop after the timed region (so that a kernel trace holds the timed launches only)")
+    ap.add_argument("--kernels-only", action="store_true",
+                    help="only gather, scatter and the copy probe, 5 launches each (for counter runs)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         log("bench.py: this build is the one-GPU hot path; it has no multi-GPU leg (run with --gpus 1).")
@@ -90,6 +97,21 @@ def main() -> int:
     payload = info["payload_bytes"]
     stream = torch.cuda.current_stream().cuda_stream
 
+    if args.kernels_only:
+        image_dev = torch.empty(max(total, 16), dtype=torch.uint8, device=dev)
+        copy_src = torch.empty_like(image_dev)
+        for _ in range(5):
+            ds.ds_pack(plan, image_dev.data_ptr(), 0, total, stream)
+        for _ in range(5):
+            ds.ds_copy_probe(image_dev.data_ptr(), copy_src.data_ptr(), total & ~15, stream)
+        for _ in range(5):
+            ds.ds_unpack(plan, image_dev.data_ptr(), 0, total, stream)
+        torch.cuda.synchronize()
+        ds.ds_plan_destroy(plan)
+        print(json.dumps({"kernels_only": True, "workload": args.workload, "image_bytes": total,
+                          "payload_bytes": payload, "copy_probe_bytes": total & ~15}), flush=True)
+        return 0
+
     # ---- measured link peak: best of 10 x 1 GiB contiguous device -> pinned host -------------
     probe_dev = torch.empty(GiB, dtype=torch.uint8, device=dev).random_(0, 255)
     probe_host = torch.empty(GiB, dtype=torch.uint8, pin_memory=True)
@@ -107,13 +129,15 @@ def main() -> int:
 
     # ---- the timed region: K snapshots, back to back, each gated ------------------------------
     eng = ds.ds_engine_create(args.ring_bytes, args.chunk_bytes, args.stage_slot_bytes, args.stage_slots, 0,
-                              ds.DS_ENGINE_AUTO_RELEASE, args.copy_streams)
+                              ds.DS_ENGINE_AUTO_RELEASE, args.copy_streams, args.first_launch_bytes)
 
-    def run_steps(k):
+    def run_steps(k, pipelined=False):
         evs = []
         for _ in range(k):
             ev = ds.ds_snapshot_async(eng, plan, stream)
             ds.ds_event_wait_on_stream(ev, stream)       # gate before the (empty) update phase
+            if not pipelined:
+                ds.ds_event_wait(ev)                     # the whole image is in the host ring
             evs.append(ev)
         for ev in evs:
             ds.ds_event_wait(ev)
@@ -139,6 +163,34 @@ def main() -> int:
     ms_per_step = elapsed * 1e3 / args.steps
     value = payload * args.steps / elapsed / 1e9
 
+    # algorithmic bytes of one gather launch: every payload byte read once, every image byte
+    # (payload + padding) written once
+    algo_bytes = payload + total
+    achieved = algo_bytes * args.steps / (pack_ms * 1e-3) / 1e9 if pack_ms > 0 else 0.0
+    # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (scaled by what the same
+    # counters read for ds_copy_probe): taken from the committed summary of that run, if there is one
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", f"pmc_traffic_{args.workload}.md")
+    if os.path.exists(tpath):
+        import re
+        m = re.search(r"traffic_bytes_per_launch\s*=\s*(\d+)", open(tpath).read())
+        traffic = int(m.group(1)) if m else None
+    roofline = {
+        "bound": "hbm", "kernel": "ds_lean_kernel<pack> (+ ds_move_kernel<pack> on the chunks it leaves)",
+        "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+        "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic,
+        "launches": launches, "avg_launch_ms": round(pack_ms / max(launches, 1), 4),
+        "algorithmic_bytes_per_launch": algo_bytes * args.steps // max(launches, 1),
+    }
+    if args.timed_only:
+        ds.ds_engine_destroy(eng)
+        ds.ds_plan_destroy(plan)
+        print(json.dumps({"metric": "snapshot GB/s/GPU (pack+D2H to pinned host)", "value": round(value, 3),
+                          "unit": "GB/s", "steps": args.steps, "warmup": args.warmup,
+                          "ms_per_step": round(ms_per_step, 3), "workload": args.workload, "timed_only": True,
+                          "roofline": roofline}), flush=True)
+        return 0
+
     # one isolated snapshot: request -> whole image resident in the host ring
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -147,6 +199,15 @@ def main() -> int:
     latency_ms = (time.perf_counter() - t0) * 1e3
     one = ds.ds_event_stats(ev)
     ds.ds_event_destroy(ev)
+
+    # the same steps without the per-step wait
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    pevs = run_steps(args.steps, pipelined=True)
+    torch.cuda.synchronize()
+    pipelined_gbps = payload * args.steps / (time.perf_counter() - t0) / 1e9
+    for ev in pevs:
+        ds.ds_event_destroy(ev)
 
     # ---- gather and scatter alone, whole image, device to device ------------------------------
     image_dev = torch.empty(max(total, 16), dtype=torch.uint8, device=dev)
@@ -169,7 +230,8 @@ def main() -> int:
     pack_med, pack_best = timed(lambda: ds.ds_pack(plan, image_dev.data_ptr(), 0, total, stream))
     unpack_med, unpack_best = timed(lambda: ds.ds_unpack(plan, image_dev.data_ptr(), 0, total, stream))
     copy_src = torch.empty_like(image_dev)
-    d2d_med, _ = timed(lambda: image_dev.copy_(copy_src))
+    nprobe = total & ~15
+    probe_med, probe_best = timed(lambda: ds.ds_copy_probe(image_dev.data_ptr(), copy_src.data_ptr(), nprobe, stream))
     del copy_src
 
     # ---- parity of this very run against the CPU oracle + the CPU baseline --------------------
@@ -271,17 +333,6 @@ def main() -> int:
     torch.cuda.synchronize()
     ds.ds_plan_destroy(plan)
 
-    # algorithmic bytes of one gather launch: every payload byte read once, every image byte
-    # (payload + padding) written once
-    algo_bytes = payload + total
-    achieved = algo_bytes * args.steps / (pack_ms * 1e-3) / 1e9 if pack_ms > 0 else 0.0
-    traffic = None
-    tpath = os.path.join(ROOT, "profiles", "traffic.json")
-    if os.path.exists(tpath):
-        try:
-            traffic = json.load(open(tpath)).get(args.workload)
-        except Exception:
-            traffic = None
     out = {
         "metric": "snapshot GB/s/GPU (pack+D2H to pinned host)",
         "value": round(value, 3), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -292,20 +343,17 @@ def main() -> int:
             "image_bytes": total, "shards": n, "align": w.align, "host_ring_bytes": args.ring_bytes,
             "d2h_chunk_bytes": args.chunk_bytes, "stage_slot_bytes": args.stage_slot_bytes,
             "stage_slots": args.stage_slots, "copy_streams": args.copy_streams,
+            "first_launch_bytes": args.first_launch_bytes,
             "workgroup_chunk_bytes": info["chunk_bytes"],
         },
-        "roofline": {
-            "bound": "hbm", "kernel": "ds_move_kernel<pack>", "achieved": round(achieved, 1),
-            "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic,
-            "launches": launches, "avg_launch_ms": round(pack_ms / max(launches, 1), 4),
-            "algorithmic_bytes_per_step": algo_bytes,
-        },
+        "roofline": roofline,
         "cpu_baseline": cpu_baseline,
         "parity": parity,
         "d2h": {"achieved_GBps": round(total * args.steps / (copy_ms * 1e-3) / 1e9, 2),
                 "link_peak_measured_GBps": round(link_best, 2),
                 "frac": round(total * args.steps / (copy_ms * 1e-3) / 1e9 / link_best, 4)},
         "snapshot_latency_ms": round(latency_ms, 3),
+        "pipelined_GBps": round(pipelined_gbps, 3),
         "capture_ms": round(capture_ms / args.steps, 3),          # request -> tensors may be mutated
         "submit_host_ms": round(submit_ms / args.steps, 4),       # host time inside ds_snapshot_async
         "plan_create_ms": round(plan_ms, 3),
@@ -313,7 +361,8 @@ def main() -> int:
             "pack_ms": round(pack_med, 4), "pack_GBps": round(algo_bytes / pack_med / 1e6, 1),
             "pack_best_GBps": round(algo_bytes / pack_best / 1e6, 1),
             "unpack_ms": round(unpack_med, 4), "unpack_GBps": round(2 * payload / unpack_med / 1e6, 1),
-            "torch_d2d_copy_GBps": round(2 * total / d2d_med / 1e6, 1),
+            "copy_probe_GBps": round(2 * nprobe / probe_med / 1e6, 1),    # plain copy, same shape: the ceiling
+            "pack_vs_copy_probe": round((algo_bytes / pack_med) / (2 * nprobe / probe_med), 4),
         },
         "overlap": overlap,
         "hip_runtime": ds.hip_runtime_in_use(),

@@ -173,6 +173,10 @@ typedef struct ds_engine_opts {
   uint32_t pack_grid_limit;  /* max work-groups resident per gather launch; 0 = one per chunk       */
   uint32_t flags;            /* DS_ENGINE_*                                                         */
   uint32_t copy_streams;     /* copy streams the chunks alternate over: 1 or 2.  0 = 1              */
+  uint64_t first_launch_bytes; /* image bytes of the first gather launch of a snapshot; multiple of
+                                d2h_chunk_bytes, <= stage_slot_bytes.  A short first launch lets the
+                                first copy start earlier; the gather of the rest then runs beside that
+                                copy.  0 = stage_slot_bytes (no short first launch)                  */
 } ds_engine_opts;
 
 /* Allocates the pinned ring, the device staging slots, two side streams
@@ -253,9 +257,20 @@ const char *ds_strerror(int code);
 int ds_last_hip_error(void);
 
 /*
+ * Measurement aid, not part of the method: a plain contiguous device-to-device
+ * copy of nbytes (multiple of 16; both pointers 16-byte aligned, device
+ * memory, not overlapping) with the same launch shape and memory instructions
+ * as the gather kernel.  It gives the HBM rate a pure copy reaches on this
+ * GPU, against which the gather is reported, and a kernel of known traffic to
+ * scale hardware byte counters with.  Asynchronous on `stream`.
+ * Errors: DS_EINVAL, DS_ERANGE, DS_EHIP.
+ */
+int ds_copy_probe(void *dst_dev, const void *src_dev, uint64_t nbytes, void *stream);
+
+/*
  * Tunables for experiments, read when a plan is created / a kernel launched:
- *   "chunk_bytes"   image bytes per work-group chunk (power of two, 4 KiB..4 MiB)
- *   "variant"       gather/scatter kernel variant (see ds_kernels.hip)
+ *   "chunk_bytes"   image bytes per work-group chunk: 8, 16 (default), 32 or 64 KiB
+ *   "variant"       0 = non-temporal loads and stores (default), 1 = plain
  * Returns DS_EINVAL for an unknown key or a value out of range.
  */
 int ds_config_set(const char *key, uint64_t value);

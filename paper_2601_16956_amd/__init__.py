@@ -28,7 +28,7 @@ EXPORTS = [
     "ds_pack", "ds_unpack", "ds_engine_create", "ds_engine_destroy", "ds_snapshot_async",
     "ds_event_wait_on_stream", "ds_event_wait_captured", "ds_event_query", "ds_event_wait",
     "ds_snapshot_next_chunk", "ds_snapshot_release_chunk", "ds_event_stats", "ds_event_destroy",
-    "ds_strerror", "ds_last_hip_error", "ds_config_set", "ds_config_get",
+    "ds_strerror", "ds_last_hip_error", "ds_config_set", "ds_config_get", "ds_copy_probe",
 ]
 
 
@@ -58,6 +58,7 @@ class ds_engine_opts(ctypes.Structure):
         ("pack_grid_limit", ctypes.c_uint32),
         ("flags", ctypes.c_uint32),
         ("copy_streams", ctypes.c_uint32),
+        ("first_launch_bytes", ctypes.c_uint64),
     ]
 
 
@@ -132,6 +133,7 @@ def _load() -> ctypes.CDLL:
         "ds_last_hip_error": ([], ctypes.c_int),
         "ds_config_set": ([ctypes.c_char_p, u64], ctypes.c_int),
         "ds_config_get": ([ctypes.c_char_p, P(u64)], ctypes.c_int),
+        "ds_copy_probe": ([vp, vp, u64, vp], ctypes.c_int),
     }
     for name, (args, res) in sig.items():
         fn = getattr(L, name)
@@ -214,9 +216,10 @@ def ds_unpack(plan: int, src_dev: int, img_lo: int, img_hi: int, stream: int = 0
 
 
 def ds_engine_create(host_ring_bytes: int = 0, d2h_chunk_bytes: int = 0, stage_slot_bytes: int = 0,
-                     stage_slots: int = 0, pack_grid_limit: int = 0, flags: int = 0, copy_streams: int = 0) -> int:
+                     stage_slots: int = 0, pack_grid_limit: int = 0, flags: int = 0, copy_streams: int = 0,
+                     first_launch_bytes: int = 0) -> int:
     opts = ds_engine_opts(host_ring_bytes, d2h_chunk_bytes, stage_slot_bytes, stage_slots, pack_grid_limit, flags,
-                          copy_streams)
+                          copy_streams, first_launch_bytes)
     out = ctypes.c_void_p(0)
     _check(_lib.ds_engine_create(ctypes.byref(opts), ctypes.byref(out)), "ds_engine_create")
     return int(out.value)
@@ -288,3 +291,7 @@ def ds_config_get(key: str) -> int:
     v = ctypes.c_uint64(0)
     _check(_lib.ds_config_get(key.encode(), ctypes.byref(v)), f"ds_config_get({key})")
     return int(v.value)
+
+
+def ds_copy_probe(dst_dev: int, src_dev: int, nbytes: int, stream: int = 0) -> None:
+    _check(_lib.ds_copy_probe(dst_dev, src_dev, nbytes, stream), "ds_copy_probe")

@@ -6,9 +6,9 @@
 // Data path of one snapshot, image bytes [0, T):
 //
 //   compute stream --E_requested--> gather stream: one gather launch per staging
-//   slot (the first launch covers just the first copy chunk so that the link
-//   starts working at once)  --E_packed--> copy stream(s): one hipMemcpyAsync per
-//   ring slot, device staging -> pinned ring  --E_done[slot]--> consumer.
+//   slot (optionally a shorter first launch, so that the link starts working
+//   sooner)  --E_packed--> copy stream(s): one hipMemcpyAsync per ring slot,
+//   device staging -> pinned ring  --E_done[slot]--> consumer.
 //
 // The caller's stream is touched twice only: the record at the request and the
 // wait at the gate.  The gate waits for the LAST GATHER, not for the last
@@ -37,6 +37,7 @@ struct ds_engine {
   uint32_t grid_limit = 0;
   uint64_t chunk_bytes = 0;       // ring slot = one copy
   uint64_t stage_slot_bytes = 0;  // image bytes per gather launch
+  uint64_t first_launch_bytes = 0; // image bytes of the first gather launch of a snapshot
   uint32_t stage_slots = 0;
   uint32_t ring_slots = 0;
   int n_copy_streams = 1;
@@ -109,8 +110,8 @@ int issue_snapshot(ds_engine *g, ds_event *ev) {
   struct Group { uint64_t lo, hi; uint32_t slot; };
   std::vector<Group> groups;
   for (uint64_t at = 0; at < T;) {
-    // the first launch is one copy chunk long, the others fill a staging slot
-    const uint64_t want = groups.empty() ? g->chunk_bytes : g->stage_slot_bytes;
+    // the first launch may be shorter than a staging slot (first_launch_bytes)
+    const uint64_t want = groups.empty() ? g->first_launch_bytes : g->stage_slot_bytes;
     const uint64_t hi = at + want < T ? at + want : T;
     groups.push_back({at, hi, (uint32_t)(g->groups_issued++ % g->stage_slots)});
     at = hi;
@@ -277,7 +278,9 @@ int ds_engine_create(const ds_engine_opts *o, ds_engine **out) {
   const uint64_t slot = o->stage_slot_bytes ? o->stage_slot_bytes : (1ull << 30);
   const uint32_t slots = o->stage_slots ? o->stage_slots : 2;
   const uint32_t ncs = o->copy_streams ? o->copy_streams : 1;
-  if ((chunk & 4095) || slot % chunk || ring_bytes < chunk || ncs > (uint32_t)kMaxCopyStreams || slots > 1024)
+  const uint64_t first = o->first_launch_bytes ? o->first_launch_bytes : slot;
+  if ((chunk & 4095) || slot % chunk || first % chunk || first > slot || ring_bytes < chunk ||
+      ncs > (uint32_t)kMaxCopyStreams || slots > 1024)
     return DS_EINVAL;
   ds_engine *g = new (std::nothrow) ds_engine;
   if (!g) return DS_ENOMEM;
@@ -285,6 +288,7 @@ int ds_engine_create(const ds_engine_opts *o, ds_engine **out) {
   g->grid_limit = o->pack_grid_limit;
   g->chunk_bytes = chunk;
   g->stage_slot_bytes = slot;
+  g->first_launch_bytes = first;
   g->stage_slots = slots;
   g->ring_slots = (uint32_t)(ring_bytes / chunk);
   g->n_copy_streams = (int)ncs;
@@ -364,7 +368,7 @@ int ds_snapshot_async(ds_engine *g, const ds_plan *plan, void *compute_stream, d
     uint64_t at = 0, k = 0;
     uint32_t group = 0;
     while (at < T) {
-      const uint64_t want = group == 0 ? g->chunk_bytes : g->stage_slot_bytes;
+      const uint64_t want = group == 0 ? g->first_launch_bytes : g->stage_slot_bytes;
       const uint64_t hi = at + want < T ? at + want : T;
       for (uint64_t lo = at; lo < hi; lo += g->chunk_bytes, ++k) {
         ev->chunks[k].file_off = lo;

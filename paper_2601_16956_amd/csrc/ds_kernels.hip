@@ -430,7 +430,34 @@ int launch_both(const ds_plan *plan, const LeanArgs &la, const MoveArgs &ma, uin
   return DS_OK;
 }
 
+// A plain contiguous copy in the lean kernel's shape (256 threads x 4 units per
+// work-group, non-temporal 16-byte accesses): the measured ceiling the gather
+// is compared with, and the known-size kernel the HBM counters are scaled by.
+__global__ __launch_bounds__(256) void ds_copy_probe_kernel(const u32x4 *__restrict__ src, u32x4 *__restrict__ dst,
+                                                            uint64_t n_units) {
+  const uint64_t base = (uint64_t)blockIdx.x * 1024 + threadIdx.x;
+  u32x4 v[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+    if (base + 256 * i < n_units) v[i] = __builtin_nontemporal_load(src + base + 256 * i);
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+    if (base + 256 * i < n_units) __builtin_nontemporal_store(v[i], dst + base + 256 * i);
+}
+
 }  // namespace
+
+extern "C" int ds_copy_probe(void *dst_dev, const void *src_dev, uint64_t nbytes, void *stream) {
+  if (nbytes == 0) return DS_OK;
+  if (!dst_dev || !src_dev || (((uintptr_t)dst_dev | (uintptr_t)src_dev | nbytes) & 15)) return DS_EINVAL;
+  const uint64_t n_units = nbytes >> 4;
+  const uint64_t grid = (n_units + 1023) / 1024;
+  if (grid > 0x7FFFFFFFull) return DS_ERANGE;
+  hipLaunchKernelGGL(ds_copy_probe_kernel, dim3((uint32_t)grid), dim3(256), 0, (hipStream_t)stream,
+                     (const u32x4 *)src_dev, (u32x4 *)dst_dev, n_units);
+  DS_HIP_TRY(hipGetLastError());
+  return DS_OK;
+}
 
 int ds_launch_move(const ds_plan *plan, bool pack, uint8_t *img, uint64_t img_lo, uint64_t img_hi,
                    uint32_t grid_limit, hipStream_t stream) {

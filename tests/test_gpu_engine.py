@@ -52,6 +52,7 @@ def _drain(ds, ev, total, delay=0.0, hold=1):
     dict(ring=2 * MiB, chunk=1 * MiB, slot=1 * MiB, slots=1, copy_streams=1),
     dict(ring=8 * MiB, chunk=2 * MiB, slot=8 * MiB, slots=3, copy_streams=2),
     dict(ring=64 * MiB, chunk=32 * MiB, slot=64 * MiB, slots=1, copy_streams=1),   # image fits one slot
+    dict(ring=8 * MiB, chunk=1 * MiB, slot=8 * MiB, slots=2, copy_streams=1, first=1 * MiB),  # short first launch
 ])
 def test_snapshot_with_consumer_matches_oracle(cfg):
     ds, orc, gu, torch = _mods()
@@ -59,7 +60,8 @@ def test_snapshot_with_consumer_matches_oracle(cfg):
     print(f"[case] snapshot consumer {cfg}", flush=True)
     want, _, _ = gu.oracle_image(w)
     dw = gu.DeviceWorkload(w)
-    eng = ds.ds_engine_create(cfg["ring"], cfg["chunk"], cfg["slot"], cfg["slots"], 0, 0, cfg["copy_streams"])
+    eng = ds.ds_engine_create(cfg["ring"], cfg["chunk"], cfg["slot"], cfg["slots"], 0, 0, cfg["copy_streams"],
+                              cfg.get("first", 0))
     try:
         for rep in range(2):                                  # the second run reuses ring, staging, events
             ev = ds.ds_snapshot_async(eng, dw.plan, torch.cuda.current_stream().cuda_stream)
@@ -184,7 +186,8 @@ def test_auto_release_and_state_errors():
         ds.ds_engine_destroy(eng)
         dw.close()
     for bad in [dict(d2h_chunk_bytes=1000), dict(d2h_chunk_bytes=MiB, stage_slot_bytes=MiB + 4096),
-                dict(host_ring_bytes=MiB, d2h_chunk_bytes=2 * MiB), dict(copy_streams=3)]:
+                dict(host_ring_bytes=MiB, d2h_chunk_bytes=2 * MiB), dict(copy_streams=3),
+                dict(d2h_chunk_bytes=MiB, stage_slot_bytes=4 * MiB, first_launch_bytes=8 * MiB)]:
         with pytest.raises(ds.DsError) as e:
             ds.ds_engine_create(**bad)
         assert e.value.code == ds.DS_EINVAL
