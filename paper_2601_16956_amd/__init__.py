@@ -46,7 +46,8 @@ class ds_shard_desc(ctypes.Structure):
 
 class ds_plan_stats(ctypes.Structure):
     _fields_ = [(n, ctypes.c_uint64) for n in (
-        "total_bytes", "payload_bytes", "n_shards", "n_tiles", "n_chunks", "chunk_bytes", "n_strided", "align")]
+        "total_bytes", "payload_bytes", "n_shards", "n_tiles", "n_chunks", "chunk_bytes", "n_strided", "align",
+        "n_general_chunks")]
 
 
 class ds_engine_opts(ctypes.Structure):

@@ -25,16 +25,16 @@ static_assert(sizeof(DsTile) == 128, "DsTile is one 128-byte line");
 
 // What the lean kernel needs to move one whole chunk, in one 32-byte load.
 // Chunks that are not "simple" (a tile boundary, the end of a payload or
-// padding inside the chunk, more than one outer dimension, rows whose length
-// is not a multiple of 16) are of kind DS_CHUNK_GENERAL and go to the general
-// kernel, which finds its tiles through first_tile[].
+// padding inside the chunk, more than one outer dimension, rows shorter than
+// 16 bytes) are of kind DS_CHUNK_GENERAL and go to the general kernel, which
+// finds its tiles through first_tile[].
 enum : uint32_t { DS_CHUNK_CONTIG = 0, DS_CHUNK_ROWS = 1, DS_CHUNK_GENERAL = 2 };
 struct DsChunkRec {
   uint64_t addr;   // CONTIG: tensor address of the chunk's first byte; ROWS: address of the run that holds it
   uint64_t pitch;  // ROWS: distance between runs in bytes
   uint32_t col0;   // ROWS: position of the chunk's first byte inside its run
-  uint32_t run;    // ROWS: run length in bytes (multiple of 16)
-  uint32_t kind;
+  uint32_t run;    // ROWS: run length in bytes (>= 16, multiple of the itemsize)
+  uint32_t kind;   // low byte: DS_CHUNK_*; bits 8..: log2(itemsize) (ROWS)
   uint32_t tile;
 };
 static_assert(sizeof(DsChunkRec) == 32, "two records per 64 bytes");

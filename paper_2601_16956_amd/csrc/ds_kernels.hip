@@ -19,8 +19,8 @@
 //   needs for a chunk is one 32-byte record prepared by the plan (DsChunkRec),
 //   so the only dependent load before the data is that record.  It handles the
 //   chunks that are whole units of one tile (contiguous, or rows of a 2-D view
-//   whose length is a multiple of 16); it is small on purpose (few registers,
-//   full occupancy).
+//   of at least 16 bytes each); it is small on purpose (few registers, full
+//   occupancy).
 //
 // ds_move_kernel: the general routine, run over the list of the remaining
 //   chunks (tile boundaries, payload tails, padding, odd row lengths, N-D):
@@ -365,16 +365,58 @@ __global__ __launch_bounds__(NT) void ds_move_kernel(MoveArgs a) {
 }
 
 // ---- the lean kernel ----------------------------------------------------------
+// bytes [s, s+16) of the 32 bytes a||b, 0 < s < 16
+__device__ __forceinline__ u32x4 splice(u32x4 a, u32x4 b, uint32_t s) {
+  uint64_t x0 = a.x | ((uint64_t)a.y << 32), x1 = a.z | ((uint64_t)a.w << 32);
+  uint64_t x2 = b.x | ((uint64_t)b.y << 32), x3 = b.z | ((uint64_t)b.w << 32);
+  if (s >= 8) {
+    x0 = x1;
+    x1 = x2;
+    x2 = x3;
+    s -= 8;
+  }
+  uint64_t r0 = x0, r1 = x1;
+  if (s) {
+    const uint32_t sh = 8 * s;
+    r0 = (x0 >> sh) | (x1 << (64 - sh));
+    r1 = (x1 >> sh) | (x2 << (64 - sh));
+  }
+  return u32x4{(uint32_t)r0, (uint32_t)(r0 >> 32), (uint32_t)r1, (uint32_t)(r1 >> 32)};
+}
+
+// bytes [0,k) of v go to p0, bytes [k,16) to p1; element by element (k is a multiple of the itemsize)
+template <int ES>
+__device__ __forceinline__ void store_cut_es(uint8_t *p0, uint8_t *p1, uint32_t k, const Unit &u) {
+  typedef typename ElemType<ES>::type E;
+#pragma unroll
+  for (int e = 0; e < 16 / ES; ++e) {
+    const uint32_t byte = e * ES;
+    uint8_t *dst = byte < k ? p0 + byte : p1 + (byte - k);
+    *reinterpret_cast<E *>(dst) = unit_get<ES>(u, e);
+  }
+}
+__device__ __forceinline__ void store_cut(uint8_t *p0, uint8_t *p1, uint32_t k, uint32_t es_log2, u32x4 v) {
+  Unit u;
+  u.q = v;
+  switch (es_log2) {
+    case 0: store_cut_es<1>(p0, p1, k, u); break;
+    case 1: store_cut_es<2>(p0, p1, k, u); break;
+    case 2: store_cut_es<4>(p0, p1, k, u); break;
+    default: store_cut_es<8>(p0, p1, k, u); break;
+  }
+}
+
 template <bool PACK, int NT, int UNROLL, bool NTL, bool NTS>
 __global__ __launch_bounds__(NT) void ds_lean_kernel(LeanArgs a) {
   const uint32_t tid = threadIdx.x;
   for (uint32_t ci = blockIdx.x; ci < a.n_chunks; ci += gridDim.x) {
     const uint32_t c = a.c_lo + ci;
     const DsChunkRec r = a.recs[c];
-    if (r.kind == DS_CHUNK_GENERAL) continue;
+    const uint32_t kind = r.kind & 0xFF;  // bits 8.. hold log2(itemsize)
+    if (kind == DS_CHUNK_GENERAL) continue;
     uint8_t *imgp = a.img + (((uint64_t)c << a.chunk_log2) - a.img_lo);
     u32x4 v[UNROLL];
-    if (r.kind == DS_CHUNK_CONTIG) {
+    if (kind == DS_CHUNK_CONTIG) {
       uint8_t *s = reinterpret_cast<uint8_t *>(r.addr);
 #pragma unroll
       for (int i = 0; i < UNROLL; ++i) {
@@ -387,21 +429,45 @@ __global__ __launch_bounds__(NT) void ds_lean_kernel(LeanArgs a) {
         if (PACK) st16_aligned<NTS>(imgp + off, v[i]);
         else st16_any<NTS>(s + off, v[i]);
       }
-    } else {  // DS_CHUNK_ROWS: run length is a multiple of 16, so no unit is cut by the end of a run
+    } else {
+      // DS_CHUNK_ROWS: runs of r.run >= 16 bytes, r.pitch apart.  A unit that lies in one
+      // run is one access.  A unit cut by the end of a run takes its first k bytes from
+      // the end of that run and the other 16-k from the start of the next one; on the
+      // gather side both come from 16-byte loads that lie wholly inside their runs
+      // (the last 16 bytes of the one, the first 16 of the other), so nothing outside
+      // the view is read; on the scatter side the two parts are stored element by
+      // element.
       uint8_t *p[UNROLL];
+      uint32_t cut[UNROLL];  // k, or 0 if the unit is not cut
 #pragma unroll
       for (int i = 0; i < UNROLL; ++i) {
         const uint32_t off = 16u * (i * NT + tid);
         const uint32_t tt = r.col0 + off;  // < 2^31 + 2^16
         const uint32_t q = tt / r.run;
-        p[i] = reinterpret_cast<uint8_t *>(r.addr + (uint64_t)q * r.pitch + (tt - q * r.run));
-        v[i] = PACK ? ld16_any<NTL>(p[i]) : ld16_aligned<NTL>(imgp + off);
+        const uint32_t col = tt - q * r.run;
+        uint8_t *row = reinterpret_cast<uint8_t *>(r.addr + (uint64_t)q * r.pitch);
+        p[i] = row + col;
+        cut[i] = col + 16u > r.run ? r.run - col : 0u;
+        if (PACK) {
+          if (cut[i] == 0) {
+            v[i] = ld16_any<NTL>(p[i]);
+          } else {
+            v[i] = splice(ld16_any<NTL>(row + r.run - 16u), ld16_any<NTL>(row + r.pitch), 16u - cut[i]);
+          }
+        } else {
+          v[i] = ld16_aligned<NTL>(imgp + off);
+        }
       }
 #pragma unroll
       for (int i = 0; i < UNROLL; ++i) {
         const uint32_t off = 16u * (i * NT + tid);
-        if (PACK) st16_aligned<NTS>(imgp + off, v[i]);
-        else st16_any<NTS>(p[i], v[i]);
+        if (PACK) {
+          st16_aligned<NTS>(imgp + off, v[i]);
+        } else if (cut[i] == 0) {
+          st16_any<NTS>(p[i], v[i]);
+        } else {
+          store_cut(p[i], p[i] + cut[i] + (r.pitch - r.run), cut[i], r.kind >> 8, v[i]);
+        }
       }
     }
   }

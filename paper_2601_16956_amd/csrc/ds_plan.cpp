@@ -299,16 +299,16 @@ int ds_plan_create(const ds_shard_desc *desc, size_t n, uint64_t align, uint32_t
               if (tl.n_outer == 0) {
                 r.kind = DS_CHUNK_CONTIG;
                 r.addr = tl.src + b0;
-              } else if (tl.n_outer == 1 && (tl.run_bytes & 15) == 0 && tl.run_bytes < ((uint64_t)1 << 31)) {
+              } else if (tl.n_outer == 1 && tl.run_bytes >= 16 && tl.run_bytes < ((uint64_t)1 << 31)) {
                 const uint64_t row0 = b0 / tl.run_bytes;
-                r.kind = DS_CHUNK_ROWS;
+                r.kind = DS_CHUNK_ROWS | (tl.es_log2 << 8);
                 r.addr = tl.src + row0 * tl.stride[0];
                 r.pitch = tl.stride[0];
                 r.col0 = (uint32_t)(b0 - row0 * tl.run_bytes);
                 r.run = (uint32_t)tl.run_bytes;
               }
             }
-            if (r.kind == DS_CHUNK_GENERAL) p->general_ids.push_back((uint32_t)c);
+            if ((r.kind & 0xFF) == DS_CHUNK_GENERAL) p->general_ids.push_back((uint32_t)c);
           }
         }
       }
@@ -346,6 +346,7 @@ int ds_plan_info(const ds_plan *plan, ds_plan_stats *out) {
   out->n_chunks = plan->n_chunks();
   out->chunk_bytes = (uint64_t)1 << plan->chunk_log2;
   out->n_strided = plan->n_strided;
+  out->n_general_chunks = plan->general_ids.size();
   out->align = plan->align;
   return DS_OK;
 }
