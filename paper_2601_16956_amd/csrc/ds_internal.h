@@ -5,6 +5,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <mutex>
 #include <vector>
 
 #include "datastates.h"
@@ -67,6 +68,11 @@ struct ds_plan {
   const uint32_t *d_first_tile = nullptr;
   const DsChunkRec *d_recs = nullptr;
   const uint32_t *d_general_ids = nullptr;
+  // a side stream (default priority) on which the general kernel runs beside the lean one when it
+  // has a lot to do; fork/join events are reused, so enqueueing is serialised by side_mu
+  hipStream_t side_stream = nullptr;
+  hipEvent_t ev_fork = nullptr, ev_join = nullptr;
+  mutable std::mutex side_mu;
   uint64_t n_chunks() const { return first_tile.empty() ? 0 : first_tile.size() - 1; }
 };
 

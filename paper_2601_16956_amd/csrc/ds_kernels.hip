@@ -473,8 +473,24 @@ __global__ __launch_bounds__(NT) void ds_lean_kernel(LeanArgs a) {
   }
 }
 
+// The general kernel gets its own stream, beside the lean kernel, when it has this many chunks.
+constexpr uint32_t kSideStreamMinChunks = 1024;
+
 template <bool PACK, bool NTL, bool NTS>
 int launch_both(const ds_plan *plan, const LeanArgs &la, const MoveArgs &ma, uint32_t grid_limit, hipStream_t stream) {
+  // Both kernels touch disjoint chunks, so they may run at the same time.  The general kernel is
+  // latency-bound (few resident waves, a chain of table loads per chunk); beside the lean kernel its
+  // bubbles are filled.  Fork/join with events; plain in-order launches when it has little to do.
+  const bool fork = la.n_chunks && ma.n_chunks >= kSideStreamMinChunks && grid_limit == 0 && plan->side_stream;
+  std::unique_lock<std::mutex> lk(plan->side_mu, std::defer_lock);
+  if (fork) {
+    lk.lock();
+    DS_HIP_TRY(hipEventRecord(plan->ev_fork, stream));
+    DS_HIP_TRY(hipStreamWaitEvent(plan->side_stream, plan->ev_fork, 0));
+    hipLaunchKernelGGL((ds_move_kernel<PACK, 256, 4, NTL, NTS>), dim3(ma.n_chunks), dim3(256), 0, plan->side_stream, ma);
+    DS_HIP_TRY(hipGetLastError());
+    DS_HIP_TRY(hipEventRecord(plan->ev_join, plan->side_stream));
+  }
   if (la.n_chunks) {
     uint32_t grid = la.n_chunks;
     if (grid_limit && grid > grid_limit) grid = grid_limit;
@@ -487,7 +503,9 @@ int launch_both(const ds_plan *plan, const LeanArgs &la, const MoveArgs &ma, uin
     }
     DS_HIP_TRY(hipGetLastError());
   }
-  if (ma.n_chunks) {
+  if (fork) {
+    DS_HIP_TRY(hipStreamWaitEvent(stream, plan->ev_join, 0));
+  } else if (ma.n_chunks) {
     uint32_t grid = ma.n_chunks;
     if (grid_limit && grid > grid_limit) grid = grid_limit;
     hipLaunchKernelGGL((ds_move_kernel<PACK, 256, 4, NTL, NTS>), dim3(grid), dim3(256), 0, stream, ma);
