@@ -273,8 +273,38 @@ def main() -> int:
         same_r = all(np.array_equal(back[lo:lo + (1 << 28)], w.arena[lo:lo + (1 << 28)])
                      for lo in range(0, back.size, 1 << 28))
         parity += "; restore byte-exact" if same_r else "; restore MISMATCH"
+        # the same restore through the pipeline: host image -> ring slots -> staging -> scatter
+        arena.fill_(0xA5)
+        rev = ds.ds_restore_begin(eng, plan, stream)
+        while True:
+            slot = ds.ds_restore_next_slot(rev)
+            if slot is None:
+                break
+            ptr, off, ln = slot
+            ctypes.memmove(ptr, want[off:off + ln].ctypes.data, ln)
+            ds.ds_restore_submit(rev, ptr)
+        ds.ds_event_wait(rev)
+        ds.ds_event_destroy(rev)
+        back = arena.cpu().numpy()
+        same_p = all(np.array_equal(back[lo:lo + (1 << 28)], w.arena[lo:lo + (1 << 28)])
+                     for lo in range(0, back.size, 1 << 28))
+        parity += "; pipelined restore byte-exact" if same_p else "; pipelined restore MISMATCH"
         arena.copy_(keep)
         del keep, got, back, want
+
+    # restore pipeline rate with a null producer (slots submitted as they are: the link and the scatter)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    rev = ds.ds_restore_begin(eng, plan, stream)
+    while True:
+        slot = ds.ds_restore_next_slot(rev)
+        if slot is None:
+            break
+        ds.ds_restore_submit(rev, slot[0])
+    ds.ds_event_wait(rev)
+    restore_s = time.perf_counter() - t0
+    rst = ds.ds_event_stats(rev)
+    ds.ds_event_destroy(rev)
 
     # ---- configs[4]: snapshots under a concurrent bf16 GEMM stream -----------------------------
     overlap = None
@@ -364,6 +394,8 @@ def main() -> int:
             "copy_probe_GBps": round(2 * nprobe / probe_med / 1e6, 1),    # plain copy, same shape: the ceiling
             "pack_vs_copy_probe": round((algo_bytes / pack_med) / (2 * nprobe / probe_med), 4),
         },
+        "restore": {"GBps_null_producer": round(payload / restore_s / 1e9, 2), "ms": round(restore_s * 1e3, 3),
+                    "scatter_ms": round(rst["pack_ms"], 3), "scatter_launches": rst["n_pack_launches"]},
         "overlap": overlap,
         "hip_runtime": ds.hip_runtime_in_use(),
     }

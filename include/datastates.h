@@ -250,6 +250,35 @@ int ds_event_stats(ds_event *ev, ds_snapshot_stats *out);
 /* Waits for the snapshot, releases chunks still held, frees the event. */
 int ds_event_destroy(ds_event *ev);
 
+/* ---- restore from a host image (recovery, Sec. V-A5 rule (3); the mirror image
+ *      of the snapshot pipeline: pinned ring -> device staging -> scatter) ------ */
+
+/*
+ * Starts a restore of the whole image of `plan` through the engine's ring and
+ * staging.  The engine must be idle: no snapshot or restore event of it may be
+ * alive (DS_EBUSY).  Scatters are ordered after everything enqueued so far on
+ * `compute_stream`.  The caller then repeats, in file order:
+ *   ds_restore_next_slot  -> a ring slot to fill with image bytes
+ *                            [file_off, file_off+len) (e.g. read from the file)
+ *   ds_restore_submit     -> the slot is copied to the device; when the chunks of
+ *                            a staging slot are complete they are scattered into
+ *                            the tensors
+ * and finally ds_event_wait (host) or ds_event_wait_on_stream (a stream that is
+ * to use the restored tensors), then ds_event_destroy.
+ */
+int ds_restore_begin(ds_engine *engine, const ds_plan *plan, void *compute_stream, ds_event **out);
+
+/*
+ * Next ring slot, in file order.  Blocks the host only while the copy that last
+ * used the slot is still in flight.  Several slots may be held at once (to read
+ * ahead); DS_EBUSY if all of them are with the caller; DS_EOF after the last.
+ */
+int ds_restore_next_slot(ds_event *ev, void **host_ptr, uint64_t *file_off, uint64_t *len);
+
+/* The slot has been filled.  Slots are submitted in the order they were handed
+ * out (DS_ESTATE otherwise).  Returns as soon as the work is enqueued. */
+int ds_restore_submit(ds_event *ev, const void *host_ptr);
+
 /* ---- misc ---------------------------------------------------------------- */
 
 const char *ds_strerror(int code);

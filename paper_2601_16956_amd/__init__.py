@@ -29,6 +29,7 @@ EXPORTS = [
     "ds_event_wait_on_stream", "ds_event_wait_captured", "ds_event_query", "ds_event_wait",
     "ds_snapshot_next_chunk", "ds_snapshot_release_chunk", "ds_event_stats", "ds_event_destroy",
     "ds_strerror", "ds_last_hip_error", "ds_config_set", "ds_config_get", "ds_copy_probe",
+    "ds_restore_begin", "ds_restore_next_slot", "ds_restore_submit",
 ]
 
 
@@ -135,6 +136,9 @@ def _load() -> ctypes.CDLL:
         "ds_config_set": ([ctypes.c_char_p, u64], ctypes.c_int),
         "ds_config_get": ([ctypes.c_char_p, P(u64)], ctypes.c_int),
         "ds_copy_probe": ([vp, vp, u64, vp], ctypes.c_int),
+        "ds_restore_begin": ([vp, vp, vp, P(vp)], ctypes.c_int),
+        "ds_restore_next_slot": ([vp, P(vp), P(u64), P(u64)], ctypes.c_int),
+        "ds_restore_submit": ([vp, vp], ctypes.c_int),
     }
     for name, (args, res) in sig.items():
         fn = getattr(L, name)
@@ -296,3 +300,23 @@ def ds_config_get(key: str) -> int:
 
 def ds_copy_probe(dst_dev: int, src_dev: int, nbytes: int, stream: int = 0) -> None:
     _check(_lib.ds_copy_probe(dst_dev, src_dev, nbytes, stream), "ds_copy_probe")
+
+
+def ds_restore_begin(engine: int, plan: int, compute_stream: int = 0) -> int:
+    out = ctypes.c_void_p(0)
+    _check(_lib.ds_restore_begin(engine, plan, compute_stream, ctypes.byref(out)), "ds_restore_begin")
+    return int(out.value)
+
+
+def ds_restore_next_slot(ev: int) -> Optional[Tuple[int, int, int]]:
+    """(host address, file offset, length) of the next ring slot to fill, or None at the end."""
+    ptr, off, ln = ctypes.c_void_p(0), ctypes.c_uint64(0), ctypes.c_uint64(0)
+    rc = _check(_lib.ds_restore_next_slot(ev, ctypes.byref(ptr), ctypes.byref(off), ctypes.byref(ln)),
+                "ds_restore_next_slot")
+    if rc == DS_EOF:
+        return None
+    return int(ptr.value), int(off.value), int(ln.value)
+
+
+def ds_restore_submit(ev: int, host_ptr: int) -> None:
+    _check(_lib.ds_restore_submit(ev, host_ptr), "ds_restore_submit")

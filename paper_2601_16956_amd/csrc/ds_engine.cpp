@@ -16,6 +16,7 @@
 // MI355X has HBM to spare (288 GB), so staging as large as the image is an
 // ordinary setting and the update phase is then delayed by the gather time
 // only (a fraction of a millisecond per GB), not by the link.
+#include <algorithm>
 #include <chrono>
 #include <condition_variable>
 #include <deque>
@@ -79,6 +80,10 @@ struct ds_event {
   bool all_issued = false;
   int error = DS_OK;
   double submit_host_ms = 0;
+  // restore (host image -> tensors): chunks are handed to the producer, submitted, copied up, scattered
+  bool restore = false;
+  uint32_t r_handed = 0, r_submitted = 0;
+  std::vector<hipEvent_t> group_done;  // scatter of staging group gi finished
 };
 
 namespace {
@@ -403,6 +408,12 @@ int ds_snapshot_async(ds_engine *g, const ds_plan *plan, void *compute_stream, d
 
 int ds_event_wait_on_stream(ds_event *ev, void *stream) {
   if (!ev) return DS_EINVAL;
+  if (ev->restore) {  // the stream may touch the tensors once the last scatter has run
+    if (!ev->all_issued) return DS_ESTATE;
+    if (ev->error != DS_OK) return ev->error;
+    DS_HIP_TRY(hipStreamWaitEvent((hipStream_t)stream, ev->final_ev, 0));
+    return DS_OK;
+  }
   int rc = wait_capture_issued(ev);
   if (rc != DS_OK) return rc;
   DS_HIP_TRY(hipStreamWaitEvent((hipStream_t)stream, ev->captured, 0));
@@ -411,6 +422,7 @@ int ds_event_wait_on_stream(ds_event *ev, void *stream) {
 
 int ds_event_wait_captured(ds_event *ev) {
   if (!ev) return DS_EINVAL;
+  if (ev->restore) return DS_ESTATE;
   int rc = wait_capture_issued(ev);
   if (rc != DS_OK) return rc;
   DS_HIP_TRY(hipEventSynchronize(ev->captured));
@@ -432,6 +444,7 @@ int ds_event_query(ds_event *ev) {
 
 int ds_event_wait(ds_event *ev) {
   if (!ev) return DS_EINVAL;
+  if (ev->restore && !ev->all_issued) return DS_ESTATE;  // chunks still to be submitted by the caller
   int rc = wait_issued(ev);
   if (rc != DS_OK) return rc;
   DS_HIP_TRY(hipEventSynchronize(ev->final_ev));
@@ -441,7 +454,7 @@ int ds_event_wait(ds_event *ev) {
 int ds_snapshot_next_chunk(ds_event *ev, const void **host_ptr, uint64_t *file_off, uint64_t *len) {
   if (!ev || !host_ptr || !file_off || !len) return DS_EINVAL;
   ds_engine *g = ev->eng;
-  if (g->flags & DS_ENGINE_AUTO_RELEASE) return DS_ESTATE;
+  if ((g->flags & DS_ENGINE_AUTO_RELEASE) || ev->restore) return DS_ESTATE;
   uint32_t k, r;
   {
     std::unique_lock<std::mutex> lk(g->mu);
@@ -465,6 +478,7 @@ int ds_snapshot_next_chunk(ds_event *ev, const void **host_ptr, uint64_t *file_o
 
 int ds_snapshot_release_chunk(ds_event *ev, const void *host_ptr) {
   if (!ev || !host_ptr) return DS_EINVAL;
+  if (ev->restore) return DS_ESTATE;
   ds_engine *g = ev->eng;
   const uint8_t *p = (const uint8_t *)host_ptr;
   if (p < g->ring || p >= g->ring + (uint64_t)g->ring_slots * g->chunk_bytes || (uint64_t)(p - g->ring) % g->chunk_bytes)
@@ -503,8 +517,8 @@ int ds_event_stats(ds_event *ev, ds_snapshot_stats *out) {
   float ms = 0;
   DS_HIP_TRY(hipEventElapsedTime(&ms, ev->copy_begin, ev->final_ev));
   out->copy_ms = ms;
-  DS_HIP_TRY(hipEventElapsedTime(&ms, ev->requested, ev->captured));
-  out->capture_ms = ms;
+  if (ev->captured) DS_HIP_TRY(hipEventElapsedTime(&ms, ev->requested, ev->captured));
+  out->capture_ms = ev->captured ? ms : 0.0;
   DS_HIP_TRY(hipEventElapsedTime(&ms, ev->requested, ev->final_ev));
   out->total_ms = ms;
   out->submit_host_ms = ev->submit_host_ms;
@@ -515,6 +529,24 @@ int ds_event_destroy(ds_event *ev) {
   if (!ev) return DS_EINVAL;
   ds_engine *g = ev->eng;
   int rc = DS_OK;
+  if (ev->restore) {
+    // whatever was submitted runs to its end; chunks never submitted are simply not restored
+    hipError_t e = hipStreamSynchronize(g->copy_stream[0]);
+    if (e == hipSuccess) e = hipStreamSynchronize(g->pack_stream);
+    if (e != hipSuccess) rc = hip_fail(e);
+    destroy_events(ev->group_done);
+    destroy_events(ev->pack_begin);
+    destroy_events(ev->pack_end);
+    for (hipEvent_t x : {ev->requested, ev->captured, ev->final_ev, ev->copy_begin})
+      if (x) (void)hipEventDestroy(x);
+    {
+      std::lock_guard<std::mutex> lk(g->mu);
+      std::fill(g->ring_busy.begin(), g->ring_busy.end(), 0);  // the ring is empty again for snapshots
+      --g->live_events;
+    }
+    delete ev;
+    return rc;
+  }
   if (!(g->flags & DS_ENGINE_AUTO_RELEASE)) {
     // hand back what the consumer still holds, then drain what it never took
     for (;;) {
@@ -554,6 +586,131 @@ int ds_event_destroy(ds_event *ev) {
   }
   delete ev;
   return rc;
+}
+
+
+// ---- restore: pinned host ring -> device staging -> scatter (the mirror image of a snapshot) -----
+
+int ds_restore_begin(ds_engine *g, const ds_plan *plan, void *compute_stream, ds_event **out) {
+  if (!g || !plan || !out || !plan->dev_blob) return DS_EINVAL;
+  {
+    std::lock_guard<std::mutex> lk(g->mu);
+    if (g->live_events > 0) return DS_EBUSY;  // ring and staging are shared with snapshots
+    ++g->live_events;
+  }
+  ds_event *ev = new (std::nothrow) ds_event;
+  int rc = ev ? DS_OK : DS_ENOMEM;
+  hipError_t e = hipSuccess;
+  if (rc == DS_OK) {
+    ev->eng = g;
+    ev->plan = plan;
+    ev->restore = true;
+    try {
+      const uint64_t T = plan->total_bytes;
+      for (uint64_t lo = 0; lo < T; lo += g->chunk_bytes) {
+        DsChunk c;
+        c.file_off = lo;
+        c.len = lo + g->chunk_bytes < T ? g->chunk_bytes : T - lo;
+        ev->chunks.push_back(c);
+      }
+      ev->group_done.assign((size_t)((T + g->stage_slot_bytes - 1) / g->stage_slot_bytes), nullptr);
+    } catch (const std::bad_alloc &) {
+      rc = DS_ENOMEM;
+    }
+  }
+  if (rc == DS_OK) {
+    // the engine is idle by contract; make sure its streams are, so that slots and staging are free
+    e = hipStreamSynchronize(g->pack_stream);
+    for (int c = 0; c < g->n_copy_streams && e == hipSuccess; ++c) e = hipStreamSynchronize(g->copy_stream[c]);
+    if (e == hipSuccess) e = hipEventCreate(&ev->requested);
+    if (e == hipSuccess) e = hipEventCreate(&ev->final_ev);
+    if (e == hipSuccess) e = hipEventCreate(&ev->copy_begin);
+    for (size_t i = 0; i < ev->group_done.size() && e == hipSuccess; ++i) e = hipEventCreate(&ev->group_done[i]);
+    // scatters must not start before what the caller has enqueued so far on its stream
+    if (e == hipSuccess) e = hipEventRecord(ev->requested, (hipStream_t)compute_stream);
+    if (e == hipSuccess) e = hipStreamWaitEvent(g->pack_stream, ev->requested, 0);
+    if (e == hipSuccess) e = hipEventRecord(ev->copy_begin, g->copy_stream[0]);
+    if (e == hipSuccess && ev->chunks.empty()) {
+      e = hipEventRecord(ev->final_ev, g->pack_stream);
+      ev->all_issued = ev->capture_issued = true;
+    }
+    if (e != hipSuccess) rc = hip_fail(e);
+  }
+  if (rc != DS_OK) {
+    if (ev) {
+      destroy_events(ev->group_done);
+      for (hipEvent_t x : {ev->requested, ev->final_ev, ev->copy_begin})
+        if (x) (void)hipEventDestroy(x);
+      delete ev;
+    }
+    std::lock_guard<std::mutex> lk(g->mu);
+    --g->live_events;
+    return rc;
+  }
+  std::fill(g->ring_busy.begin(), g->ring_busy.end(), 0);
+  *out = ev;
+  return DS_OK;
+}
+
+int ds_restore_next_slot(ds_event *ev, void **host_ptr, uint64_t *file_off, uint64_t *len) {
+  if (!ev || !host_ptr || !file_off || !len) return DS_EINVAL;
+  if (!ev->restore) return DS_ESTATE;
+  ds_engine *g = ev->eng;
+  if (ev->r_handed >= ev->chunks.size()) return DS_EOF;
+  if (ev->r_handed - ev->r_submitted >= g->ring_slots) return DS_EBUSY;  // every slot is with the caller
+  const uint32_t k = ev->r_handed;
+  const uint32_t r = k % g->ring_slots;
+  // the slot's previous content must have left for the device
+  if (g->ring_busy[r]) DS_HIP_TRY(hipEventSynchronize(g->ring_done[r]));
+  ev->chunks[k].ring_slot = r;
+  ev->chunks[k].state = 2;
+  ev->r_handed = k + 1;
+  *host_ptr = g->ring + (uint64_t)r * g->chunk_bytes;
+  *file_off = ev->chunks[k].file_off;
+  *len = ev->chunks[k].len;
+  return DS_OK;
+}
+
+int ds_restore_submit(ds_event *ev, const void *host_ptr) {
+  if (!ev || !host_ptr) return DS_EINVAL;
+  if (!ev->restore) return DS_ESTATE;
+  ds_engine *g = ev->eng;
+  const uint32_t k = ev->r_submitted;  // chunks are submitted in the order they were handed out
+  if (k >= ev->r_handed) return DS_ESTATE;
+  DsChunk &c = ev->chunks[k];
+  if (host_ptr != g->ring + (uint64_t)c.ring_slot * g->chunk_bytes) return DS_ESTATE;
+  const uint64_t S = g->stage_slot_bytes;
+  const size_t gi = (size_t)(c.file_off / S);
+  const uint64_t glo = (uint64_t)gi * S;
+  const uint64_t ghi = glo + S < ev->plan->total_bytes ? glo + S : ev->plan->total_bytes;
+  const uint32_t s = (uint32_t)(gi % g->stage_slots);
+  uint8_t *slot = g->stage + (uint64_t)s * S;
+  hipStream_t cs = g->copy_stream[0];
+  // first chunk of a group: its staging slot must have been scattered out by the group that used it before
+  if (c.file_off == glo && gi >= g->stage_slots) W_TRY(hipStreamWaitEvent(cs, ev->group_done[gi - g->stage_slots], 0));
+  W_TRY(hipMemcpyAsync(slot + (c.file_off - glo), host_ptr, c.len, hipMemcpyHostToDevice, cs));
+  W_TRY(hipEventRecord(g->ring_done[c.ring_slot], cs));
+  g->ring_busy[c.ring_slot] = 1;
+  c.state = 3;
+  ev->r_submitted = k + 1;
+  if (c.file_off + c.len == ghi) {  // the group is complete: scatter it
+    hipEvent_t b, e;
+    W_TRY(hipEventCreate(&b));
+    ev->pack_begin.push_back(b);
+    W_TRY(hipEventCreate(&e));
+    ev->pack_end.push_back(e);
+    W_TRY(hipStreamWaitEvent(g->pack_stream, g->ring_done[c.ring_slot], 0));
+    W_TRY(hipEventRecord(b, g->pack_stream));
+    int rc = ds_launch_move(ev->plan, false, slot, glo, ghi, g->grid_limit, g->pack_stream);
+    if (rc != DS_OK) return rc;
+    W_TRY(hipEventRecord(e, g->pack_stream));
+    W_TRY(hipEventRecord(ev->group_done[gi], g->pack_stream));
+    if (ghi == ev->plan->total_bytes) {
+      W_TRY(hipEventRecord(ev->final_ev, g->pack_stream));
+      ev->all_issued = ev->capture_issued = true;
+    }
+  }
+  return DS_OK;
 }
 
 }  // extern "C"

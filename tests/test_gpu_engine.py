@@ -191,3 +191,92 @@ def test_auto_release_and_state_errors():
         with pytest.raises(ds.DsError) as e:
             ds.ds_engine_create(**bad)
         assert e.value.code == ds.DS_EINVAL
+
+
+@pytest.mark.parametrize("cfg", [
+    dict(ring=4 * MiB, chunk=1 * MiB, slot=4 * MiB, slots=2, ahead=1),
+    dict(ring=2 * MiB, chunk=1 * MiB, slot=1 * MiB, slots=1, ahead=2),
+    dict(ring=8 * MiB, chunk=2 * MiB, slot=8 * MiB, slots=3, ahead=3),
+    dict(ring=64 * MiB, chunk=32 * MiB, slot=64 * MiB, slots=1, ahead=1),
+])
+def test_restore_pipeline_matches_oracle(cfg):
+    """Host image -> ring slots -> staging -> scatter; the whole arena (wiped to
+    0xA5 first) is compared with the oracle's unpack into a wiped host arena."""
+    ds, orc, gu, torch = _mods()
+    w = W.fragmentation(1200, max_bytes=1 << 16, seed=71)
+    print(f"[case] restore {cfg}", flush=True)
+    img, offs, tab = gu.oracle_image(w)
+    dw = gu.DeviceWorkload(w, arena_fill=0xA5)
+    eng = ds.ds_engine_create(cfg["ring"], cfg["chunk"], cfg["slot"], cfg["slots"], 0, 0, 1)
+    s = torch.cuda.current_stream().cuda_stream
+    try:
+        for rep in range(2):
+            dw.arena.fill_(0xA5)
+            ev = ds.ds_restore_begin(eng, dw.plan, s)
+            with pytest.raises(ds.DsError) as e:                  # one event at a time on a restoring engine
+                ds.ds_restore_begin(eng, dw.plan, s)
+            assert e.value.code == ds.DS_EBUSY
+            held = []
+            while True:
+                got = ds.ds_restore_next_slot(ev)
+                if got is not None:
+                    ptr, off, ln = got
+                    ctypes.memmove(ptr, img[off:off + ln].ctypes.data, ln)
+                    held.append(ptr)
+                while held and (got is None or len(held) >= cfg["ahead"]):
+                    ds.ds_restore_submit(ev, held.pop(0))
+                if got is None:
+                    break
+            ds.ds_event_wait_on_stream(ev, s)
+            probe = dw.arena.clone()                              # on the gated stream: sees the restored state
+            ds.ds_event_wait(ev)
+            assert ds.ds_event_query(ev) == ds.DS_OK
+            st = ds.ds_event_stats(ev)
+            assert st["n_pack_launches"] >= 1 and st["total_ms"] > 0
+            ds.ds_event_destroy(ev)
+            back = dw.arena_host()
+            if rep == 0:
+                w.arena[:] = 0xA5
+                orc.unpack(tab, len(w.shards), img)
+            assert gu.first_mismatch(back, w.arena) is None, gu.first_mismatch(back, w.arena)
+            assert gu.first_mismatch(probe.cpu().numpy(), w.arena) is None
+    finally:
+        ds.ds_engine_destroy(eng)
+        dw.close()
+
+
+def test_restore_state_errors():
+    ds, orc, gu, torch = _mods()
+    w = W.tiny_gpt()
+    dw = gu.DeviceWorkload(w)
+    eng = ds.ds_engine_create(2 * MiB, 1 * MiB, 2 * MiB, 2, 0, 0, 1)
+    s = torch.cuda.current_stream().cuda_stream
+    try:
+        ev = ds.ds_restore_begin(eng, dw.plan, s)
+        a = ds.ds_restore_next_slot(ev)
+        b = ds.ds_restore_next_slot(ev)
+        with pytest.raises(ds.DsError) as e:                      # both slots are with the caller
+            ds.ds_restore_next_slot(ev)
+        assert e.value.code == ds.DS_EBUSY
+        with pytest.raises(ds.DsError) as e:                      # out of order
+            ds.ds_restore_submit(ev, b[0])
+        assert e.value.code == ds.DS_ESTATE
+        with pytest.raises(ds.DsError) as e:                      # not finished: nothing to wait for yet
+            ds.ds_event_wait(ev)
+        assert e.value.code == ds.DS_ESTATE
+        with pytest.raises(ds.DsError) as e:
+            ds.ds_snapshot_next_chunk(ev)
+        assert e.value.code == ds.DS_ESTATE
+        ds.ds_restore_submit(ev, a[0])
+        ds.ds_event_destroy(ev)                                   # abandoning a restore is allowed
+        ev = ds.ds_snapshot_async(eng, dw.plan, s)                # the engine is usable again
+        with pytest.raises(ds.DsError) as e:
+            ds.ds_restore_begin(eng, dw.plan, s)
+        assert e.value.code == ds.DS_EBUSY
+        with pytest.raises(ds.DsError) as e:
+            ds.ds_restore_next_slot(ev)
+        assert e.value.code == ds.DS_ESTATE
+        ds.ds_event_destroy(ev)
+    finally:
+        ds.ds_engine_destroy(eng)
+        dw.close()
