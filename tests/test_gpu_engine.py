@@ -53,6 +53,7 @@ def _drain(ds, ev, total, delay=0.0, hold=1):
     dict(ring=8 * MiB, chunk=2 * MiB, slot=8 * MiB, slots=3, copy_streams=2),
     dict(ring=64 * MiB, chunk=32 * MiB, slot=64 * MiB, slots=1, copy_streams=1),   # image fits one slot
     dict(ring=8 * MiB, chunk=1 * MiB, slot=8 * MiB, slots=2, copy_streams=1, first=1 * MiB),  # short first launch
+    dict(ring=8 * MiB, chunk=2 * MiB, slot=8 * MiB, slots=2, copy_streams=1, grid=64),        # grid-limited gather
 ])
 def test_snapshot_with_consumer_matches_oracle(cfg):
     ds, orc, gu, torch = _mods()
@@ -60,7 +61,7 @@ def test_snapshot_with_consumer_matches_oracle(cfg):
     print(f"[case] snapshot consumer {cfg}", flush=True)
     want, _, _ = gu.oracle_image(w)
     dw = gu.DeviceWorkload(w)
-    eng = ds.ds_engine_create(cfg["ring"], cfg["chunk"], cfg["slot"], cfg["slots"], 0, 0, cfg["copy_streams"],
+    eng = ds.ds_engine_create(cfg["ring"], cfg["chunk"], cfg["slot"], cfg["slots"], cfg.get("grid", 0), 0, cfg["copy_streams"],
                               cfg.get("first", 0))
     try:
         for rep in range(2):                                  # the second run reuses ring, staging, events

@@ -194,3 +194,49 @@ def test_range_and_argument_errors_on_device_plan():
         assert e.value.code == ds.DS_EINVAL
     finally:
         dw.close()
+
+
+def test_sizes_beyond_32_bits():
+    """One contiguous shard of 5 GiB (offsets inside a tile beyond 2^32) and a 2-D
+    view whose rows are longer than 2^31 bytes (the 64-bit index path of the
+    general kernel), pack and restore, whole image and whole arena."""
+    ds, orc, gu = _mods()
+    import torch
+    GiB = 1 << 30
+    big = 5 * GiB + 48                      # not a multiple of the chunk size: ends inside a chunk
+    row = 2 * GiB + 4112                    # > 2^31, a multiple of 16
+    pitch = row + 4096
+    arena_bytes = 512 + big + 1024 + 2 * pitch
+    rng = np.random.default_rng(12)
+    arena = np.empty(arena_bytes, dtype=np.uint8)
+    blk = rng.integers(0, 256, size=1 << 26, dtype=np.uint8)
+    for lo in range(0, arena_bytes, blk.size):            # period 64 MiB, shifted per block so that
+        n = min(blk.size, arena_bytes - lo)               # a displacement by the period is still seen
+        arena[lo:lo + n] = np.roll(blk, lo >> 26)[:n]
+    second = (512 + big + 1024 + 15) & ~15
+    shards = [Shard("flat5g", "u8", (big,), (1,), 512 + 4, 0),
+              Shard("long_rows", "u8", (2, row), (pitch, 1), second + 3, 1),
+              Shard("tail", "i64", (3,), (1,), 8, 2)]
+    w = _adhoc(arena, shards, 4096)
+    print(f"[case] beyond 32 bits: arena {arena_bytes} bytes", flush=True)
+    want, offs, tab = gu.oracle_image(w)
+    dw = gu.DeviceWorkload(w)
+    try:
+        assert dw.total == want.size and dw.offsets == offs
+        image = torch.full((dw.total,), 0xFF, dtype=torch.uint8, device="cuda")
+        s = torch.cuda.current_stream().cuda_stream
+        ds.ds_pack(dw.plan, image.data_ptr(), 0, dw.total, s)
+        torch.cuda.synchronize()
+        got = image.cpu().numpy()
+        assert gu.first_mismatch(got, want) is None, gu.first_mismatch(got, want)
+        del got
+        dw.arena.fill_(0xA5)
+        image.copy_(torch.from_numpy(want))
+        ds.ds_unpack(dw.plan, image.data_ptr(), 0, dw.total, s)
+        torch.cuda.synchronize()
+        back = dw.arena_host()
+        w.arena[:] = 0xA5
+        orc.unpack(tab, len(shards), want)
+        assert gu.first_mismatch(back, w.arena) is None, gu.first_mismatch(back, w.arena)
+    finally:
+        dw.close()
