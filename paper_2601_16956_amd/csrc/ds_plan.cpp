@@ -258,14 +258,23 @@ int ds_plan_create(const ds_shard_desc *desc, size_t n, uint64_t align, uint32_t
       for (size_t i = 0; i < n; ++i) if (sizes[i]) order.push_back(i);
       std::sort(order.begin(), order.end(),
                 [&](size_t a, size_t b) { return desc[a].file_offset < desc[b].file_offset; });
+      // overlaps first (over the whole table), holes second: the code returned for a table with
+      // both kinds of mistake does not depend on where they are
       uint64_t prev_end = 0;  // end of the shard before, in the image
       for (size_t k = 0; k < order.size() && rc == DS_OK; ++k) {
         const ds_shard_desc &d = desc[order[k]];
         if (d.file_offset < prev_end) { rc = DS_EOVERLAP; break; }
-        if ((flags & DS_PLAN_STRICT) && d.file_offset > round_up(prev_end, align)) { rc = DS_EGAP; break; }
         prev_end = d.file_offset + sizes[order[k]];
       }
-      if (rc == DS_OK && (flags & DS_PLAN_STRICT) && p->total_bytes > round_up(prev_end, align)) rc = DS_EGAP;
+      if (rc == DS_OK && (flags & DS_PLAN_STRICT)) {
+        prev_end = 0;
+        for (size_t k = 0; k < order.size(); ++k) {
+          const ds_shard_desc &d = desc[order[k]];
+          if (d.file_offset > round_up(prev_end, align)) { rc = DS_EGAP; break; }
+          prev_end = d.file_offset + sizes[order[k]];
+        }
+        if (rc == DS_OK && p->total_bytes > round_up(prev_end, align)) rc = DS_EGAP;
+      }
       if (rc == DS_OK) {
         if (p->total_bytes && (order.empty() || desc[order[0]].file_offset > 0)) {
           DsTile hole;  // the image starts with bytes of no shard: a tile of pure padding
