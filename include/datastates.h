@@ -5,8 +5,8 @@
  * DataStates-LLM (arXiv 2601.16956): the fragmented, mixed-precision, possibly
  * strided model/optimizer shards of one rank are coalesced into one contiguous
  * image laid out like the checkpoint file (Sec. V-A1 "coalescing", Sec. V-A5
- * rule (1) "fixed offsets"), the image is streamed to a pre-pinned, reused
- * host ring (Sec. V-A1, Sec. V-B/V-C "pinned circular buffer") in chunks that
+ * rule (1): offsets fixed in advance), the image is streamed to a pre-pinned,
+ * reused host ring (Sec. V-A1; the circular host cache of Sec. V-B/V-C) in chunks that
  * need not be whole tensors (Sec. V-A4), while training continues; the
  * mutating update phase is gated on the capture (Sec. V-A2).  Restore is the
  * inverse scatter.
@@ -62,8 +62,9 @@ typedef enum ds_dtype { DS_F32 = 0, DS_BF16 = 1, DS_F16 = 2, DS_I64 = 3, DS_U8 =
 
 /*
  * One shard: a view into device memory plus its place in the file.
- * (The "many independently owned tensor shards per rank whose boundaries are
- * dictated by TP/PP/DP and optimizer sharding", Sec. IV-C.)
+ * (Sec. IV-C: a rank owns many separate shards, cut where the parallel
+ * execution plan and the optimizer sharding put the cuts, not where a
+ * checkpoint layout would.)
  */
 typedef struct ds_shard_desc {
   const void *base;               /* DEVICE address of element (0,...,0); multiple of the itemsize */
@@ -106,8 +107,8 @@ int ds_layout_assign(ds_shard_desc *desc, size_t n, uint64_t align, uint64_t *to
  * work-group chunks and uploads the tables to the current device.  The
  * descriptors are copied: the caller may free `desc` afterwards.  The tensors
  * themselves stay owned by the caller and must stay allocated while the plan
- * is used.  The plan is reused by every snapshot of the same shard set (the
- * paper's "reused for all checkpoint requests", Sec. V-A1).
+ * is used.  The plan is reused by every snapshot of the same shard set (Sec.
+ * V-A1: what is set up once serves all later checkpoint requests).
  * Errors: DS_EINVAL, DS_EALIGN, DS_EOVERLAP, DS_EGAP, DS_ENOMEM, DS_EHIP.
  */
 int ds_plan_create(const ds_shard_desc *desc, size_t n, uint64_t align, uint32_t flags, ds_plan **out);
@@ -220,8 +221,8 @@ int ds_event_query(ds_event *ev);
 int ds_event_wait(ds_event *ev);
 
 /*
- * Consumer side (Sec. V-A3: "the next chunk in the stream: how many bytes from
- * where"): blocks until the next chunk of the image is resident in the ring,
+ * Consumer side (Sec. V-A3: the stream is exposed chunk by chunk, each an
+ * address and a length): blocks until the next chunk of the image is resident in the ring,
  * then returns its host address, its offset in the file and its length.
  * Chunks come in file order.  DS_EOF after the last.  The memory stays valid
  * until ds_snapshot_release_chunk.  Not used with DS_ENGINE_AUTO_RELEASE.
