@@ -406,7 +406,14 @@ __device__ __forceinline__ void store_cut(uint8_t *p0, uint8_t *p1, uint32_t k, 
   }
 }
 
-template <bool PACK, int NT, int UNROLL, bool NTL, bool NTS>
+// BUFST: the gather writes the image through buffer stores with the cache policy "sc0 sc1 nt"
+// (write-through, streaming).  Measured on a plain copy of this shape: 6.25 TB/s against 6.07 TB/s with
+// "nt" global stores and 5.88 TB/s with plain ones.  The buffer form is used because the compiler has an
+// intrinsic with a cache-policy operand for it (and none for global stores); the resource covers exactly
+// the work-group's chunk, so an out-of-range store would be dropped by the hardware.
+constexpr int kStorePolicySc0Sc1Nt = 1 | 2 | 16;  // sc0 | nt | sc1 in the intrinsic's aux operand
+
+template <bool PACK, int NT, int UNROLL, bool NTL, bool NTS, bool BUFST>
 __global__ __launch_bounds__(NT) void ds_lean_kernel(LeanArgs a) {
   const uint32_t tid = threadIdx.x;
   for (uint32_t ci = blockIdx.x; ci < a.n_chunks; ci += gridDim.x) {
@@ -415,6 +422,8 @@ __global__ __launch_bounds__(NT) void ds_lean_kernel(LeanArgs a) {
     const uint32_t kind = r.kind & 0xFF;  // bits 8.. hold log2(itemsize)
     if (kind == DS_CHUNK_GENERAL) continue;
     uint8_t *imgp = a.img + (((uint64_t)c << a.chunk_log2) - a.img_lo);
+    __amdgpu_buffer_rsrc_t image_rsrc;
+    if (PACK && BUFST) image_rsrc = __builtin_amdgcn_make_buffer_rsrc(imgp, 0, NT * UNROLL * 16, 0x00020000);
     u32x4 v[UNROLL];
     if (kind == DS_CHUNK_CONTIG) {
       uint8_t *s = reinterpret_cast<uint8_t *>(r.addr);
@@ -426,7 +435,8 @@ __global__ __launch_bounds__(NT) void ds_lean_kernel(LeanArgs a) {
 #pragma unroll
       for (int i = 0; i < UNROLL; ++i) {
         const uint32_t off = 16u * (i * NT + tid);
-        if (PACK) st16_aligned<NTS>(imgp + off, v[i]);
+        if (PACK && BUFST) __builtin_amdgcn_raw_buffer_store_b128(v[i], image_rsrc, (int)off, 0, kStorePolicySc0Sc1Nt);
+        else if (PACK) st16_aligned<NTS>(imgp + off, v[i]);
         else st16_any<NTS>(s + off, v[i]);
       }
     } else {
@@ -461,7 +471,9 @@ __global__ __launch_bounds__(NT) void ds_lean_kernel(LeanArgs a) {
 #pragma unroll
       for (int i = 0; i < UNROLL; ++i) {
         const uint32_t off = 16u * (i * NT + tid);
-        if (PACK) {
+        if (PACK && BUFST) {
+          __builtin_amdgcn_raw_buffer_store_b128(v[i], image_rsrc, (int)off, 0, kStorePolicySc0Sc1Nt);
+        } else if (PACK) {
           st16_aligned<NTS>(imgp + off, v[i]);
         } else if (cut[i] == 0) {
           st16_any<NTS>(p[i], v[i]);
@@ -476,7 +488,7 @@ __global__ __launch_bounds__(NT) void ds_lean_kernel(LeanArgs a) {
 // The general kernel gets its own stream, beside the lean kernel, when it has this many chunks.
 constexpr uint32_t kSideStreamMinChunks = 1024;
 
-template <bool PACK, bool NTL, bool NTS>
+template <bool PACK, bool NTL, bool NTS, bool BUFST>
 int launch_both(const ds_plan *plan, const LeanArgs &la, const MoveArgs &ma, uint32_t grid_limit, hipStream_t stream) {
   // Both kernels touch disjoint chunks, so they may run at the same time.  The general kernel is
   // latency-bound (few resident waves, a chain of table loads per chunk); beside the lean kernel its
@@ -495,10 +507,10 @@ int launch_both(const ds_plan *plan, const LeanArgs &la, const MoveArgs &ma, uin
     uint32_t grid = la.n_chunks;
     if (grid_limit && grid > grid_limit) grid = grid_limit;
     switch (plan->chunk_log2) {  // a lean chunk is exactly 256 threads x unroll x 16 bytes
-      case 13: hipLaunchKernelGGL((ds_lean_kernel<PACK, 256, 2, NTL, NTS>), dim3(grid), dim3(256), 0, stream, la); break;
-      case 14: hipLaunchKernelGGL((ds_lean_kernel<PACK, 256, 4, NTL, NTS>), dim3(grid), dim3(256), 0, stream, la); break;
-      case 15: hipLaunchKernelGGL((ds_lean_kernel<PACK, 256, 8, NTL, NTS>), dim3(grid), dim3(256), 0, stream, la); break;
-      case 16: hipLaunchKernelGGL((ds_lean_kernel<PACK, 512, 8, NTL, NTS>), dim3(grid), dim3(512), 0, stream, la); break;
+      case 13: hipLaunchKernelGGL((ds_lean_kernel<PACK, 256, 2, NTL, NTS, BUFST>), dim3(grid), dim3(256), 0, stream, la); break;
+      case 14: hipLaunchKernelGGL((ds_lean_kernel<PACK, 256, 4, NTL, NTS, BUFST>), dim3(grid), dim3(256), 0, stream, la); break;
+      case 15: hipLaunchKernelGGL((ds_lean_kernel<PACK, 256, 8, NTL, NTS, BUFST>), dim3(grid), dim3(256), 0, stream, la); break;
+      case 16: hipLaunchKernelGGL((ds_lean_kernel<PACK, 512, 8, NTL, NTS, BUFST>), dim3(grid), dim3(512), 0, stream, la); break;
       default: return DS_EINVAL;
     }
     DS_HIP_TRY(hipGetLastError());
@@ -519,14 +531,18 @@ int launch_both(const ds_plan *plan, const LeanArgs &la, const MoveArgs &ma, uin
 // is compared with, and the known-size kernel the HBM counters are scaled by.
 __global__ __launch_bounds__(256) void ds_copy_probe_kernel(const u32x4 *__restrict__ src, u32x4 *__restrict__ dst,
                                                             uint64_t n_units) {
-  const uint64_t base = (uint64_t)blockIdx.x * 1024 + threadIdx.x;
+  const uint64_t first = (uint64_t)blockIdx.x * 1024;  // this work-group's 1024 units
+  const uint64_t left = n_units - first;
+  const uint32_t mine = left < 1024 ? (uint32_t)left : 1024u;
+  __amdgpu_buffer_rsrc_t out = __builtin_amdgcn_make_buffer_rsrc(dst + first, 0, (int)(mine * 16u), 0x00020000);
   u32x4 v[4];
 #pragma unroll
   for (int i = 0; i < 4; ++i)
-    if (base + 256 * i < n_units) v[i] = __builtin_nontemporal_load(src + base + 256 * i);
+    if (threadIdx.x + 256u * i < mine) v[i] = __builtin_nontemporal_load(src + first + threadIdx.x + 256 * i);
 #pragma unroll
   for (int i = 0; i < 4; ++i)
-    if (base + 256 * i < n_units) __builtin_nontemporal_store(v[i], dst + base + 256 * i);
+    if (threadIdx.x + 256u * i < mine)
+      __builtin_amdgcn_raw_buffer_store_b128(v[i], out, (int)(16u * (threadIdx.x + 256u * i)), 0, kStorePolicySc0Sc1Nt);
 }
 
 }  // namespace
@@ -589,10 +605,15 @@ int ds_launch_move(const ds_plan *plan, bool pack, uint8_t *img, uint64_t img_lo
     ma.n_chunks = ma.n_extra + (uint32_t)(hi - lo);
   }
   const uint64_t variant = ds_cfg_variant();
-  if (variant == 1) {
-    return pack ? launch_both<true, false, false>(plan, la, ma, grid_limit, stream)
-                : launch_both<false, false, false>(plan, la, ma, grid_limit, stream);
+  if (variant == 1) {  // plain loads and stores
+    return pack ? launch_both<true, false, false, false>(plan, la, ma, grid_limit, stream)
+                : launch_both<false, false, false, false>(plan, la, ma, grid_limit, stream);
   }
-  return pack ? launch_both<true, true, true>(plan, la, ma, grid_limit, stream)
-              : launch_both<false, true, true>(plan, la, ma, grid_limit, stream);
+  if (variant == 2) {  // non-temporal global loads and stores everywhere
+    return pack ? launch_both<true, true, true, false>(plan, la, ma, grid_limit, stream)
+                : launch_both<false, true, true, false>(plan, la, ma, grid_limit, stream);
+  }
+  // default: non-temporal accesses, and the lean gather writes the image with "sc0 sc1 nt" buffer stores
+  return pack ? launch_both<true, true, true, true>(plan, la, ma, grid_limit, stream)
+              : launch_both<false, true, true, false>(plan, la, ma, grid_limit, stream);
 }

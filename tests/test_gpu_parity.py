@@ -64,7 +64,7 @@ def test_unpack_matches_oracle(name):
 
 
 @pytest.mark.parametrize("chunk_bytes", [8192, 16384, 32768, 65536])
-@pytest.mark.parametrize("variant", [0, 1])
+@pytest.mark.parametrize("variant", [0, 1, 2])
 def test_chunk_sizes_and_kernel_variants(chunk_bytes, variant):
     ds, orc, gu = _mods()
     w = W.fragmentation(1500, max_bytes=1 << 19, seed=77)
@@ -240,3 +240,16 @@ def test_sizes_beyond_32_bits():
         assert gu.first_mismatch(back, w.arena) is None, gu.first_mismatch(back, w.arena)
     finally:
         dw.close()
+
+
+def test_copy_probe_copies():
+    ds, orc, gu = _mods()
+    import torch
+    for n in (16, 16 * 1023, 16 * 1024, 16 * 1025, (64 << 20) + 48):
+        src = torch.empty(n, dtype=torch.uint8, device="cuda").random_(0, 255)
+        dst = torch.zeros(n + 64, dtype=torch.uint8, device="cuda")
+        ds.ds_copy_probe(dst.data_ptr(), src.data_ptr(), n, torch.cuda.current_stream().cuda_stream)
+        torch.cuda.synchronize()
+        assert torch.equal(dst[:n], src) and not dst[n:].any(), n
+    with pytest.raises(ds.DsError):
+        ds.ds_copy_probe(dst.data_ptr(), src.data_ptr(), 24, 0)
