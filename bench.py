@@ -59,6 +59,9 @@ def main() -> int:
     ap.add_argument("--first-launch-bytes", type=int, default=0, help="short first gather launch (0 = none)")
     ap.add_argument("--no-overlap", action="store_true", help="skip the concurrent-GEMM leg (configs[4])")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-file", action="store_true", help="skip the file-tier leg")
+    ap.add_argument("--file-dir", default="/tmp", help="where the file-tier leg writes its image")
+    ap.add_argument("--file-threads", type=int, default=8)
     ap.add_argument("--gemm-iters", type=int, default=12, help="iterations of the overlap leg")
     ap.add_argument("--timed-only", action="store_true",
                     help="stop after the timed region (so that a kernel trace holds the timed launches only)")
@@ -361,6 +364,39 @@ def main() -> int:
 
     ds.ds_engine_destroy(eng)
     torch.cuda.synchronize()
+
+    # ---- the file tier: snapshot -> ring -> file with writer threads, then file -> ring -> GPU ---
+    file_tier = None
+    if not args.no_file:
+        path = os.path.join(args.file_dir, f"ds_bench_{os.getpid()}.img")
+        eng2 = ds.ds_engine_create(args.ring_bytes, args.chunk_bytes, args.stage_slot_bytes, args.stage_slots, 0, 0,
+                                   args.copy_streams, args.first_launch_bytes)
+        try:
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            ev = ds.ds_snapshot_async(eng2, plan, stream)
+            fl = ds.ds_flush_start(ev, path, args.file_threads, ds.DS_FILE_DIRECT)
+            ds.ds_event_wait_on_stream(ev, stream)
+            nbytes, _ = ds.ds_flush_wait(fl)
+            flush_s = time.perf_counter() - t0
+            ds.ds_event_wait(ev)
+            ds.ds_event_destroy(ev)
+            t0 = time.perf_counter()
+            rev = ds.ds_restore_from_file(eng2, plan, path, args.file_threads, ds.DS_FILE_DIRECT, stream)
+            ds.ds_event_wait(rev)
+            load_s = time.perf_counter() - t0
+            ds.ds_event_destroy(rev)
+            file_tier = {"dir": args.file_dir, "threads": args.file_threads, "bytes": nbytes,
+                         "snapshot_to_file_GBps": round(payload / flush_s / 1e9, 2),
+                         "file_to_gpu_GBps": round(payload / load_s / 1e9, 2),
+                         "note": "request -> last byte written (page cache, no fsync); file -> tensors restored"}
+        except ds.DsError as e:
+            file_tier = {"error": str(e)}
+        finally:
+            ds.ds_engine_destroy(eng2)
+            if os.path.exists(path):
+                os.remove(path)
+    torch.cuda.synchronize()
     ds.ds_plan_destroy(plan)
 
     out = {
@@ -397,6 +433,7 @@ def main() -> int:
         "restore": {"GBps_null_producer": round(payload / restore_s / 1e9, 2), "ms": round(restore_s * 1e3, 3),
                     "scatter_ms": round(rst["pack_ms"], 3), "scatter_launches": rst["n_pack_launches"]},
         "overlap": overlap,
+        "file_tier": file_tier,
         "hip_runtime": ds.hip_runtime_in_use(),
     }
     print(json.dumps(out), flush=True)

@@ -59,6 +59,7 @@ typedef enum ds_dtype { DS_F32 = 0, DS_BF16 = 1, DS_F16 = 2, DS_I64 = 3, DS_U8 =
 #define DS_EHIP (-7)     /* a HIP call failed; see ds_last_hip_error()            */
 #define DS_EBUSY (-8)    /* object still has work in flight / chunk not released  */
 #define DS_ESTATE (-9)   /* call not valid in this state (e.g. release of a chunk never handed out) */
+#define DS_EIO (-10)     /* a file operation failed; see ds_last_errno()           */
 
 /*
  * One shard: a view into device memory plus its place in the file.
@@ -81,6 +82,7 @@ typedef struct ds_shard_desc {
 typedef struct ds_plan ds_plan;
 typedef struct ds_engine ds_engine;
 typedef struct ds_event ds_event;
+typedef struct ds_flush ds_flush;
 
 /* ---- layout and plan (Sec. V-A3 composite provider, duty (a): sizes and
  *      offsets in the stream; Sec. V-A5 rule (1)) ---------------------------- */
@@ -279,6 +281,43 @@ int ds_restore_next_slot(ds_event *ev, void **host_ptr, uint64_t *file_off, uint
 /* The slot has been filled.  Slots are submitted in the order they were handed
  * out (DS_ESTATE otherwise).  Returns as soon as the work is enqueued. */
 int ds_restore_submit(ds_event *ev, const void *host_ptr);
+
+/* ---- host <-> file tier (Sec. V-A4: a chunk goes on to the next tier as soon
+ *      as it is resident; Sec. V-C: persistence on background threads) -------- */
+
+#define DS_FILE_DIRECT 1u /* O_DIRECT for every transfer whose address, offset and length are multiples
+                             of 4 KiB (ring slots are); anything else, and everything once the kernel
+                             refuses direct I/O on the ring's pages (EFAULT/EINVAL), goes through a
+                             buffered descriptor */
+#define DS_FILE_SYNC 2u   /* fsync before ds_flush_wait returns                                        */
+
+/*
+ * Starts the consumer of a snapshot taken on an engine WITHOUT
+ * DS_ENGINE_AUTO_RELEASE: one thread takes the chunks as they land in the ring,
+ * `threads` writer threads (0 = 4, at most 64) write each at its file offset
+ * into `path` (created / truncated) and give the ring slot back.  Returns at
+ * once.  The caller must not call ds_snapshot_next_chunk on `ev` itself.
+ * Errors: DS_EINVAL, DS_ENOMEM, DS_EIO.
+ */
+int ds_flush_start(ds_event *ev, const char *path, uint32_t threads, uint32_t flags, ds_flush **out);
+
+/* Waits until the whole image is in the file, closes it and frees the flush.
+ * Either out pointer may be NULL.  Errors: DS_EIO (ds_last_errno()), or the
+ * error that ended the snapshot. */
+int ds_flush_wait(ds_flush *flush, uint64_t *bytes_written, double *seconds);
+
+/*
+ * Restore from a file written by a flush: reads the image with `threads`
+ * reader threads into ring slots and feeds the restore pipeline
+ * (ds_restore_begin / next_slot / submit) in file order.  Returns when the last
+ * chunk has been submitted; *out is then waited for and destroyed like any
+ * restore event.  The engine must be idle.  Errors: as ds_restore_begin, DS_EIO.
+ */
+int ds_restore_from_file(ds_engine *engine, const ds_plan *plan, const char *path, uint32_t threads,
+                         uint32_t flags, void *compute_stream, ds_event **out);
+
+/* errno of the file operation that last produced DS_EIO on this thread. */
+int ds_last_errno(void);
 
 /* ---- misc ---------------------------------------------------------------- */
 

@@ -17,8 +17,9 @@ LIB_PATH = os.path.join(_HERE, "libdatastates_hip.so")
 DS_MAX_DIMS = 6
 DS_F32, DS_BF16, DS_F16, DS_I64, DS_U8 = 0, 1, 2, 3, 4
 DS_OK, DS_NOT_READY, DS_EOF = 0, 1, 2
-DS_EINVAL, DS_EALIGN, DS_EOVERLAP, DS_EGAP, DS_ERANGE, DS_ENOMEM, DS_EHIP, DS_EBUSY, DS_ESTATE = (
-    -1, -2, -3, -4, -5, -6, -7, -8, -9)
+DS_EINVAL, DS_EALIGN, DS_EOVERLAP, DS_EGAP, DS_ERANGE, DS_ENOMEM, DS_EHIP, DS_EBUSY, DS_ESTATE, DS_EIO = (
+    -1, -2, -3, -4, -5, -6, -7, -8, -9, -10)
+DS_FILE_DIRECT, DS_FILE_SYNC = 1, 2
 DS_PLAN_STRICT, DS_PLAN_HOST_ONLY = 1, 2
 DS_ENGINE_AUTO_RELEASE = 1
 
@@ -30,6 +31,7 @@ EXPORTS = [
     "ds_snapshot_next_chunk", "ds_snapshot_release_chunk", "ds_event_stats", "ds_event_destroy",
     "ds_strerror", "ds_last_hip_error", "ds_config_set", "ds_config_get", "ds_copy_probe",
     "ds_restore_begin", "ds_restore_next_slot", "ds_restore_submit",
+    "ds_flush_start", "ds_flush_wait", "ds_restore_from_file", "ds_last_errno",
 ]
 
 
@@ -84,6 +86,8 @@ class DsError(RuntimeError):
         msg = _lib.ds_strerror(code).decode()
         if code == DS_EHIP:
             msg += f" [hipError {_lib.ds_last_hip_error()}]"
+        if code == DS_EIO:
+            msg += f" [errno {_lib.ds_last_errno()}]"
         super().__init__(f"{where}: {msg} ({code})")
 
 
@@ -139,6 +143,10 @@ def _load() -> ctypes.CDLL:
         "ds_restore_begin": ([vp, vp, vp, P(vp)], ctypes.c_int),
         "ds_restore_next_slot": ([vp, P(vp), P(u64), P(u64)], ctypes.c_int),
         "ds_restore_submit": ([vp, vp], ctypes.c_int),
+        "ds_flush_start": ([vp, ctypes.c_char_p, u32, u32, P(vp)], ctypes.c_int),
+        "ds_flush_wait": ([vp, P(u64), P(ctypes.c_double)], ctypes.c_int),
+        "ds_restore_from_file": ([vp, vp, ctypes.c_char_p, u32, u32, vp, P(vp)], ctypes.c_int),
+        "ds_last_errno": ([], ctypes.c_int),
     }
     for name, (args, res) in sig.items():
         fn = getattr(L, name)
@@ -320,3 +328,28 @@ def ds_restore_next_slot(ev: int) -> Optional[Tuple[int, int, int]]:
 
 def ds_restore_submit(ev: int, host_ptr: int) -> None:
     _check(_lib.ds_restore_submit(ev, host_ptr), "ds_restore_submit")
+
+
+def ds_flush_start(ev: int, path: str, threads: int = 0, flags: int = 0) -> int:
+    out = ctypes.c_void_p(0)
+    _check(_lib.ds_flush_start(ev, path.encode(), threads, flags, ctypes.byref(out)), "ds_flush_start")
+    return int(out.value)
+
+
+def ds_flush_wait(flush: int) -> Tuple[int, float]:
+    """(bytes written, seconds from ds_flush_start to the last write)."""
+    nbytes, secs = ctypes.c_uint64(0), ctypes.c_double(0)
+    _check(_lib.ds_flush_wait(flush, ctypes.byref(nbytes), ctypes.byref(secs)), "ds_flush_wait")
+    return int(nbytes.value), float(secs.value)
+
+
+def ds_restore_from_file(engine: int, plan: int, path: str, threads: int = 0, flags: int = 0,
+                         compute_stream: int = 0) -> int:
+    out = ctypes.c_void_p(0)
+    _check(_lib.ds_restore_from_file(engine, plan, path.encode(), threads, flags, compute_stream,
+                                     ctypes.byref(out)), "ds_restore_from_file")
+    return int(out.value)
+
+
+def ds_last_errno() -> int:
+    return int(_lib.ds_last_errno())

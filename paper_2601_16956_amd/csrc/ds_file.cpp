@@ -1,0 +1,353 @@
+// Host <-> file tier of the snapshot pipeline (DataStates-LLM Sec. V-A4: a
+// chunk moves on to the next tier as soon as it is resident; Sec. V-C: file
+// persistence runs on background threads in native code, with direct I/O).
+//
+// Built on the public chunk interface only: a flush is a consumer of
+// ds_snapshot_next_chunk / ds_snapshot_release_chunk, a file restore is a
+// producer for ds_restore_next_slot / ds_restore_submit.  Writes and reads go
+// to the byte offsets the plan fixed (Sec. V-A5 rule (1)), so several threads
+// work on one file without coordination.  Plain pwrite/pread: the image has no
+// liburing, and the point here is the overlap of file I/O with the copies,
+// not the submission interface.
+#include <fcntl.h>
+#include <sys/stat.h>
+#include <unistd.h>
+
+#include <atomic>
+#include <cerrno>
+#include <chrono>
+#include <condition_variable>
+#include <deque>
+#include <mutex>
+#include <new>
+#include <thread>
+#include <vector>
+
+#include "datastates.h"
+
+namespace {
+
+thread_local int g_last_errno = 0;
+
+struct IoJob {
+  void *ptr = nullptr;
+  uint64_t off = 0, len = 0;
+  int slot = -1;  // restore: index into the in-flight window
+};
+
+bool direct_ok(const void *p, uint64_t off, uint64_t len) {
+  return (((uintptr_t)p | off | len) & 4095) == 0;
+}
+
+// whole-range pwrite / pread; returns 0 or errno
+int write_all(int fd, const uint8_t *p, uint64_t len, uint64_t off) {
+  while (len) {
+    ssize_t w = pwrite(fd, p, len, (off_t)off);
+    if (w < 0) {
+      if (errno == EINTR) continue;
+      return errno;
+    }
+    p += w;
+    off += (uint64_t)w;
+    len -= (uint64_t)w;
+  }
+  return 0;
+}
+int read_all(int fd, uint8_t *p, uint64_t len, uint64_t off) {
+  while (len) {
+    ssize_t r = pread(fd, p, len, (off_t)off);
+    if (r < 0) {
+      if (errno == EINTR) continue;
+      return errno;
+    }
+    if (r == 0) return EIO;  // file shorter than the image
+    p += r;
+    off += (uint64_t)r;
+    len -= (uint64_t)r;
+  }
+  return 0;
+}
+
+double now_s() {
+  return std::chrono::duration<double>(std::chrono::steady_clock::now().time_since_epoch()).count();
+}
+
+}  // namespace
+
+struct ds_flush {
+  ds_event *ev = nullptr;
+  int fd_direct = -1, fd_buffered = -1;
+  uint32_t flags = 0;
+  std::thread dispatcher;
+  std::vector<std::thread> writers;
+  std::mutex mu;
+  std::condition_variable cv;
+  std::deque<IoJob> queue;
+  bool no_more = false;
+  std::atomic<int> status{DS_OK};
+  std::atomic<int> err_no{0};
+  std::atomic<uint64_t> bytes{0};
+  std::atomic<bool> direct_usable{true};
+  double t0 = 0, t1 = 0;
+};
+
+namespace {
+
+void flush_fail(ds_flush *f, int status, int e) {
+  int expect = DS_OK;
+  if (f->status.compare_exchange_strong(expect, status)) f->err_no.store(e);
+}
+
+void writer_main(ds_flush *f) {
+  for (;;) {
+    IoJob j;
+    {
+      std::unique_lock<std::mutex> lk(f->mu);
+      f->cv.wait(lk, [&] { return f->no_more || !f->queue.empty(); });
+      if (f->queue.empty()) return;
+      j = f->queue.front();
+      f->queue.pop_front();
+    }
+    if (f->status.load() == DS_OK) {
+      const bool direct = f->direct_usable.load() && f->fd_direct >= 0 && direct_ok(j.ptr, j.off, j.len);
+      int e = write_all(direct ? f->fd_direct : f->fd_buffered, (const uint8_t *)j.ptr, j.len, j.off);
+      if (e && direct && (e == EFAULT || e == EINVAL)) {
+        // direct I/O has to pin the pages of the buffer itself, which the kernel refuses for some mappings
+        // (the HIP pinned ring among them on this system): go on through the page cache
+        f->direct_usable.store(false);
+        e = write_all(f->fd_buffered, (const uint8_t *)j.ptr, j.len, j.off);
+      }
+      if (e) flush_fail(f, DS_EIO, e);
+      else f->bytes.fetch_add(j.len);
+    }
+    // the slot goes back whatever happened, so that the snapshot itself can finish
+    int rc = ds_snapshot_release_chunk(f->ev, j.ptr);
+    if (rc != DS_OK) flush_fail(f, rc, 0);
+  }
+}
+
+void dispatcher_main(ds_flush *f) {
+  for (;;) {
+    const void *p = nullptr;
+    uint64_t off = 0, len = 0;
+    int rc = ds_snapshot_next_chunk(f->ev, &p, &off, &len);
+    if (rc == DS_EOF) break;
+    if (rc != DS_OK) {
+      flush_fail(f, rc, 0);
+      break;
+    }
+    IoJob j;
+    j.ptr = const_cast<void *>(p);
+    j.off = off;
+    j.len = len;
+    {
+      std::lock_guard<std::mutex> lk(f->mu);
+      f->queue.push_back(j);
+    }
+    f->cv.notify_one();
+  }
+  {
+    std::lock_guard<std::mutex> lk(f->mu);
+    f->no_more = true;
+  }
+  f->cv.notify_all();
+}
+
+}  // namespace
+
+extern "C" {
+
+int ds_last_errno(void) { return g_last_errno; }
+
+int ds_flush_start(ds_event *ev, const char *path, uint32_t threads, uint32_t flags, ds_flush **out) {
+  if (!ev || !path || !out || (flags & ~(DS_FILE_DIRECT | DS_FILE_SYNC))) return DS_EINVAL;
+  if (threads == 0) threads = 4;
+  if (threads > 64) return DS_EINVAL;
+  ds_flush *f = new (std::nothrow) ds_flush;
+  if (!f) return DS_ENOMEM;
+  f->ev = ev;
+  f->flags = flags;
+  f->fd_buffered = open(path, O_WRONLY | O_CREAT | O_TRUNC | O_CLOEXEC, 0644);
+  if (f->fd_buffered < 0) {
+    g_last_errno = errno;
+    delete f;
+    return DS_EIO;
+  }
+  // direct I/O where the file system has it; chunks that are not 4 KiB-shaped take the buffered descriptor
+  if (flags & DS_FILE_DIRECT) f->fd_direct = open(path, O_WRONLY | O_DIRECT | O_CLOEXEC);
+  f->t0 = now_s();
+  // writers first: a dispatcher without anyone to release slots would wait for ever
+  try {
+    for (uint32_t i = 0; i < threads; ++i) f->writers.emplace_back(writer_main, f);
+  } catch (...) {
+  }
+  bool started = !f->writers.empty();
+  if (started) {
+    try {
+      f->dispatcher = std::thread(dispatcher_main, f);
+    } catch (...) {
+      started = false;
+    }
+  }
+  if (!started) {
+    {
+      std::lock_guard<std::mutex> lk(f->mu);
+      f->no_more = true;
+    }
+    f->cv.notify_all();
+    for (std::thread &t : f->writers) t.join();
+    if (f->fd_direct >= 0) close(f->fd_direct);
+    close(f->fd_buffered);
+    delete f;
+    return DS_ENOMEM;
+  }
+  *out = f;
+  return DS_OK;
+}
+
+int ds_flush_wait(ds_flush *f, uint64_t *bytes_written, double *seconds) {
+  if (!f) return DS_EINVAL;
+  if (f->dispatcher.joinable()) f->dispatcher.join();
+  f->cv.notify_all();
+  for (std::thread &t : f->writers)
+    if (t.joinable()) t.join();
+  int status = f->status.load();
+  if (status == DS_OK && (f->flags & DS_FILE_SYNC) && fsync(f->fd_buffered) != 0) {
+    status = DS_EIO;
+    f->err_no.store(errno);
+  }
+  f->t1 = now_s();
+  if (f->fd_direct >= 0) close(f->fd_direct);
+  if (close(f->fd_buffered) != 0 && status == DS_OK) {
+    status = DS_EIO;
+    f->err_no.store(errno);
+  }
+  if (bytes_written) *bytes_written = f->bytes.load();
+  if (seconds) *seconds = f->t1 - f->t0;
+  g_last_errno = f->err_no.load();
+  delete f;
+  return status;
+}
+
+int ds_restore_from_file(ds_engine *engine, const ds_plan *plan, const char *path, uint32_t threads, uint32_t flags,
+                         void *compute_stream, ds_event **out) {
+  if (!engine || !plan || !path || !out || (flags & ~DS_FILE_DIRECT)) return DS_EINVAL;
+  if (threads == 0) threads = 4;
+  if (threads > 64) return DS_EINVAL;
+  const int fd_buffered = open(path, O_RDONLY | O_CLOEXEC);
+  if (fd_buffered < 0) {
+    g_last_errno = errno;
+    return DS_EIO;
+  }
+  const int fd_direct = (flags & DS_FILE_DIRECT) ? open(path, O_RDONLY | O_DIRECT | O_CLOEXEC) : -1;
+  ds_event *ev = nullptr;
+  int rc = ds_restore_begin(engine, plan, compute_stream, &ev);
+  if (rc != DS_OK) {
+    if (fd_direct >= 0) close(fd_direct);
+    close(fd_buffered);
+    return rc;
+  }
+  // A window of slots is read by `threads` readers at once and submitted in file order.
+  struct Shared {
+    std::mutex mu;
+    std::condition_variable cv;
+    std::deque<IoJob> todo;
+    std::vector<int> done;  // per window position: 0 pending, 1 read, <0 = -errno
+    bool stop = false;
+  } sh;
+  std::atomic<bool> direct_usable{true};
+  const uint32_t window = threads;
+  sh.done.assign(window, 0);
+  std::vector<IoJob> win(window);
+  std::vector<std::thread> readers;
+  auto reader = [&]() {
+    for (;;) {
+      IoJob j;
+      {
+        std::unique_lock<std::mutex> lk(sh.mu);
+        sh.cv.wait(lk, [&] { return sh.stop || !sh.todo.empty(); });
+        if (sh.todo.empty()) return;
+        j = sh.todo.front();
+        sh.todo.pop_front();
+      }
+      const bool direct = direct_usable.load() && fd_direct >= 0 && direct_ok(j.ptr, j.off, j.len);
+      int e = read_all(direct ? fd_direct : fd_buffered, (uint8_t *)j.ptr, j.len, j.off);
+      if (e && direct && (e == EFAULT || e == EINVAL)) {  // see writer_main
+        direct_usable.store(false);
+        e = read_all(fd_buffered, (uint8_t *)j.ptr, j.len, j.off);
+      }
+      {
+        std::lock_guard<std::mutex> lk(sh.mu);
+        sh.done[j.slot] = e ? -e : 1;
+      }
+      sh.cv.notify_all();
+    }
+  };
+  int err_no = 0;
+  try {
+    for (uint32_t i = 0; i < threads; ++i) readers.emplace_back(reader);
+  } catch (...) {
+    rc = DS_ENOMEM;
+  }
+  uint64_t handed = 0, submitted = 0;
+  bool eof = false;
+  while (rc == DS_OK && (!eof || submitted < handed)) {
+    // fill the window
+    while (!eof && handed - submitted < window) {
+      void *p = nullptr;
+      uint64_t off = 0, len = 0;
+      int r = ds_restore_next_slot(ev, &p, &off, &len);
+      if (r == DS_EOF) { eof = true; break; }
+      if (r == DS_EBUSY) break;  // the ring is smaller than the window: submit first
+      if (r != DS_OK) { rc = r; break; }
+      IoJob j;
+      j.ptr = p;
+      j.off = off;
+      j.len = len;
+      j.slot = (int)(handed % window);
+      win[j.slot] = j;
+      {
+        std::lock_guard<std::mutex> lk(sh.mu);
+        sh.done[j.slot] = 0;
+        sh.todo.push_back(j);
+      }
+      sh.cv.notify_one();
+      ++handed;
+    }
+    if (rc != DS_OK || submitted == handed) continue;
+    // submit the oldest one once it has been read
+    const int pos = (int)(submitted % window);
+    int state;
+    {
+      std::unique_lock<std::mutex> lk(sh.mu);
+      sh.cv.wait(lk, [&] { return sh.done[pos] != 0; });
+      state = sh.done[pos];
+    }
+    if (state < 0) {
+      rc = DS_EIO;
+      err_no = -state;
+      break;
+    }
+    rc = ds_restore_submit(ev, win[pos].ptr);
+    ++submitted;
+  }
+  {
+    std::lock_guard<std::mutex> lk(sh.mu);
+    sh.stop = true;
+    if (rc != DS_OK) sh.todo.clear();
+  }
+  sh.cv.notify_all();
+  for (std::thread &t : readers)
+    if (t.joinable()) t.join();
+  if (fd_direct >= 0) close(fd_direct);
+  close(fd_buffered);
+  if (rc != DS_OK) {
+    g_last_errno = err_no;
+    (void)ds_event_destroy(ev);
+    return rc;
+  }
+  *out = ev;
+  return DS_OK;
+}
+
+}  // extern "C"

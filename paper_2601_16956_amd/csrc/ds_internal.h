@@ -36,7 +36,8 @@ struct DsChunkRec {
   uint32_t col0;   // ROWS: position of the chunk's first byte inside its run
   uint32_t run;    // ROWS: run length in bytes (>= 16, multiple of the itemsize)
   uint32_t kind;   // low byte: DS_CHUNK_*; bits 8..: log2(itemsize) (ROWS)
-  uint32_t tile;
+  uint32_t tile;   // GENERAL: first tile of the chunk.  ROWS: (step / run) << 16 | (step % run), step = bytes
+                   // between two units of one thread (threads per work-group x 16)
 };
 static_assert(sizeof(DsChunkRec) == 32, "two records per 64 bytes");
 

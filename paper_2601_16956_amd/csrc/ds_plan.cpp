@@ -181,6 +181,7 @@ const char *ds_strerror(int code) {
     case DS_EHIP: return "a HIP call failed (see ds_last_hip_error)";
     case DS_EBUSY: return "work still in flight";
     case DS_ESTATE: return "call not valid in this state";
+    case DS_EIO: return "a file operation failed (see ds_last_errno)";
     default: return "unknown datastates status";
   }
 }
@@ -326,6 +327,10 @@ int ds_plan_create(const ds_shard_desc *desc, size_t n, uint64_t align, uint32_t
                 r.pitch = tl.stride[0];
                 r.col0 = (uint32_t)(b0 - row0 * tl.run_bytes);
                 r.run = (uint32_t)tl.run_bytes;
+                // a thread's units are 256 threads x 16 bytes apart (512 x 16 for 64 KiB chunks): that
+                // step, divided by the run length once here instead of once per unit in the kernel
+                const uint64_t step = chunk == (64u << 10) ? 8192 : 4096;
+                r.tile = (uint32_t)(((step / tl.run_bytes) << 16) | (step % tl.run_bytes));
               }
             }
             if ((r.kind & 0xFF) == DS_CHUNK_GENERAL) p->general_ids.push_back((uint32_t)c);

@@ -281,3 +281,49 @@ def test_restore_state_errors():
     finally:
         ds.ds_engine_destroy(eng)
         dw.close()
+
+
+@pytest.mark.parametrize("flags_name", ["buffered", "direct_sync"])
+def test_flush_to_file_and_restore_from_file(tmp_path, flags_name):
+    """GPU -> ring -> file with background writer threads, then file -> ring ->
+    GPU; the file must be the oracle's image, the restored arena the oracle's
+    unpack of it."""
+    ds, orc, gu, torch = _mods()
+    flags = 0 if flags_name == "buffered" else (ds.DS_FILE_DIRECT | ds.DS_FILE_SYNC)
+    w = W.fragmentation(2500, max_bytes=1 << 17, seed=91)
+    print(f"[case] file tier {flags_name}", flush=True)
+    want, offs, tab = gu.oracle_image(w)
+    dw = gu.DeviceWorkload(w)
+    eng = ds.ds_engine_create(6 * MiB, 1 * MiB, 8 * MiB, 2, 0, 0, 1)     # ring far smaller than the image
+    s = torch.cuda.current_stream().cuda_stream
+    path = str(tmp_path / "image.bin")
+    try:
+        ev = ds.ds_snapshot_async(eng, dw.plan, s)
+        fl = ds.ds_flush_start(ev, path, 3, flags)
+        ds.ds_event_wait_on_stream(ev, s)
+        nbytes, secs = ds.ds_flush_wait(fl)
+        ds.ds_event_wait(ev)
+        ds.ds_event_destroy(ev)
+        assert nbytes == dw.total and secs > 0
+        on_disk = np.fromfile(path, dtype=np.uint8)
+        assert gu.first_mismatch(on_disk, want) is None, gu.first_mismatch(on_disk, want)
+
+        dw.arena.fill_(0xA5)
+        rev = ds.ds_restore_from_file(eng, dw.plan, path, 3, flags & ds.DS_FILE_DIRECT, s)
+        ds.ds_event_wait(rev)
+        ds.ds_event_destroy(rev)
+        w.arena[:] = 0xA5
+        orc.unpack(tab, len(w.shards), want)
+        assert gu.first_mismatch(dw.arena_host(), w.arena) is None
+
+        with pytest.raises(ds.DsError) as e:                       # a file that is too short
+            with open(path, "r+b") as f:
+                f.truncate(dw.total // 2)
+            ds.ds_restore_from_file(eng, dw.plan, path, 2, 0, s)
+        assert e.value.code == ds.DS_EIO
+        with pytest.raises(ds.DsError) as e:
+            ds.ds_restore_from_file(eng, dw.plan, str(tmp_path / "missing.bin"), 2, 0, s)
+        assert e.value.code == ds.DS_EIO and ds.ds_last_errno() == 2
+    finally:
+        ds.ds_engine_destroy(eng)
+        dw.close()
