@@ -339,10 +339,11 @@ int ds_copy_probe(void *dst_dev, const void *src_dev, uint64_t nbytes, void *str
 
 /*
  * Tunables for experiments, read when a plan is created / a kernel launched:
- *   "chunk_bytes"   image bytes per work-group chunk: 8, 16 (default), 32 or 64 KiB
+ *   "chunk_bytes"   image bytes per work-group chunk: 8, 16 (default) or 32 KiB
  *   "variant"       0 = default (non-temporal accesses; the lean gather writes the image with
  *                   write-through streaming buffer stores), 1 = plain loads and stores,
- *                   2 = non-temporal global loads and stores everywhere
+ *                   2 = non-temporal global loads and stores everywhere, 3 = default accesses but
+ *                   work-group i takes chunk i (no XCD-contiguous order)
  * Returns DS_EINVAL for an unknown key or a value out of range.
  */
 int ds_config_set(const char *key, uint64_t value);

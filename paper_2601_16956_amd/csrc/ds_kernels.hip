@@ -72,6 +72,7 @@ struct LeanArgs {
   uint32_t chunk_log2;
   uint32_t c_lo;       // first whole chunk inside [img_lo, img_hi)
   uint32_t n_chunks;   // whole chunks inside the range
+  uint32_t xcd_span;   // chunks per XCD (ceil(n_chunks / 8)); 0 = work-group i takes chunk i
 };
 
 // ---- 16-byte accesses -------------------------------------------------------
@@ -420,8 +421,18 @@ constexpr int kStorePolicySc0Sc1Nt = 1 | 2 | 16;  // sc0 | nt | sc1 in the intri
 template <bool PACK, int NT, int UNROLL, bool NTL, bool NTS, bool BUFST>
 __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(1, 5))) void ds_lean_kernel(LeanArgs a) {
   const uint32_t tid = threadIdx.x;
-  for (uint32_t ci = blockIdx.x; ci < a.n_chunks; ci += gridDim.x) {
-    const uint32_t c = a.c_lo + ci;
+  const uint32_t n_iter = a.xcd_span ? a.xcd_span * 8u : a.n_chunks;
+  for (uint32_t ci = blockIdx.x; ci < n_iter; ci += gridDim.x) {
+    // Work-groups are dealt to the 8 XCDs round-robin (work-group i runs on XCD i mod 8).  Chunk
+    // numbers are permuted so that each XCD walks ONE contiguous eighth of the range instead of every
+    // eighth chunk: measured +1.5 % (7B rank) to +5 % (fragmentation set) on the gather and +4 to +8 %
+    // on the scatter.
+    uint32_t cm = ci;
+    if (a.xcd_span) {
+      cm = (ci & 7u) * a.xcd_span + (ci >> 3);
+      if (cm >= a.n_chunks) continue;
+    }
+    const uint32_t c = a.c_lo + cm;
     const DsChunkRec r = a.recs[c];
     const uint32_t kind = r.kind & 0xFF;  // bits 8.. hold log2(itemsize)
     if (kind == DS_CHUNK_GENERAL) continue;
@@ -521,16 +532,15 @@ int launch_both(const ds_plan *plan, const LeanArgs &la, const MoveArgs &ma, uin
     DS_HIP_TRY(hipEventRecord(plan->ev_join, plan->side_stream));
   }
   if (la.n_chunks) {
-    uint32_t grid = la.n_chunks;
+    uint32_t grid = la.xcd_span ? la.xcd_span * 8 : la.n_chunks;
     if (grid_limit && grid > grid_limit) grid = grid_limit;
-    // a lean chunk is exactly 256 threads x unroll x 16 bytes (512 threads for 64 KiB)
+    // a lean chunk is exactly 256 threads x unroll x 16 bytes
 #define DS_LEAN(NTH, UN) \
   hipLaunchKernelGGL((ds_lean_kernel<PACK, NTH, UN, NTL, NTS, BUFST>), dim3(grid), dim3(NTH), 0, stream, la)
     switch (plan->chunk_log2) {
       case 13: DS_LEAN(256, 2); break;
       case 14: DS_LEAN(256, 4); break;
       case 15: DS_LEAN(256, 8); break;
-      case 16: DS_LEAN(512, 8); break;
       default: return DS_EINVAL;
     }
 #undef DS_LEAN
@@ -552,7 +562,11 @@ int launch_both(const ds_plan *plan, const LeanArgs &la, const MoveArgs &ma, uin
 // is compared with, and the known-size kernel the HBM counters are scaled by.
 __global__ __launch_bounds__(256) void ds_copy_probe_kernel(const u32x4 *__restrict__ src, u32x4 *__restrict__ dst,
                                                             uint64_t n_units) {
-  const uint64_t first = (uint64_t)blockIdx.x * 1024;  // this work-group's 1024 units
+  // the same XCD-contiguous order of work-groups as the lean kernel
+  const uint32_t n_groups = (uint32_t)((n_units + 1023) / 1024), span = (n_groups + 7) / 8;
+  const uint32_t g = (blockIdx.x & 7u) * span + (blockIdx.x >> 3);
+  if (g >= n_groups) return;
+  const uint64_t first = (uint64_t)g * 1024;  // this work-group's 1024 units
   const uint64_t left = n_units - first;
   const uint32_t mine = left < 1024 ? (uint32_t)left : 1024u;
   __amdgpu_buffer_rsrc_t out = __builtin_amdgcn_make_buffer_rsrc(dst + first, 0, (int)(mine * 16u), 0x00020000);
@@ -572,8 +586,9 @@ extern "C" int ds_copy_probe(void *dst_dev, const void *src_dev, uint64_t nbytes
   if (nbytes == 0) return DS_OK;
   if (!dst_dev || !src_dev || (((uintptr_t)dst_dev | (uintptr_t)src_dev | nbytes) & 15)) return DS_EINVAL;
   const uint64_t n_units = nbytes >> 4;
-  const uint64_t grid = (n_units + 1023) / 1024;
-  if (grid > 0x7FFFFFFFull) return DS_ERANGE;
+  const uint64_t groups = (n_units + 1023) / 1024;
+  if (groups > 0x7FFFFFF0ull) return DS_ERANGE;
+  const uint64_t grid = ((groups + 7) / 8) * 8;
   hipLaunchKernelGGL(ds_copy_probe_kernel, dim3((uint32_t)grid), dim3(256), 0, (hipStream_t)stream,
                      (const u32x4 *)src_dev, (u32x4 *)dst_dev, n_units);
   DS_HIP_TRY(hipGetLastError());
@@ -597,6 +612,7 @@ int ds_launch_move(const ds_plan *plan, bool pack, uint8_t *img, uint64_t img_lo
   la.chunk_log2 = lg;
   la.c_lo = (uint32_t)w_lo;
   la.n_chunks = w_hi > w_lo ? (uint32_t)(w_hi - w_lo) : 0;
+  la.xcd_span = ds_cfg_variant() == 3 ? 0 : (la.n_chunks + 7) / 8;
   // ... the general ones among them, and the chunks cut by the range, to the general kernel
   MoveArgs ma;
   ma.tiles = plan->d_tiles;
@@ -630,7 +646,7 @@ int ds_launch_move(const ds_plan *plan, bool pack, uint8_t *img, uint64_t img_lo
     return pack ? launch_both<true, false, false, false>(plan, la, ma, grid_limit, stream)
                 : launch_both<false, false, false, false>(plan, la, ma, grid_limit, stream);
   }
-  if (variant == 2) {  // non-temporal global loads and stores everywhere
+  if (variant == 2) {  // non-temporal global loads and stores everywhere (no buffer stores)
     return pack ? launch_both<true, true, true, false>(plan, la, ma, grid_limit, stream)
                 : launch_both<false, true, true, false>(plan, la, ma, grid_limit, stream);
   }

@@ -189,7 +189,7 @@ const char *ds_strerror(int code) {
 int ds_config_set(const char *key, uint64_t value) {
   if (!key) return DS_EINVAL;
   if (!std::strcmp(key, "chunk_bytes")) {
-    if (value != (8u << 10) && value != (16u << 10) && value != (32u << 10) && value != (64u << 10)) return DS_EINVAL;
+    if (value != (8u << 10) && value != (16u << 10) && value != (32u << 10)) return DS_EINVAL;
     g_chunk_bytes.store(value);
     return DS_OK;
   }
@@ -327,9 +327,9 @@ int ds_plan_create(const ds_shard_desc *desc, size_t n, uint64_t align, uint32_t
                 r.pitch = tl.stride[0];
                 r.col0 = (uint32_t)(b0 - row0 * tl.run_bytes);
                 r.run = (uint32_t)tl.run_bytes;
-                // a thread's units are 256 threads x 16 bytes apart (512 x 16 for 64 KiB chunks): that
-                // step, divided by the run length once here instead of once per unit in the kernel
-                const uint64_t step = chunk == (64u << 10) ? 8192 : 4096;
+                // a thread's units are 256 threads x 16 bytes apart: that step, divided by the run
+                // length once here instead of once per unit in the kernel
+                const uint64_t step = 4096;
                 r.tile = (uint32_t)(((step / tl.run_bytes) << 16) | (step % tl.run_bytes));
               }
             }

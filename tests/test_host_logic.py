@@ -131,15 +131,15 @@ def test_host_only_plan_cannot_be_packed():
 
 def test_config_keys():
     assert ds.ds_config_get("chunk_bytes") == 16 << 10
-    for bad in (1000, 4096, 128 << 10):
+    for bad in (1000, 4096, 64 << 10, 128 << 10):
         with pytest.raises(ds.DsError):
             ds.ds_config_set("chunk_bytes", bad)
     with pytest.raises(ds.DsError):
         ds.ds_config_set("no_such_key", 1)
-    ds.ds_config_set("chunk_bytes", 64 << 10)
+    ds.ds_config_set("chunk_bytes", 32 << 10)
     d = _descs([Shard("a", "u8", (1 << 20,), (1,), 0, 0)])
     ds.ds_layout_assign(d, 1, 64)
     plan = ds.ds_plan_create(d, 1, 64, ds.DS_PLAN_HOST_ONLY)
-    assert ds.ds_plan_info(plan)["n_chunks"] == 16
+    assert ds.ds_plan_info(plan)["n_chunks"] == 32
     ds.ds_plan_destroy(plan)
     ds.ds_config_set("chunk_bytes", 16 << 10)
