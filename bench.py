@@ -179,7 +179,7 @@ def main() -> int:
         m = re.search(r"traffic_bytes_per_launch\s*=\s*(\d+)", open(tpath).read())
         traffic = int(m.group(1)) if m else None
     roofline = {
-        "bound": "hbm", "kernel": "ds_lean_kernel<pack> (+ ds_move_kernel<pack> on the chunks it leaves)",
+        "bound": "hbm", "kernel": "ds_move_kernel<pack>",
         "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
         "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic,
         "launches": launches, "avg_launch_ms": round(pack_ms / max(launches, 1), 4),

@@ -128,7 +128,7 @@ typedef struct ds_plan_stats {
   uint64_t chunk_bytes;   /* image bytes per work-group chunk                     */
   uint64_t n_strided;     /* shards that are not one contiguous run               */
   uint64_t align;
-  uint64_t n_general_chunks; /* chunks left to the general kernel (the lean kernel takes the rest) */
+  uint64_t n_general_chunks; /* chunks that take the kernel's general path (the lean path takes the rest) */
 } ds_plan_stats;
 
 int ds_plan_info(const ds_plan *plan, ds_plan_stats *out);

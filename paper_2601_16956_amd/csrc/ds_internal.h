@@ -5,7 +5,6 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
-#include <mutex>
 #include <vector>
 
 #include "datastates.h"
@@ -24,10 +23,10 @@ struct DsTile {
 };
 static_assert(sizeof(DsTile) == 128, "DsTile is one 128-byte line");
 
-// What the lean kernel needs to move one whole chunk, in one 32-byte load.
+// What the kernel's lean path needs to move one whole chunk, in one 32-byte load.
 // Chunks that are not "simple" (a tile boundary, the end of a payload or
 // padding inside the chunk, more than one outer dimension, rows shorter than
-// 16 bytes) are of kind DS_CHUNK_GENERAL and go to the general kernel, which
+// 16 bytes) are of kind DS_CHUNK_GENERAL and take the general path, which
 // finds its tiles through first_tile[].
 enum : uint32_t { DS_CHUNK_CONTIG = 0, DS_CHUNK_ROWS = 1, DS_CHUNK_GENERAL = 2 };
 struct DsChunkRec {
@@ -69,11 +68,6 @@ struct ds_plan {
   const uint32_t *d_first_tile = nullptr;
   const DsChunkRec *d_recs = nullptr;
   const uint32_t *d_general_ids = nullptr;
-  // a side stream (default priority) on which the general kernel runs beside the lean one when it
-  // has a lot to do; fork/join events are reused, so enqueueing is serialised by side_mu
-  hipStream_t side_stream = nullptr;
-  hipEvent_t ev_fork = nullptr, ev_join = nullptr;
-  mutable std::mutex side_mu;
   uint64_t n_chunks() const { return first_tile.empty() ? 0 : first_tile.size() - 1; }
 };
 

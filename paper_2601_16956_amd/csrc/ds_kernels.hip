@@ -8,22 +8,22 @@
 // shards look like, and every work-group moves the same number of bytes
 // however fragmented its part of the image is.
 //
-// Two kernels share a pack (or unpack) call:
+// One kernel, ds_move_kernel, serves a pack (or unpack) call; a work-group takes one chunk down one of
+// two paths:
 //
-// ds_lean_kernel: one pass per chunk, a chunk being exactly threads x unroll
+// lean path: one pass per chunk, a chunk being exactly threads x unroll
 //   units (16 KiB by default), so a thread issues all its loads, then all its
 //   stores, and is done.  Measured on MI355X a plain copy of this shape runs
-//   at ~5.9 TB/s (read+write) against ~5.3 TB/s for work-groups that stream
+//   at ~6 TB/s (read+write) against ~5.3 TB/s for work-groups that stream
 //   through 64-256 KiB each: many short-lived work-groups keep the addresses
-//   in flight inside a compact, moving window of HBM.  Everything the kernel
+//   in flight inside a compact, moving window of HBM.  Everything the path
 //   needs for a chunk is one 32-byte record prepared by the plan (DsChunkRec),
 //   so the only dependent load before the data is that record.  It handles the
 //   chunks that are whole units of one tile (contiguous, or rows of a 2-D view
-//   of at least 16 bytes each); it is small on purpose (few registers, full
-//   occupancy).
+//   of at least 16 bytes each).
 //
-// ds_move_kernel: the general routine, run over the list of the remaining
-//   chunks (tile boundaries, payload tails, padding, odd row lengths, N-D):
+// general path: the remaining chunks (tile boundaries, payload tails, padding,
+//   N-D views), taken from the plan's list of them:
 //   - A chunk that holds a few tiles walks them one after the other with the
 //     whole work-group ("direct" path).
 //   - A chunk that holds many small tiles takes them 64 at a time: every lane
@@ -296,21 +296,21 @@ __device__ __forceinline__ uint32_t wave_inclusive_scan(uint32_t x, uint32_t lan
   return x;
 }
 
+// One general chunk (number ci of the launch's list), whole work-group.
+// s_incl: inclusive scan of unit counts of the 64 tiles of a batch; s_begin: where each tile's clipped
+// range starts, relative to the chunk (both kWave words of LDS).
 template <bool PACK, int NT, int UNROLL, bool NTL, bool NTS>
-__global__ __launch_bounds__(NT) void ds_move_kernel(MoveArgs a) {
-  __shared__ uint32_t s_incl[kWave];   // inclusive scan of unit counts of the 64 tiles of a batch
-  __shared__ uint32_t s_begin[kWave];  // where each tile's clipped range starts, relative to the chunk
+__device__ __forceinline__ void general_chunk(const MoveArgs &a, uint32_t ci, uint32_t *s_incl, uint32_t *s_begin) {
   const uint32_t tid = threadIdx.x;
   const uint32_t lane = tid & (kWave - 1);
-
-  for (uint32_t ci = blockIdx.x; ci < a.n_chunks; ci += gridDim.x) {
+  {
     const uint64_t c = ci < a.n_extra ? a.extra[ci] : a.ids[ci - a.n_extra];
     const uint64_t c_begin = c << a.chunk_log2;
     uint64_t c_end = (c + 1) << a.chunk_log2;
     if (c_end > a.total) c_end = a.total;
     const uint64_t cb = c_begin > a.img_lo ? c_begin : a.img_lo;
     const uint64_t ce = c_end < a.img_hi ? c_end : a.img_hi;
-    if (cb >= ce) continue;
+    if (cb >= ce) return;
     const uint32_t t0 = a.first_tile[c];
     uint32_t t1 = a.first_tile[c + 1];
     if (a.tile_off[t1] >= c_end) --t1;  // that tile starts where this chunk ends
@@ -321,7 +321,7 @@ __global__ __launch_bounds__(NT) void ds_move_kernel(MoveArgs a) {
         const uint64_t lo = tb > cb ? tb : cb, hi = te < ce ? te : ce;
         if (lo < hi) move_tile_direct<PACK, NT, UNROLL, NTL, NTS>(a.tiles + t, tb, lo, hi, a.img, a.img_lo);
       }
-      continue;
+      return;
     }
 
     for (uint32_t bt = t0; bt <= t1; bt += kWave) {
@@ -365,7 +365,7 @@ __global__ __launch_bounds__(NT) void ds_move_kernel(MoveArgs a) {
   }
 }
 
-// ---- the lean kernel ----------------------------------------------------------
+// ---- the lean path -----------------------------------------------------------
 // bytes [s, s+16) of the 32 bytes a||b, 0 < s < 16
 __device__ __forceinline__ u32x4 splice(u32x4 a, u32x4 b, uint32_t s) {
   uint64_t x0 = a.x | ((uint64_t)a.y << 32), x1 = a.z | ((uint64_t)a.w << 32);
@@ -414,15 +414,13 @@ __device__ __forceinline__ void store_cut(uint8_t *p0, uint8_t *p1, uint32_t k, 
 // the work-group's chunk, so an out-of-range store would be dropped by the hardware.
 constexpr int kStorePolicySc0Sc1Nt = 1 | 2 | 16;  // sc0 | nt | sc1 in the intrinsic's aux operand
 
-// At most 5 waves per SIMD (the attribute makes the compiler pad the register allocation): measured, the
-// scatter runs 5 % faster with 4-5 resident waves than with the 8 its 42 registers would allow, and the
-// gather (5 by its own register use) is at its best there too -- fewer work-groups in flight keep the
-// addresses in a more compact window of HBM; with 3 or fewer both lose ~9 %.
+// Number of lean work items of a launch; item ci takes one lean chunk, whole work-group.
+__device__ __forceinline__ uint32_t lean_items(const LeanArgs &a) { return a.xcd_span ? a.xcd_span * 8u : a.n_chunks; }
+
 template <bool PACK, int NT, int UNROLL, bool NTL, bool NTS, bool BUFST>
-__global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(1, 5))) void ds_lean_kernel(LeanArgs a) {
+__device__ __forceinline__ void lean_chunk(const LeanArgs &a, uint32_t ci) {
   const uint32_t tid = threadIdx.x;
-  const uint32_t n_iter = a.xcd_span ? a.xcd_span * 8u : a.n_chunks;
-  for (uint32_t ci = blockIdx.x; ci < n_iter; ci += gridDim.x) {
+  {
     // Work-groups are dealt to the 8 XCDs round-robin (work-group i runs on XCD i mod 8).  Chunk
     // numbers are permuted so that each XCD walks ONE contiguous eighth of the range instead of every
     // eighth chunk: measured +1.5 % (7B rank) to +5 % (fragmentation set) on the gather and +4 to +8 %
@@ -430,12 +428,12 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(1, 5))) void
     uint32_t cm = ci;
     if (a.xcd_span) {
       cm = (ci & 7u) * a.xcd_span + (ci >> 3);
-      if (cm >= a.n_chunks) continue;
+      if (cm >= a.n_chunks) return;
     }
     const uint32_t c = a.c_lo + cm;
     const DsChunkRec r = a.recs[c];
     const uint32_t kind = r.kind & 0xFF;  // bits 8.. hold log2(itemsize)
-    if (kind == DS_CHUNK_GENERAL) continue;
+    if (kind == DS_CHUNK_GENERAL) return;
     uint8_t *imgp = a.img + (((uint64_t)c << a.chunk_log2) - a.img_lo);
     __amdgpu_buffer_rsrc_t image_rsrc;
     if (PACK && BUFST) image_rsrc = __builtin_amdgcn_make_buffer_rsrc(imgp, 0, NT * UNROLL * 16, 0x00020000);
@@ -513,56 +511,70 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(1, 5))) void
   }
 }
 
-// The general kernel gets its own stream, beside the lean kernel, when it has this many chunks.
-constexpr uint32_t kSideStreamMinChunks = 1024;
+// Both paths in one launch.  Work items are taken in rows of 8 (one per XCD, so that the lean items keep
+// their XCDs); every period-th row, gen_rows of them in all, holds 8 general chunks, the others 8 lean
+// items.  The general chunks are latency-bound (chains of table loads): spread evenly, from the first row
+// on, their bubbles are filled by the lean work-groups beside them and none is left for the tail.
+// Measured against two launches (lean kernel, then general kernel, or both side by side on two streams):
+// +2.7 % on the gather of the 7B rank, whose few general chunks cost a launch gap of their own, and
+// 0 to +1 % elsewhere.
+//
+// At most 5 waves per SIMD (the attribute makes the compiler pad the register allocation): measured, the
+// lean scatter runs 5 % faster with 4-5 resident waves than with the 8 its own registers would allow, and
+// the gather is at its best there too -- fewer work-groups in flight keep the addresses in a more compact
+// window of HBM; with 3 or fewer both lose ~9 %.
+//
+// A lean chunk is exactly 256 threads x UNROLL x 16 bytes; the general path always works in passes of
+// 256 x 4 units.
+template <bool PACK, int UNROLL, bool NTL, bool NTS, bool BUFST>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 5))) void ds_move_kernel(
+    LeanArgs la, MoveArgs ma, uint32_t gen_rows, uint32_t period) {
+  __shared__ uint32_t s_incl[kWave];
+  __shared__ uint32_t s_begin[kWave];
+  const uint32_t n_lean = lean_items(la);
+  const uint32_t n_iter = (gen_rows + (n_lean + 7u) / 8u) * 8u;
+  for (uint32_t wi = blockIdx.x; wi < n_iter; wi += gridDim.x) {
+    const uint32_t row = wi >> 3, q = row / period;
+    uint32_t before = (row + period - 1) / period;  // general rows before this one
+    if (before > gen_rows) before = gen_rows;
+    if (q * period == row && q < gen_rows) {
+      const uint32_t gi = q * 8u + (wi & 7u);
+      if (gi < ma.n_chunks) general_chunk<PACK, 256, 4, NTL, NTS>(ma, gi, s_incl, s_begin);
+    } else {
+      const uint32_t ci = (row - before) * 8u + (wi & 7u);
+      if (ci < n_lean) lean_chunk<PACK, 256, UNROLL, NTL, NTS, BUFST>(la, ci);
+    }
+  }
+}
 
 template <bool PACK, bool NTL, bool NTS, bool BUFST>
-int launch_both(const ds_plan *plan, const LeanArgs &la, const MoveArgs &ma, uint32_t grid_limit, hipStream_t stream) {
-  // Both kernels touch disjoint chunks, so they may run at the same time.  The general kernel is
-  // latency-bound (few resident waves, a chain of table loads per chunk); beside the lean kernel its
-  // bubbles are filled.  Fork/join with events; plain in-order launches when it has little to do.
-  const bool fork = la.n_chunks && ma.n_chunks >= kSideStreamMinChunks && grid_limit == 0 && plan->side_stream;
-  std::unique_lock<std::mutex> lk(plan->side_mu, std::defer_lock);
-  if (fork) {
-    lk.lock();
-    DS_HIP_TRY(hipEventRecord(plan->ev_fork, stream));
-    DS_HIP_TRY(hipStreamWaitEvent(plan->side_stream, plan->ev_fork, 0));
-    hipLaunchKernelGGL((ds_move_kernel<PACK, 256, 4, NTL, NTS>), dim3(ma.n_chunks), dim3(256), 0, plan->side_stream, ma);
-    DS_HIP_TRY(hipGetLastError());
-    DS_HIP_TRY(hipEventRecord(plan->ev_join, plan->side_stream));
+int launch_move(uint32_t chunk_log2, const LeanArgs &la, const MoveArgs &ma, uint32_t grid_limit, hipStream_t stream) {
+  const uint32_t gen_rows = (ma.n_chunks + 7u) / 8u;
+  const uint32_t lean_rows = ((la.xcd_span ? la.xcd_span * 8 : la.n_chunks) + 7u) / 8u;
+  const uint32_t rows = gen_rows + lean_rows;
+  if (rows == 0) return DS_OK;
+  const uint32_t period = gen_rows ? rows / gen_rows : 1u;  // >= 1
+  uint32_t grid = rows * 8u;
+  if (grid_limit && grid > grid_limit) grid = grid_limit;
+#define DS_MOVE(UN) \
+  hipLaunchKernelGGL((ds_move_kernel<PACK, UN, NTL, NTS, BUFST>), dim3(grid), dim3(256), 0, stream, la, ma, gen_rows, period)
+  switch (chunk_log2) {
+    case 13: DS_MOVE(2); break;
+    case 14: DS_MOVE(4); break;
+    case 15: DS_MOVE(8); break;
+    default: return DS_EINVAL;
   }
-  if (la.n_chunks) {
-    uint32_t grid = la.xcd_span ? la.xcd_span * 8 : la.n_chunks;
-    if (grid_limit && grid > grid_limit) grid = grid_limit;
-    // a lean chunk is exactly 256 threads x unroll x 16 bytes
-#define DS_LEAN(NTH, UN) \
-  hipLaunchKernelGGL((ds_lean_kernel<PACK, NTH, UN, NTL, NTS, BUFST>), dim3(grid), dim3(NTH), 0, stream, la)
-    switch (plan->chunk_log2) {
-      case 13: DS_LEAN(256, 2); break;
-      case 14: DS_LEAN(256, 4); break;
-      case 15: DS_LEAN(256, 8); break;
-      default: return DS_EINVAL;
-    }
-#undef DS_LEAN
-    DS_HIP_TRY(hipGetLastError());
-  }
-  if (fork) {
-    DS_HIP_TRY(hipStreamWaitEvent(stream, plan->ev_join, 0));
-  } else if (ma.n_chunks) {
-    uint32_t grid = ma.n_chunks;
-    if (grid_limit && grid > grid_limit) grid = grid_limit;
-    hipLaunchKernelGGL((ds_move_kernel<PACK, 256, 4, NTL, NTS>), dim3(grid), dim3(256), 0, stream, ma);
-    DS_HIP_TRY(hipGetLastError());
-  }
+#undef DS_MOVE
+  DS_HIP_TRY(hipGetLastError());
   return DS_OK;
 }
 
-// A plain contiguous copy in the lean kernel's shape (256 threads x 4 units per
+// A plain contiguous copy in the lean path's shape (256 threads x 4 units per
 // work-group, non-temporal 16-byte accesses): the measured ceiling the gather
 // is compared with, and the known-size kernel the HBM counters are scaled by.
 __global__ __launch_bounds__(256) void ds_copy_probe_kernel(const u32x4 *__restrict__ src, u32x4 *__restrict__ dst,
                                                             uint64_t n_units) {
-  // the same XCD-contiguous order of work-groups as the lean kernel
+  // the same XCD-contiguous order of work-groups as the lean path
   const uint32_t n_groups = (uint32_t)((n_units + 1023) / 1024), span = (n_groups + 7) / 8;
   const uint32_t g = (blockIdx.x & 7u) * span + (blockIdx.x >> 3);
   if (g >= n_groups) return;
@@ -601,7 +613,7 @@ int ds_launch_move(const ds_plan *plan, bool pack, uint8_t *img, uint64_t img_lo
   const uint64_t C = (uint64_t)1 << lg;
   const uint64_t n_total = plan->n_chunks();
   if (img_hi > plan->total_bytes || img_lo >= img_hi) return DS_ERANGE;
-  // whole chunks inside the range go to the lean kernel (which skips the general ones) ...
+  // whole chunks inside the range go down the lean path (which skips the general ones) ...
   uint64_t w_lo = (img_lo + C - 1) >> lg;
   uint64_t w_hi = img_hi >> lg;
   if (img_hi == plan->total_bytes) w_hi = n_total;  // the last chunk may be short; it is 'general' then
@@ -613,7 +625,7 @@ int ds_launch_move(const ds_plan *plan, bool pack, uint8_t *img, uint64_t img_lo
   la.c_lo = (uint32_t)w_lo;
   la.n_chunks = w_hi > w_lo ? (uint32_t)(w_hi - w_lo) : 0;
   la.xcd_span = ds_cfg_variant() == 3 ? 0 : (la.n_chunks + 7) / 8;
-  // ... the general ones among them, and the chunks cut by the range, to the general kernel
+  // ... the general ones among them, and the chunks cut by the range, down the general path
   MoveArgs ma;
   ma.tiles = plan->d_tiles;
   ma.tile_off = plan->d_tile_off;
@@ -643,14 +655,14 @@ int ds_launch_move(const ds_plan *plan, bool pack, uint8_t *img, uint64_t img_lo
   }
   const uint64_t variant = ds_cfg_variant();
   if (variant == 1) {  // plain loads and stores
-    return pack ? launch_both<true, false, false, false>(plan, la, ma, grid_limit, stream)
-                : launch_both<false, false, false, false>(plan, la, ma, grid_limit, stream);
+    return pack ? launch_move<true, false, false, false>(lg, la, ma, grid_limit, stream)
+                : launch_move<false, false, false, false>(lg, la, ma, grid_limit, stream);
   }
   if (variant == 2) {  // non-temporal global loads and stores everywhere (no buffer stores)
-    return pack ? launch_both<true, true, true, false>(plan, la, ma, grid_limit, stream)
-                : launch_both<false, true, true, false>(plan, la, ma, grid_limit, stream);
+    return pack ? launch_move<true, true, true, false>(lg, la, ma, grid_limit, stream)
+                : launch_move<false, true, true, false>(lg, la, ma, grid_limit, stream);
   }
   // default: non-temporal accesses, and the lean gather writes the image with "sc0 sc1 nt" buffer stores
-  return pack ? launch_both<true, true, true, true>(plan, la, ma, grid_limit, stream)
-              : launch_both<false, true, true, false>(plan, la, ma, grid_limit, stream);
+  return pack ? launch_move<true, true, true, true>(lg, la, ma, grid_limit, stream)
+              : launch_move<false, true, true, false>(lg, la, ma, grid_limit, stream);
 }

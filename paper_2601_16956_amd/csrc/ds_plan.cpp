@@ -12,14 +12,6 @@
 
 namespace {
 
-void free_device_side(ds_plan *p) {
-  if (p->ev_fork) (void)hipEventDestroy(p->ev_fork);
-  if (p->ev_join) (void)hipEventDestroy(p->ev_join);
-  if (p->side_stream) (void)hipStreamDestroy(p->side_stream);
-  p->ev_fork = p->ev_join = nullptr;
-  p->side_stream = nullptr;
-}
-
 thread_local int g_last_hip_error = 0;
 
 std::atomic<uint64_t> g_chunk_bytes{16u << 10};
@@ -140,9 +132,6 @@ int upload(ds_plan *p) {
   if (!p->general_ids.empty())
     DS_HIP_TRY(hipMemcpy(base + b_tiles + b_off + b_first + b_recs, p->general_ids.data(),
                          p->general_ids.size() * sizeof(uint32_t), hipMemcpyHostToDevice));
-  DS_HIP_TRY(hipStreamCreateWithFlags(&p->side_stream, hipStreamNonBlocking));
-  DS_HIP_TRY(hipEventCreateWithFlags(&p->ev_fork, hipEventDisableTiming));
-  DS_HIP_TRY(hipEventCreateWithFlags(&p->ev_join, hipEventDisableTiming));
   return DS_OK;
 }
 
@@ -303,7 +292,7 @@ int ds_plan_create(const ds_shard_desc *desc, size_t n, uint64_t align, uint32_t
             p->first_tile[c] = (uint32_t)t;
           }
           p->first_tile[n_chunks] = (uint32_t)p->tiles.size();
-          // classify every chunk for the lean kernel
+          // classify every chunk for the kernel's lean path
           p->recs.resize(n_chunks);
           for (uint64_t c = 0; c < n_chunks; ++c) {
             DsChunkRec &r = p->recs[c];
@@ -343,7 +332,6 @@ int ds_plan_create(const ds_shard_desc *desc, size_t n, uint64_t align, uint32_t
   }
   if (rc == DS_OK && !(flags & DS_PLAN_HOST_ONLY)) rc = upload(p);
   if (rc != DS_OK) {
-    free_device_side(p);
     if (p->dev_blob) (void)hipFree(p->dev_blob);
     delete p;
     return rc;
@@ -355,7 +343,6 @@ int ds_plan_create(const ds_shard_desc *desc, size_t n, uint64_t align, uint32_t
 int ds_plan_destroy(ds_plan *plan) {
   if (!plan) return DS_EINVAL;
   int rc = DS_OK;
-  free_device_side(plan);
   if (plan->dev_blob) {
     hipError_t e = hipFree(plan->dev_blob);
     if (e != hipSuccess) { ds_set_hip_error(e); rc = DS_EHIP; }

@@ -199,7 +199,7 @@ def test_range_and_argument_errors_on_device_plan():
 def test_sizes_beyond_32_bits():
     """One contiguous shard of 5 GiB (offsets inside a tile beyond 2^32) and a 2-D
     view whose rows are longer than 2^31 bytes (the 64-bit index path of the
-    general kernel), pack and restore, whole image and whole arena."""
+    general path), pack and restore, whole image and whole arena."""
     ds, orc, gu = _mods()
     import torch
     GiB = 1 << 30
