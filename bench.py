@@ -235,6 +235,7 @@ def main() -> int:
     copy_src = torch.empty_like(image_dev)
     nprobe = total & ~15
     probe_med, probe_best = timed(lambda: ds.ds_copy_probe(image_dev.data_ptr(), copy_src.data_ptr(), nprobe, stream))
+    dtod_med, _ = timed(lambda: copy_src.copy_(image_dev))      # the runtime's own device-to-device copy
     del copy_src
 
     # ---- parity of this very run against the CPU oracle + the CPU baseline --------------------
@@ -328,11 +329,12 @@ def main() -> int:
         gemm_ms = a.elapsed_time(b) / 20
         G = max(4, int(round(1.5 * one["total_ms"] / gemm_ms)))   # forward/backward ~1.5x one snapshot
 
-        def loop(with_snapshots: bool):
+        def loop(with_snapshots: bool, G: int = G):
             evs = []
             prev = None
             a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             torch.cuda.synchronize()
+            w0 = time.perf_counter()
             a.record()
             for _ in range(args.gemm_iters):
                 for _ in range(G):                                # state is only read here
@@ -348,6 +350,7 @@ def main() -> int:
             for ev in evs:
                 ds.ds_event_wait(ev)
                 ds.ds_event_destroy(ev)
+            loop.wall_ms = (time.perf_counter() - w0) * 1e3      # until the last snapshot is in the host ring
             return a.elapsed_time(b)
 
         loop(True)
@@ -360,42 +363,80 @@ def main() -> int:
             "slowdown_pct": round(100.0 * (with_s - base) / base, 2),
             "ring_bytes": args.ring_bytes,
         }
+        # stress point: a compute window far shorter than one snapshot, so every gate stalls and the
+        # loop runs at the pace of the link (back-pressure of the ring and the staging slots)
+        Gs = max(1, G // 6)
+        base_s = min(loop(False, Gs) for _ in range(2))
+        with_ss = loop(True, Gs)
+        overlap["stress"] = {
+            "gemms_per_iter": Gs, "ms_without_snapshots": round(base_s, 2), "ms_with_snapshots": round(with_ss, 2),
+            "wall_ms_until_last_snapshot_done": round(loop.wall_ms, 2),
+            "snapshot_GBps_sustained": round(payload * args.gemm_iters / loop.wall_ms / 1e6, 2),
+            "note": "compute window 1/6 of the default: the gate and the staging slots make the loop wait for the link",
+        }
         del A, B, C
 
     ds.ds_engine_destroy(eng)
     torch.cuda.synchronize()
 
-    # ---- the file tier: snapshot -> ring -> file with writer threads, then file -> ring -> GPU ---
+    # ---- the checkpoint file: snapshot -> ring -> tensor region (writer threads) with an object log
+    # appended behind it at the same time, trailer last; then file -> ring -> GPU ---------------
     file_tier = None
     if not args.no_file:
-        path = os.path.join(args.file_dir, f"ds_bench_{os.getpid()}.img")
+        import threading
         eng2 = ds.ds_engine_create(args.ring_bytes, args.chunk_bytes, args.stage_slot_bytes, args.stage_slots, 0, 0,
                                    args.copy_streams, args.first_launch_bytes)
+        obj_chunk = os.urandom(64 << 10)
+        n_obj_threads, chunks_per_thread = 2, 128             # 16 MiB of serialized objects in 64 KiB chunks
+
+        def one_dir(d):
+            path = os.path.join(d, f"ds_bench_{os.getpid()}.ckpt")
+            try:
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                ev = ds.ds_snapshot_async(eng2, plan, stream)
+                ck = ds.ds_ckpt_create(path, plan, ds.DS_FILE_DIRECT)
+                ds.ds_ckpt_flush_snapshot(ck, ev, args.file_threads)
+
+                def objects(t):
+                    for k in range(chunks_per_thread):
+                        ds.ds_ckpt_append(ck, 1000 + t * 16 + k % 16, obj_chunk)
+                ts = [threading.Thread(target=objects, args=(t,)) for t in range(n_obj_threads)]
+                for t in ts:
+                    t.start()
+                ds.ds_event_wait_on_stream(ev, stream)
+                for t in ts:
+                    t.join()
+                nbytes, _ = ds.ds_ckpt_finish(ck)
+                flush_s = time.perf_counter() - t0
+                ds.ds_event_wait(ev)
+                ds.ds_event_destroy(ev)
+                t0 = time.perf_counter()
+                rd = ds.ds_ckpt_open(path)
+                rev = ds.ds_ckpt_restore(rd, eng2, plan, args.file_threads, ds.DS_FILE_DIRECT, stream)
+                ds.ds_event_wait(rev)
+                load_s = time.perf_counter() - t0
+                ds.ds_event_destroy(rev)
+                lay = ds.ds_ckpt_layout_info(rd)
+                ds.ds_ckpt_close(rd)
+                return {"dir": d, "file_bytes": nbytes, "object_log_bytes": lay["log_end"] - lay["tensor_bytes"],
+                        "object_chunks": lay["n_chunks"],
+                        "snapshot_to_file_GBps": round(nbytes / flush_s / 1e9, 2),
+                        "file_to_gpu_GBps": round(payload / load_s / 1e9, 2)}
+            except ds.DsError as e:
+                return {"dir": d, "error": str(e)}
+            finally:
+                if os.path.exists(path):
+                    os.remove(path)
+
         try:
-            torch.cuda.synchronize()
-            t0 = time.perf_counter()
-            ev = ds.ds_snapshot_async(eng2, plan, stream)
-            fl = ds.ds_flush_start(ev, path, args.file_threads, ds.DS_FILE_DIRECT)
-            ds.ds_event_wait_on_stream(ev, stream)
-            nbytes, _ = ds.ds_flush_wait(fl)
-            flush_s = time.perf_counter() - t0
-            ds.ds_event_wait(ev)
-            ds.ds_event_destroy(ev)
-            t0 = time.perf_counter()
-            rev = ds.ds_restore_from_file(eng2, plan, path, args.file_threads, ds.DS_FILE_DIRECT, stream)
-            ds.ds_event_wait(rev)
-            load_s = time.perf_counter() - t0
-            ds.ds_event_destroy(rev)
-            file_tier = {"dir": args.file_dir, "threads": args.file_threads, "bytes": nbytes,
-                         "snapshot_to_file_GBps": round(payload / flush_s / 1e9, 2),
-                         "file_to_gpu_GBps": round(payload / load_s / 1e9, 2),
-                         "note": "request -> last byte written (page cache, no fsync); file -> tensors restored"}
-        except ds.DsError as e:
-            file_tier = {"error": str(e)}
+            dirs = [args.file_dir] + (["/dev/shm"] if os.path.isdir("/dev/shm") and args.file_dir != "/dev/shm" else [])
+            file_tier = {"threads": args.file_threads,
+                         "note": "request -> trailer written (page cache, no fsync); open + check -> tensors restored; "
+                                 "/dev/shm is memory-backed: the software path without the disk",
+                         "runs": [one_dir(d) for d in dirs]}
         finally:
             ds.ds_engine_destroy(eng2)
-            if os.path.exists(path):
-                os.remove(path)
     torch.cuda.synchronize()
     ds.ds_plan_destroy(plan)
 
@@ -428,6 +469,7 @@ def main() -> int:
             "pack_best_GBps": round(algo_bytes / pack_best / 1e6, 1),
             "unpack_ms": round(unpack_med, 4), "unpack_GBps": round(2 * payload / unpack_med / 1e6, 1),
             "copy_probe_GBps": round(2 * nprobe / probe_med / 1e6, 1),    # plain copy, same shape: the ceiling
+            "runtime_d2d_copy_GBps": round(2 * total / dtod_med / 1e6, 1),   # torch copy_ (hipMemcpy device to device)
             "pack_vs_copy_probe": round((algo_bytes / pack_med) / (2 * nprobe / probe_med), 4),
         },
         "restore": {"GBps_null_producer": round(payload / restore_s / 1e9, 2), "ms": round(restore_s * 1e3, 3),

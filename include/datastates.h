@@ -60,6 +60,7 @@ typedef enum ds_dtype { DS_F32 = 0, DS_BF16 = 1, DS_F16 = 2, DS_I64 = 3, DS_U8 =
 #define DS_EBUSY (-8)    /* object still has work in flight / chunk not released  */
 #define DS_ESTATE (-9)   /* call not valid in this state (e.g. release of a chunk never handed out) */
 #define DS_EIO (-10)     /* a file operation failed; see ds_last_errno()           */
+#define DS_EFORMAT (-11) /* not a checkpoint file of this format, or a damaged one   */
 
 /*
  * One shard: a view into device memory plus its place in the file.
@@ -83,6 +84,8 @@ typedef struct ds_plan ds_plan;
 typedef struct ds_engine ds_engine;
 typedef struct ds_event ds_event;
 typedef struct ds_flush ds_flush;
+typedef struct ds_ckpt ds_ckpt;               /* a checkpoint file being written */
+typedef struct ds_ckpt_reader ds_ckpt_reader; /* a checkpoint file opened for recovery */
 
 /* ---- layout and plan (Sec. V-A3 composite provider, duty (a): sizes and
  *      offsets in the stream; Sec. V-A5 rule (1)) ---------------------------- */
@@ -137,6 +140,10 @@ int ds_plan_info(const ds_plan *plan, ds_plan_stats *out);
  * (Sec. V-A5 rule (3)).  Any out pointer may be NULL. */
 int ds_plan_shard(const ds_plan *plan, size_t i, uint64_t *tensor_id, uint32_t *dtype,
                   uint64_t *file_offset, uint64_t *nbytes);
+
+/* Shape of manifest entry i: *ndim and the first *ndim extents of shape[DS_MAX_DIMS]
+ * (the rest are set to 0).  Either out pointer may be NULL. */
+int ds_plan_shard_shape(const ds_plan *plan, size_t i, uint32_t *ndim, int64_t *shape);
 
 /* ---- the kernels (gather = Sec. V-A1 coalescing done on the device; scatter
  *      = recovery, Sec. V-A5 rule (3)) -------------------------------------- */
@@ -318,6 +325,105 @@ int ds_restore_from_file(ds_engine *engine, const ds_plan *plan, const char *pat
 
 /* errno of the file operation that last produced DS_EIO on this thread. */
 int ds_last_errno(void);
+
+/* ---- the checkpoint file (Sec. V-A5: tensors at offsets fixed in advance,
+ *      serialized objects appended behind them as a concurrent log, a metadata
+ *      header at the END of the file that describes both) ---------------------
+ *
+ * Layout, all integers little-endian:
+ *   [0, T)            the tensor region: the image of the plan, byte for byte
+ *   [T, E)            the object log.  A chunk of len bytes claims the next
+ *                     round_up(len, 8) bytes; bytes never written read as 0
+ *   [E, E+80n+32m)    the trailer: n tensor entries, then m chunk entries
+ *       tensor entry (80 B): u64 tensor_id, u32 dtype, u32 ndim, u64 shape[6]
+ *                     (unused extents 0), u64 file_offset, u64 nbytes; plan order
+ *       chunk entry (32 B): u64 object_id, u64 seq, u64 file_offset, u64 len;
+ *                     sorted by (object_id, seq); an object is the concatenation
+ *                     of its chunks seq = 0, 1, ...
+ *   last 64 B         the footer: char magic[8] = "DSCKPT01", u32 version = 1,
+ *                     u32 flags = 0, u64 align, u64 T, u64 E, u64 n, u64 m,
+ *                     u32 crc of the trailer, u32 crc of the 60 footer bytes before
+ *                     it (CRC-32 of IEEE 802.3, as in zlib)
+ * The paper fixes the three rules, not the bytes: the encoding is this library's.
+ * A rank that writes several files per checkpoint uses one plan and one
+ * ds_ckpt per file.
+ */
+
+/*
+ * Creates / truncates `path` for a checkpoint of `plan` (which may be a
+ * DS_PLAN_HOST_ONLY plan when the tensor region comes from host memory).
+ * flags: DS_FILE_DIRECT / DS_FILE_SYNC as for a flush.  The plan must outlive
+ * the ds_ckpt.  Errors: DS_EINVAL, DS_ENOMEM, DS_EIO.
+ */
+int ds_ckpt_create(const char *path, const ds_plan *plan, uint32_t flags, ds_ckpt **out);
+
+/* Fills the tensor region from a snapshot of the same plan: ds_flush_start on
+ * this file (`threads` writers).  Once per ds_ckpt; returns at once.
+ * Errors: DS_EINVAL, DS_ESTATE (a second call), DS_ENOMEM. */
+int ds_ckpt_flush_snapshot(ds_ckpt *ckpt, ds_event *snapshot, uint32_t threads);
+
+/* Writes len bytes of HOST memory at file_off of the tensor region
+ * (file_off + len <= T).  Thread-safe.  Errors: DS_EINVAL, DS_ERANGE, DS_EIO. */
+int ds_ckpt_write_region(ds_ckpt *ckpt, uint64_t file_off, const void *host, uint64_t len);
+
+/*
+ * Appends one chunk of a serialized object to the log.  Thread-safe and
+ * concurrent with the flush of the tensors: the position is claimed with one
+ * atomic add, then written.  Chunks of one object_id are numbered in call
+ * order.  len may be 0 (data may then be NULL).  Errors: DS_EINVAL, DS_EIO.
+ */
+int ds_ckpt_append(ds_ckpt *ckpt, uint64_t object_id, const void *data, uint64_t len);
+
+/*
+ * Waits for the flush (if one was started), writes trailer and footer, syncs
+ * under DS_FILE_SYNC, closes the file and frees the ds_ckpt (also on error).
+ * No ds_ckpt_append may be running.  Out pointers may be NULL: the file's
+ * length, seconds since ds_ckpt_create.  Errors: DS_EIO, or the error that
+ * ended the snapshot / the first failed append.
+ */
+int ds_ckpt_finish(ds_ckpt *ckpt, uint64_t *file_bytes, double *seconds);
+
+typedef struct ds_ckpt_layout {
+  uint64_t align;
+  uint64_t tensor_bytes;   /* T                              */
+  uint64_t log_end;        /* E: where the trailer starts    */
+  uint64_t n_tensors;
+  uint64_t n_chunks;       /* log chunks                     */
+  uint64_t n_objects;      /* distinct object ids            */
+  uint64_t file_bytes;
+} ds_ckpt_layout;
+
+typedef struct ds_ckpt_tensor {
+  uint64_t tensor_id;
+  uint32_t dtype;
+  uint32_t ndim;
+  int64_t shape[DS_MAX_DIMS];
+  uint64_t file_offset;
+  uint64_t nbytes;
+} ds_ckpt_tensor;
+
+/*
+ * Opens a checkpoint file and checks it: footer magic, version and checksum,
+ * trailer bounds and checksum, every tensor inside [0, T) at a multiple of the
+ * alignment, every chunk inside [T, E), chunk order and numbering.
+ * Errors: DS_EIO (cannot open / read), DS_EFORMAT, DS_ENOMEM.
+ */
+int ds_ckpt_open(const char *path, ds_ckpt_reader **out);
+int ds_ckpt_close(ds_ckpt_reader *reader);
+int ds_ckpt_layout_info(const ds_ckpt_reader *reader, ds_ckpt_layout *out);
+/* Tensor entry i (0 <= i < n_tensors). */
+int ds_ckpt_tensor_info(const ds_ckpt_reader *reader, size_t i, ds_ckpt_tensor *out);
+/* The k-th object in ascending id order (0 <= k < n_objects): its id and length. */
+int ds_ckpt_object_at(const ds_ckpt_reader *reader, size_t k, uint64_t *object_id, uint64_t *nbytes);
+/* Reads object `object_id` whole into buf (capacity cap); *len = its length.
+ * Errors: DS_EINVAL (no such object), DS_ERANGE (cap too small; *len is set), DS_EIO. */
+int ds_ckpt_object_read(const ds_ckpt_reader *reader, uint64_t object_id, void *buf, uint64_t cap, uint64_t *len);
+/* DS_OK if the file's tensor entries, alignment and T are exactly the plan's
+ * manifest (ids, dtypes, shapes, offsets, sizes, order); DS_EFORMAT if not. */
+int ds_ckpt_matches_plan(const ds_ckpt_reader *reader, const ds_plan *plan);
+/* ds_ckpt_matches_plan, then ds_restore_from_file on the tensor region. */
+int ds_ckpt_restore(const ds_ckpt_reader *reader, ds_engine *engine, const ds_plan *plan, uint32_t threads,
+                    uint32_t flags, void *compute_stream, ds_event **out);
 
 /* ---- misc ---------------------------------------------------------------- */
 

@@ -19,6 +19,7 @@ DS_F32, DS_BF16, DS_F16, DS_I64, DS_U8 = 0, 1, 2, 3, 4
 DS_OK, DS_NOT_READY, DS_EOF = 0, 1, 2
 DS_EINVAL, DS_EALIGN, DS_EOVERLAP, DS_EGAP, DS_ERANGE, DS_ENOMEM, DS_EHIP, DS_EBUSY, DS_ESTATE, DS_EIO = (
     -1, -2, -3, -4, -5, -6, -7, -8, -9, -10)
+DS_EFORMAT = -11
 DS_FILE_DIRECT, DS_FILE_SYNC = 1, 2
 DS_PLAN_STRICT, DS_PLAN_HOST_ONLY = 1, 2
 DS_ENGINE_AUTO_RELEASE = 1
@@ -32,6 +33,9 @@ EXPORTS = [
     "ds_strerror", "ds_last_hip_error", "ds_config_set", "ds_config_get", "ds_copy_probe",
     "ds_restore_begin", "ds_restore_next_slot", "ds_restore_submit",
     "ds_flush_start", "ds_flush_wait", "ds_restore_from_file", "ds_last_errno",
+    "ds_plan_shard_shape", "ds_ckpt_create", "ds_ckpt_flush_snapshot", "ds_ckpt_write_region", "ds_ckpt_append",
+    "ds_ckpt_finish", "ds_ckpt_open", "ds_ckpt_close", "ds_ckpt_layout_info", "ds_ckpt_tensor_info",
+    "ds_ckpt_object_at", "ds_ckpt_object_read", "ds_ckpt_matches_plan", "ds_ckpt_restore",
 ]
 
 
@@ -77,6 +81,22 @@ class ds_snapshot_stats(ctypes.Structure):
         ("capture_ms", ctypes.c_double),
         ("total_ms", ctypes.c_double),
         ("submit_host_ms", ctypes.c_double),
+    ]
+
+
+class ds_ckpt_layout(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_uint64) for n in (
+        "align", "tensor_bytes", "log_end", "n_tensors", "n_chunks", "n_objects", "file_bytes")]
+
+
+class ds_ckpt_tensor(ctypes.Structure):
+    _fields_ = [
+        ("tensor_id", ctypes.c_uint64),
+        ("dtype", ctypes.c_uint32),
+        ("ndim", ctypes.c_uint32),
+        ("shape", ctypes.c_int64 * DS_MAX_DIMS),
+        ("file_offset", ctypes.c_uint64),
+        ("nbytes", ctypes.c_uint64),
     ]
 
 
@@ -147,6 +167,20 @@ def _load() -> ctypes.CDLL:
         "ds_flush_wait": ([vp, P(u64), P(ctypes.c_double)], ctypes.c_int),
         "ds_restore_from_file": ([vp, vp, ctypes.c_char_p, u32, u32, vp, P(vp)], ctypes.c_int),
         "ds_last_errno": ([], ctypes.c_int),
+        "ds_plan_shard_shape": ([vp, sz, P(u32), P(ctypes.c_int64)], ctypes.c_int),
+        "ds_ckpt_create": ([ctypes.c_char_p, vp, u32, P(vp)], ctypes.c_int),
+        "ds_ckpt_flush_snapshot": ([vp, vp, u32], ctypes.c_int),
+        "ds_ckpt_write_region": ([vp, u64, vp, u64], ctypes.c_int),
+        "ds_ckpt_append": ([vp, u64, vp, u64], ctypes.c_int),
+        "ds_ckpt_finish": ([vp, P(u64), P(ctypes.c_double)], ctypes.c_int),
+        "ds_ckpt_open": ([ctypes.c_char_p, P(vp)], ctypes.c_int),
+        "ds_ckpt_close": ([vp], ctypes.c_int),
+        "ds_ckpt_layout_info": ([vp, P(ds_ckpt_layout)], ctypes.c_int),
+        "ds_ckpt_tensor_info": ([vp, sz, P(ds_ckpt_tensor)], ctypes.c_int),
+        "ds_ckpt_object_at": ([vp, sz, P(u64), P(u64)], ctypes.c_int),
+        "ds_ckpt_object_read": ([vp, u64, vp, u64, P(u64)], ctypes.c_int),
+        "ds_ckpt_matches_plan": ([vp, vp], ctypes.c_int),
+        "ds_ckpt_restore": ([vp, vp, vp, u32, u32, vp, P(vp)], ctypes.c_int),
     }
     for name, (args, res) in sig.items():
         fn = getattr(L, name)
@@ -353,3 +387,87 @@ def ds_restore_from_file(engine: int, plan: int, path: str, threads: int = 0, fl
 
 def ds_last_errno() -> int:
     return int(_lib.ds_last_errno())
+
+
+def ds_plan_shard_shape(plan: int, i: int) -> Tuple[int, ...]:
+    nd = ctypes.c_uint32(0)
+    shape = (ctypes.c_int64 * DS_MAX_DIMS)()
+    _check(_lib.ds_plan_shard_shape(plan, i, ctypes.byref(nd), shape), "ds_plan_shard_shape")
+    return tuple(int(shape[j]) for j in range(nd.value))
+
+
+def ds_ckpt_create(path: str, plan: int, flags: int = 0) -> int:
+    out = ctypes.c_void_p(0)
+    _check(_lib.ds_ckpt_create(path.encode(), plan, flags, ctypes.byref(out)), "ds_ckpt_create")
+    return int(out.value)
+
+
+def ds_ckpt_flush_snapshot(ckpt: int, snapshot: int, threads: int = 0) -> None:
+    _check(_lib.ds_ckpt_flush_snapshot(ckpt, snapshot, threads), "ds_ckpt_flush_snapshot")
+
+
+def ds_ckpt_write_region(ckpt: int, file_off: int, host_ptr: int, nbytes: int) -> None:
+    _check(_lib.ds_ckpt_write_region(ckpt, file_off, host_ptr, nbytes), "ds_ckpt_write_region")
+
+
+def ds_ckpt_append(ckpt: int, object_id: int, data: bytes) -> None:
+    _check(_lib.ds_ckpt_append(ckpt, object_id, ctypes.c_char_p(data) if data else None, len(data)),
+           "ds_ckpt_append")
+
+
+def ds_ckpt_finish(ckpt: int) -> Tuple[int, float]:
+    """(file length, seconds since ds_ckpt_create)."""
+    nbytes, secs = ctypes.c_uint64(0), ctypes.c_double(0)
+    _check(_lib.ds_ckpt_finish(ckpt, ctypes.byref(nbytes), ctypes.byref(secs)), "ds_ckpt_finish")
+    return int(nbytes.value), float(secs.value)
+
+
+def ds_ckpt_open(path: str) -> int:
+    out = ctypes.c_void_p(0)
+    _check(_lib.ds_ckpt_open(path.encode(), ctypes.byref(out)), "ds_ckpt_open")
+    return int(out.value)
+
+
+def ds_ckpt_close(reader: int) -> None:
+    _check(_lib.ds_ckpt_close(reader), "ds_ckpt_close")
+
+
+def ds_ckpt_layout_info(reader: int) -> dict:
+    lay = ds_ckpt_layout()
+    _check(_lib.ds_ckpt_layout_info(reader, ctypes.byref(lay)), "ds_ckpt_layout_info")
+    return {n: int(getattr(lay, n)) for n, _ in ds_ckpt_layout._fields_}
+
+
+def ds_ckpt_tensor_info(reader: int, i: int) -> dict:
+    t = ds_ckpt_tensor()
+    _check(_lib.ds_ckpt_tensor_info(reader, i, ctypes.byref(t)), "ds_ckpt_tensor_info")
+    return {"tensor_id": int(t.tensor_id), "dtype": int(t.dtype), "shape": tuple(int(t.shape[j]) for j in range(t.ndim)),
+            "file_offset": int(t.file_offset), "nbytes": int(t.nbytes)}
+
+
+def ds_ckpt_object_at(reader: int, k: int) -> Tuple[int, int]:
+    oid, nb = ctypes.c_uint64(0), ctypes.c_uint64(0)
+    _check(_lib.ds_ckpt_object_at(reader, k, ctypes.byref(oid), ctypes.byref(nb)), "ds_ckpt_object_at")
+    return int(oid.value), int(nb.value)
+
+
+def ds_ckpt_object_read(reader: int, object_id: int) -> bytes:
+    ln = ctypes.c_uint64(0)
+    rc = _lib.ds_ckpt_object_read(reader, object_id, None, 0, ctypes.byref(ln))
+    if rc not in (DS_OK, DS_ERANGE):
+        _check(rc, "ds_ckpt_object_read")
+    buf = ctypes.create_string_buffer(max(int(ln.value), 1))
+    _check(_lib.ds_ckpt_object_read(reader, object_id, buf, ln.value, ctypes.byref(ln)), "ds_ckpt_object_read")
+    return buf.raw[:ln.value]
+
+
+def ds_ckpt_matches_plan(reader: int, plan: int) -> None:
+    _check(_lib.ds_ckpt_matches_plan(reader, plan), "ds_ckpt_matches_plan")
+
+
+def ds_ckpt_restore(reader: int, engine: int, plan: int, threads: int = 0, flags: int = 0,
+                    compute_stream: int = 0) -> int:
+    out = ctypes.c_void_p(0)
+    _check(_lib.ds_ckpt_restore(reader, engine, plan, threads, flags, compute_stream, ctypes.byref(out)),
+           "ds_ckpt_restore")
+    return int(out.value)

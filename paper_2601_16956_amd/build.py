@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libdatastates_hip.so")
-SOURCES = ["ds_plan.cpp", "ds_kernels.hip", "ds_engine.cpp", "ds_file.cpp"]
+SOURCES = ["ds_plan.cpp", "ds_kernels.hip", "ds_engine.cpp", "ds_file.cpp", "ds_ckpt.cpp"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-pthread",

@@ -6,8 +6,8 @@
 // ds_snapshot_next_chunk / ds_snapshot_release_chunk, a file restore is a
 // producer for ds_restore_next_slot / ds_restore_submit.  Writes and reads go
 // to the byte offsets the plan fixed (Sec. V-A5 rule (1)), so several threads
-// work on one file without coordination.  Plain pwrite/pread: the image has no
-// liburing, and the point here is the overlap of file I/O with the copies,
+// work on one file without coordination.  Plain pwrite/pread: liburing is not
+// installed here, and the point is the overlap of file I/O with the copies,
 // not the submission interface.
 #include <fcntl.h>
 #include <sys/stat.h>
@@ -23,7 +23,7 @@
 #include <thread>
 #include <vector>
 
-#include "datastates.h"
+#include "ds_internal.h"
 
 namespace {
 
@@ -78,6 +78,7 @@ struct ds_flush {
   ds_event *ev = nullptr;
   int fd_direct = -1, fd_buffered = -1;
   uint32_t flags = 0;
+  bool own_fds = true;  // false: the descriptors belong to a checkpoint writer, which syncs and closes them
   std::thread dispatcher;
   std::vector<std::thread> writers;
   std::mutex mu;
@@ -155,26 +156,18 @@ void dispatcher_main(ds_flush *f) {
 
 }  // namespace
 
-extern "C" {
-
-int ds_last_errno(void) { return g_last_errno; }
-
-int ds_flush_start(ds_event *ev, const char *path, uint32_t threads, uint32_t flags, ds_flush **out) {
-  if (!ev || !path || !out || (flags & ~(DS_FILE_DIRECT | DS_FILE_SYNC))) return DS_EINVAL;
+int ds_flush_start_fds(ds_event *ev, int fd_buffered, int fd_direct, uint32_t threads, uint32_t flags,
+                       ds_flush **out) {
+  if (!ev || !out || fd_buffered < 0 || (flags & ~(DS_FILE_DIRECT | DS_FILE_SYNC))) return DS_EINVAL;
   if (threads == 0) threads = 4;
   if (threads > 64) return DS_EINVAL;
   ds_flush *f = new (std::nothrow) ds_flush;
   if (!f) return DS_ENOMEM;
   f->ev = ev;
   f->flags = flags;
-  f->fd_buffered = open(path, O_WRONLY | O_CREAT | O_TRUNC | O_CLOEXEC, 0644);
-  if (f->fd_buffered < 0) {
-    g_last_errno = errno;
-    delete f;
-    return DS_EIO;
-  }
-  // direct I/O where the file system has it; chunks that are not 4 KiB-shaped take the buffered descriptor
-  if (flags & DS_FILE_DIRECT) f->fd_direct = open(path, O_WRONLY | O_DIRECT | O_CLOEXEC);
+  f->own_fds = false;
+  f->fd_buffered = fd_buffered;
+  f->fd_direct = fd_direct;
   f->t0 = now_s();
   // writers first: a dispatcher without anyone to release slots would wait for ever
   try {
@@ -196,12 +189,36 @@ int ds_flush_start(ds_event *ev, const char *path, uint32_t threads, uint32_t fl
     }
     f->cv.notify_all();
     for (std::thread &t : f->writers) t.join();
-    if (f->fd_direct >= 0) close(f->fd_direct);
-    close(f->fd_buffered);
     delete f;
     return DS_ENOMEM;
   }
   *out = f;
+  return DS_OK;
+}
+
+void ds_set_errno(int e) { g_last_errno = e; }
+
+extern "C" {
+
+int ds_last_errno(void) { return g_last_errno; }
+
+int ds_flush_start(ds_event *ev, const char *path, uint32_t threads, uint32_t flags, ds_flush **out) {
+  if (!ev || !path || !out || (flags & ~(DS_FILE_DIRECT | DS_FILE_SYNC))) return DS_EINVAL;
+  if (threads > 64) return DS_EINVAL;
+  const int fd_buffered = open(path, O_WRONLY | O_CREAT | O_TRUNC | O_CLOEXEC, 0644);
+  if (fd_buffered < 0) {
+    g_last_errno = errno;
+    return DS_EIO;
+  }
+  // direct I/O where the file system has it; chunks that are not 4 KiB-shaped take the buffered descriptor
+  const int fd_direct = (flags & DS_FILE_DIRECT) ? open(path, O_WRONLY | O_DIRECT | O_CLOEXEC) : -1;
+  int rc = ds_flush_start_fds(ev, fd_buffered, fd_direct, threads, flags, out);
+  if (rc != DS_OK) {
+    if (fd_direct >= 0) close(fd_direct);
+    close(fd_buffered);
+    return rc;
+  }
+  (*out)->own_fds = true;
   return DS_OK;
 }
 
@@ -212,16 +229,18 @@ int ds_flush_wait(ds_flush *f, uint64_t *bytes_written, double *seconds) {
   for (std::thread &t : f->writers)
     if (t.joinable()) t.join();
   int status = f->status.load();
-  if (status == DS_OK && (f->flags & DS_FILE_SYNC) && fsync(f->fd_buffered) != 0) {
-    status = DS_EIO;
-    f->err_no.store(errno);
+  if (f->own_fds) {
+    if (status == DS_OK && (f->flags & DS_FILE_SYNC) && fsync(f->fd_buffered) != 0) {
+      status = DS_EIO;
+      f->err_no.store(errno);
+    }
+    if (f->fd_direct >= 0) close(f->fd_direct);
+    if (close(f->fd_buffered) != 0 && status == DS_OK) {
+      status = DS_EIO;
+      f->err_no.store(errno);
+    }
   }
   f->t1 = now_s();
-  if (f->fd_direct >= 0) close(f->fd_direct);
-  if (close(f->fd_buffered) != 0 && status == DS_OK) {
-    status = DS_EIO;
-    f->err_no.store(errno);
-  }
   if (bytes_written) *bytes_written = f->bytes.load();
   if (seconds) *seconds = f->t1 - f->t0;
   g_last_errno = f->err_no.load();

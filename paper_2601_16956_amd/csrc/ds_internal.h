@@ -43,9 +43,16 @@ static_assert(sizeof(DsChunkRec) == 32, "two records per 64 bytes");
 struct DsManifestEntry {
   uint64_t tensor_id;
   uint32_t dtype;
+  uint32_t ndim;
+  int64_t shape[DS_MAX_DIMS];  // unused extents 0
   uint64_t file_offset;
   uint64_t nbytes;
 };
+
+// The flush of a snapshot into a file that somebody else opened and will close (the checkpoint writer).
+// fd_direct may be -1.
+int ds_flush_start_fds(ds_event *ev, int fd_buffered, int fd_direct, uint32_t threads, uint32_t flags, ds_flush **out);
+void ds_set_errno(int e);  // what ds_last_errno() returns on this thread
 
 struct ds_plan {
   uint64_t align = 0;

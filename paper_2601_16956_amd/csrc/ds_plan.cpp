@@ -171,6 +171,7 @@ const char *ds_strerror(int code) {
     case DS_EBUSY: return "work still in flight";
     case DS_ESTATE: return "call not valid in this state";
     case DS_EIO: return "a file operation failed (see ds_last_errno)";
+    case DS_EFORMAT: return "not a checkpoint file of this format, or a damaged one";
     default: return "unknown datastates status";
   }
 }
@@ -236,7 +237,13 @@ int ds_plan_create(const ds_shard_desc *desc, size_t n, uint64_t align, uint32_t
         if (bad_stride) { rc = DS_EINVAL; break; }
         if (!view_is_injective(d)) { rc = DS_EOVERLAP; break; }
       }
-      p->manifest[i] = {d.tensor_id, d.dtype, d.file_offset, sizes[i]};
+      DsManifestEntry &me = p->manifest[i];
+      me.tensor_id = d.tensor_id;
+      me.dtype = d.dtype;
+      me.ndim = d.ndim;
+      for (uint32_t j = 0; j < DS_MAX_DIMS; ++j) me.shape[j] = j < d.ndim ? d.shape[j] : 0;
+      me.file_offset = d.file_offset;
+      me.nbytes = sizes[i];
       p->payload_bytes += sizes[i];
       end_max = std::max(end_max, d.file_offset + sizes[i]);
     }
@@ -373,6 +380,15 @@ int ds_plan_shard(const ds_plan *plan, size_t i, uint64_t *tensor_id, uint32_t *
   if (dtype) *dtype = m.dtype;
   if (file_offset) *file_offset = m.file_offset;
   if (nbytes) *nbytes = m.nbytes;
+  return DS_OK;
+}
+
+int ds_plan_shard_shape(const ds_plan *plan, size_t i, uint32_t *ndim, int64_t *shape) {
+  if (!plan || i >= plan->manifest.size()) return DS_EINVAL;
+  const DsManifestEntry &m = plan->manifest[i];
+  if (ndim) *ndim = m.ndim;
+  if (shape)
+    for (uint32_t j = 0; j < DS_MAX_DIMS; ++j) shape[j] = m.shape[j];
   return DS_OK;
 }
 

@@ -1,0 +1,288 @@
+"""The checkpoint file: the oracle's statement of it against a hand-written
+file and the rules it must obey, then the library's writer and reader against
+the oracle, byte for byte (CPU only: the tensor region comes from host memory
+through ds_ckpt_write_region; the GPU path into the same file is covered by the
+gpu tests)."""
+import ctypes
+import json
+import os
+import random
+import threading
+import zlib
+
+import numpy as np
+import pytest
+
+import paper_2601_16956_amd as ds
+import workloads as W
+from oracle import ckpt_format as fmt
+from oracle import ds_oracle as orc
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+
+
+def crc32_bitwise(data: bytes) -> int:
+    """CRC-32 of IEEE 802.3 by its definition: the bits of the message, least significant first,
+    through a shift register with the reflected polynomial 0xEDB88320; register starts and ends inverted."""
+    reg = 0xFFFFFFFF
+    for byte in data:
+        for k in range(8):
+            bit = ((byte >> k) ^ reg) & 1
+            reg >>= 1
+            if bit:
+                reg ^= 0xEDB88320
+    return reg ^ 0xFFFFFFFF
+
+
+def golden():
+    g = json.load(open(os.path.join(HERE, "golden", "ckpt_hand.json")))
+    body = bytes.fromhex(g["image_hex"] + "".join(g["log_hex"]))
+    trailer = bytes.fromhex("".join(g["trailer_hex"]))
+    footer = bytes.fromhex("".join(g["footer_hex_without_checksums"]))
+    footer += crc32_bitwise(trailer).to_bytes(4, "little")
+    footer += crc32_bitwise(footer).to_bytes(4, "little")
+    blob = body + trailer + footer
+    assert len(blob) == g["file_bytes"]
+    return g, blob
+
+
+def test_checksum_is_the_textbook_crc32():
+    assert crc32_bitwise(b"123456789") == 0xCBF43926          # the published check value
+    assert zlib.crc32(b"123456789") == 0xCBF43926
+    rng = random.Random(5)
+    for n in (0, 1, 7, 64, 1000):
+        data = bytes(rng.randrange(256) for _ in range(n))
+        assert zlib.crc32(data) == crc32_bitwise(data)
+
+
+def test_oracle_builds_the_hand_written_file():
+    g, blob = golden()
+    tensors = [(t["tensor_id"], t["dtype"], tuple(t["shape"]), t["file_offset"], t["nbytes"]) for t in g["tensors"]]
+    appends = [(oid, bytes.fromhex(h)) for oid, h in g["appends"]]
+    built = fmt.build_file(g["align"], bytes.fromhex(g["image_hex"]), tensors, appends)
+    assert built == blob
+    back = fmt.parse_file(blob)
+    assert back["tensors"] == tensors and back["image"] == bytes.fromhex(g["image_hex"])
+    assert back["objects"] == {int(k): bytes.fromhex(v) for k, v in g["objects"].items()}
+    assert (back["align"], back["tensor_bytes"], back["log_end"]) == (16, 32, 56)
+
+
+def test_oracle_rules_on_random_files():
+    rng = random.Random(11)
+    for case in range(30):
+        align = rng.choice([16, 64, 512])
+        T = align * rng.randrange(0, 5)
+        image = bytes(rng.randrange(256) for _ in range(T))
+        tensors = [(rng.randrange(1 << 40), rng.randrange(5), (rng.randrange(9),), 0, min(T, rng.randrange(9)))
+                   for _ in range(rng.randrange(4))]
+        appends = [(rng.choice([1, 2, 3, 1 << 63]), bytes(rng.randrange(256) for _ in range(rng.choice([0, 1, 8, 13, 100]))))
+                   for _ in range(rng.randrange(12))]
+        blob = fmt.build_file(align, image, tensors, appends)
+        back = fmt.parse_file(blob)
+        assert blob[:T] == image                               # rule 1: the tensors are where they were planned
+        want = {}
+        for oid, data in appends:
+            want[oid] = want.get(oid, b"") + data
+        assert back["objects"] == want                         # rule 2: the log gives every object back
+        assert back["tensors"] == tensors                      # rule 3: found from the end of the file
+        assert back["log_end"] - T == sum((len(d) + 7) // 8 * 8 for _, d in appends)
+        # damage anywhere in trailer or footer is noticed
+        if len(blob) > T:
+            pos = rng.randrange(back["log_end"], len(blob))
+            bad = bytearray(blob)
+            bad[pos] ^= 0x40
+            with pytest.raises(fmt.FormatError):
+                fmt.parse_file(bytes(bad))
+        with pytest.raises(fmt.FormatError):
+            fmt.parse_file(blob[:-1])
+
+
+# ---- the library against the oracle --------------------------------------------------------
+
+def _host_plan(w):
+    n = len(w.shards)
+    d = ds.make_descs(w.shards, w.arena.ctypes.data)
+    total = ds.ds_layout_assign(d, n, w.align)
+    plan = ds.ds_plan_create(d, n, w.align, ds.DS_PLAN_HOST_ONLY)
+    tab = orc.table(w.shards, w.arena.ctypes.data)
+    assert orc.layout(tab, n, w.align) == total
+    image = orc.pack(tab, n, total)
+    return plan, d, n, total, image
+
+
+def _manifest(plan, n):
+    out = []
+    for i in range(n):
+        tid, dt, off, nb = ds.ds_plan_shard(plan, i)
+        out.append((tid, dt, ds.ds_plan_shard_shape(plan, i), off, nb))
+    return out
+
+
+def _write_with_library(path, plan, image, appends, flags=0):
+    ck = ds.ds_ckpt_create(path, plan, flags)
+    img = np.ascontiguousarray(image)
+    # the tensor region in three pieces, out of order
+    cuts = [0, img.size // 3 // 16 * 16, img.size // 2 // 16 * 16, img.size]
+    for a, b in [(cuts[2], cuts[3]), (cuts[0], cuts[1]), (cuts[1], cuts[2])]:
+        ds.ds_ckpt_write_region(ck, a, img.ctypes.data + a, b - a)
+    for oid, data in appends:
+        ds.ds_ckpt_append(ck, oid, data)
+    return ds.ds_ckpt_finish(ck)
+
+
+def test_library_writes_the_hand_written_file(tmp_path):
+    g, blob = golden()
+    arena = np.frombuffer(bytes.fromhex(g["image_hex"]), dtype=np.uint8).copy()
+    d = (ds.ds_shard_desc * 1)()
+    d[0].base = arena.ctypes.data
+    d[0].dtype = ds.DS_U8
+    d[0].ndim = 1
+    d[0].shape[0] = 20
+    d[0].strides[0] = 1
+    d[0].tensor_id = 7
+    d[0].file_offset = 0
+    plan = ds.ds_plan_create(d, 1, 16, ds.DS_PLAN_HOST_ONLY)
+    path = str(tmp_path / "hand.ckpt")
+    nbytes, _ = _write_with_library(path, plan, arena, [(oid, bytes.fromhex(h)) for oid, h in g["appends"]])
+    assert nbytes == len(blob)
+    assert open(path, "rb").read() == blob
+    ds.ds_plan_destroy(plan)
+
+
+@pytest.mark.parametrize("maker", [
+    lambda: W.tiny_gpt(),
+    lambda: W.fragmentation(300, max_bytes=1 << 14, seed=21),
+])
+def test_library_file_equals_oracle_file_and_reads_back(tmp_path, maker):
+    w = maker()
+    plan, d, n, total, image = _host_plan(w)
+    rng = random.Random(3)
+    appends = [(rng.choice([10, 11, 12, 2 ** 64 - 1]), bytes(rng.randrange(256) for _ in range(rng.choice([0, 3, 8, 4097]))))
+               for _ in range(25)]
+    path = str(tmp_path / "a.ckpt")
+    nbytes, secs = _write_with_library(path, plan, image, appends, flags=ds.DS_FILE_SYNC)
+    want = fmt.build_file(w.align, image.tobytes(), _manifest(plan, n), appends)
+    got = open(path, "rb").read()
+    assert nbytes == len(want) and got == want
+
+    # the library's reader on the oracle's bytes
+    path2 = str(tmp_path / "b.ckpt")
+    open(path2, "wb").write(want)
+    r = ds.ds_ckpt_open(path2)
+    lay = ds.ds_ckpt_layout_info(r)
+    back = fmt.parse_file(want)
+    assert lay["align"] == w.align and lay["tensor_bytes"] == total and lay["log_end"] == back["log_end"]
+    assert lay["n_tensors"] == n and lay["n_chunks"] == len(appends) and lay["file_bytes"] == len(want)
+    assert lay["n_objects"] == len(back["objects"])
+    for i in (0, n // 2, n - 1):
+        t = ds.ds_ckpt_tensor_info(r, i)
+        assert (t["tensor_id"], t["dtype"], t["shape"], t["file_offset"], t["nbytes"]) == back["tensors"][i]
+    ids = []
+    for k in range(lay["n_objects"]):
+        oid, nb = ds.ds_ckpt_object_at(r, k)
+        ids.append(oid)
+        assert nb == len(back["objects"][oid])
+        assert ds.ds_ckpt_object_read(r, oid) == back["objects"][oid]
+    assert ids == sorted(back["objects"])
+    with pytest.raises(ds.DsError) as e:
+        ds.ds_ckpt_object_read(r, 999)
+    assert e.value.code == ds.DS_EINVAL
+    ds.ds_ckpt_matches_plan(r, plan)
+    # another plan (one shard fewer) does not match
+    plan2 = ds.ds_plan_create(d, n - 1, w.align, ds.DS_PLAN_HOST_ONLY)
+    with pytest.raises(ds.DsError) as e:
+        ds.ds_ckpt_matches_plan(r, plan2)
+    assert e.value.code == ds.DS_EFORMAT
+    ds.ds_plan_destroy(plan2)
+    ds.ds_ckpt_close(r)
+    ds.ds_plan_destroy(plan)
+
+
+def test_concurrent_appends_form_a_valid_log(tmp_path):
+    w = W.tiny_gpt()
+    plan, d, n, total, image = _host_plan(w)
+    path = str(tmp_path / "c.ckpt")
+    ck = ds.ds_ckpt_create(path, plan, 0)
+    n_threads, per = 6, 200
+    sent = {}
+
+    def worker(t):
+        rng = random.Random(100 + t)
+        mine = b""
+        for k in range(per):
+            data = bytes([t]) * rng.choice([0, 1, 5, 8, 33, 1000])
+            ds.ds_ckpt_append(ck, 1000 + t, data)           # ctypes drops the GIL during the call
+            mine += data
+        sent[1000 + t] = mine
+
+    img = np.ascontiguousarray(image)
+    ts = [threading.Thread(target=worker, args=(t,)) for t in range(n_threads)]
+    for t in ts:
+        t.start()
+    ds.ds_ckpt_write_region(ck, 0, img.ctypes.data, img.size)   # the tensors go in at the same time
+    for t in ts:
+        t.join()
+    ds.ds_ckpt_finish(ck)
+    back = fmt.parse_file(open(path, "rb").read())
+    assert back["image"] == image.tobytes()
+    assert back["objects"] == sent
+    assert back["n_chunks"] == n_threads * per
+    ds.ds_plan_destroy(plan)
+
+
+def test_damaged_files_are_refused(tmp_path):
+    w = W.tiny_gpt()
+    plan, d, n, total, image = _host_plan(w)
+    good = fmt.build_file(w.align, image.tobytes(), _manifest(plan, n), [(1, b"abc"), (2, b"")])
+    lay = fmt.parse_file(good)
+    E = lay["log_end"]
+    cases = {
+        "truncated": good[:-1],
+        "magic": good[:-64] + b"X" + good[-63:],
+        "trailer bit": good[:E + 5] + bytes([good[E + 5] ^ 1]) + good[E + 6:],
+        "footer bit": good[:-30] + bytes([good[-30] ^ 1]) + good[-29:],
+        "tiny": b"DSCKPT01",
+        "extra tail": good + b"\0" * 8,
+    }
+    for name, blob in cases.items():
+        path = str(tmp_path / "bad.ckpt")
+        open(path, "wb").write(blob)
+        with pytest.raises(ds.DsError) as e:
+            ds.ds_ckpt_open(path)
+        assert e.value.code == ds.DS_EFORMAT, name
+        with pytest.raises(fmt.FormatError):
+            fmt.parse_file(blob)
+    with pytest.raises(ds.DsError) as e:
+        ds.ds_ckpt_open(str(tmp_path / "does_not_exist"))
+    assert e.value.code == ds.DS_EIO
+    # a consistent file whose entries lie: checksums recomputed, so only the bounds checks can object
+    import struct
+    trailer = bytearray(good[E:-64])
+    struct.pack_into("<Q", trailer, 64, total)               # first tensor's offset = T, its bytes now end beyond T
+    footer = bytearray(good[-64:])
+    struct.pack_into("<I", footer, 56, zlib.crc32(bytes(trailer)))
+    struct.pack_into("<I", footer, 60, zlib.crc32(bytes(footer[:60])))
+    path = str(tmp_path / "lie.ckpt")
+    open(path, "wb").write(good[:E] + bytes(trailer) + bytes(footer))
+    with pytest.raises(ds.DsError) as e:
+        ds.ds_ckpt_open(path)
+    assert e.value.code == ds.DS_EFORMAT
+    ds.ds_plan_destroy(plan)
+
+
+def test_ckpt_argument_errors(tmp_path):
+    w = W.tiny_gpt()
+    plan, d, n, total, image = _host_plan(w)
+    with pytest.raises(ds.DsError) as e:
+        ds.ds_ckpt_create(str(tmp_path / "no_such_dir" / "x"), plan, 0)
+    assert e.value.code == ds.DS_EIO
+    with pytest.raises(ds.DsError) as e:
+        ds.ds_ckpt_create(str(tmp_path / "x"), plan, 64)
+    assert e.value.code == ds.DS_EINVAL
+    ck = ds.ds_ckpt_create(str(tmp_path / "x"), plan, 0)
+    img = np.ascontiguousarray(image)
+    with pytest.raises(ds.DsError) as e:
+        ds.ds_ckpt_write_region(ck, total - 8, img.ctypes.data, 16)
+    assert e.value.code == ds.DS_ERANGE
+    ds.ds_ckpt_finish(ck)
+    ds.ds_plan_destroy(plan)

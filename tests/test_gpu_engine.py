@@ -327,3 +327,77 @@ def test_flush_to_file_and_restore_from_file(tmp_path, flags_name):
     finally:
         ds.ds_engine_destroy(eng)
         dw.close()
+
+
+def test_checkpoint_file_from_a_snapshot_with_concurrent_object_log(tmp_path):
+    """Snapshot -> ring -> tensor region of a checkpoint file while three
+    threads append object chunks to the log behind it; the oracle's parser must
+    find the oracle's image, every object and the plan's manifest; the file
+    restores the tensors through the pipeline; a file of another plan is refused."""
+    import threading
+    from oracle import ckpt_format as fmt
+    ds, orc, gu, torch = _mods()
+    w = W.fragmentation(2500, max_bytes=1 << 17, seed=93)
+    print("[case] checkpoint file", flush=True)
+    want, offs, tab = gu.oracle_image(w)
+    dw = gu.DeviceWorkload(w)
+    eng = ds.ds_engine_create(6 * MiB, 1 * MiB, 8 * MiB, 2, 0, 0, 1)
+    s = torch.cuda.current_stream().cuda_stream
+    path = str(tmp_path / "rank0.ckpt")
+    sent = {}
+
+    def producer(t, ck):
+        rng = np.random.default_rng(500 + t)
+        mine = b""
+        for k in range(40):
+            data = rng.integers(0, 256, size=int(rng.choice([0, 7, 64, 5000])), dtype=np.uint8).tobytes()
+            ds.ds_ckpt_append(ck, 70 + t, data)
+            mine += data
+        sent[70 + t] = mine
+
+    try:
+        ev = ds.ds_snapshot_async(eng, dw.plan, s)
+        ck = ds.ds_ckpt_create(path, dw.plan, 0)
+        ds.ds_ckpt_flush_snapshot(ck, ev, 3)
+        with pytest.raises(ds.DsError) as e:
+            ds.ds_ckpt_flush_snapshot(ck, ev, 3)
+        assert e.value.code == ds.DS_ESTATE
+        ts = [threading.Thread(target=producer, args=(t, ck)) for t in range(3)]
+        for t in ts:
+            t.start()
+        ds.ds_event_wait_on_stream(ev, s)
+        for t in ts:
+            t.join()
+        nbytes, secs = ds.ds_ckpt_finish(ck)
+        ds.ds_event_wait(ev)
+        ds.ds_event_destroy(ev)
+        blob = open(path, "rb").read()
+        assert nbytes == len(blob)
+        back = fmt.parse_file(blob)
+        assert gu.first_mismatch(np.frombuffer(back["image"], dtype=np.uint8), want) is None
+        assert back["objects"] == sent
+        n = len(w.shards)
+        assert back["tensors"] == [ds.ds_plan_shard(dw.plan, i)[:2] + (ds.ds_plan_shard_shape(dw.plan, i),)
+                                   + ds.ds_plan_shard(dw.plan, i)[2:] for i in range(n)]
+
+        r = ds.ds_ckpt_open(path)
+        dw.arena.fill_(0xA5)
+        rev = ds.ds_ckpt_restore(r, eng, dw.plan, 3, 0, s)
+        ds.ds_event_wait(rev)
+        ds.ds_event_destroy(rev)
+        w.arena[:] = 0xA5
+        orc.unpack(tab, n, want)
+        assert gu.first_mismatch(dw.arena_host(), w.arena) is None
+        for oid, data in sent.items():
+            assert ds.ds_ckpt_object_read(r, oid) == data
+        # a plan over other shards does not match this file
+        w2 = W.tiny_gpt()
+        dw2 = gu.DeviceWorkload(w2)
+        with pytest.raises(ds.DsError) as e:
+            ds.ds_ckpt_restore(r, eng, dw2.plan, 2, 0, s)
+        assert e.value.code == ds.DS_EFORMAT
+        dw2.close()
+        ds.ds_ckpt_close(r)
+    finally:
+        ds.ds_engine_destroy(eng)
+        dw.close()

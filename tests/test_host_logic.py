@@ -33,7 +33,7 @@ def test_struct_sizes_match_the_header():
 
 
 def test_strerror_covers_all_codes():
-    for code in (0, 1, 2, -1, -2, -3, -4, -5, -6, -7, -8, -9, -10):
+    for code in (0, 1, 2, -1, -2, -3, -4, -5, -6, -7, -8, -9, -10, -11):
         assert "unknown" not in ds.ds_strerror(code)
     assert "unknown" in ds.ds_strerror(-99)
 
