@@ -55,7 +55,7 @@ def main() -> int:
     ap.add_argument("--chunk-bytes", type=int, default=32 * MiB, help="one device-to-host copy / ring slot")
     ap.add_argument("--stage-slot-bytes", type=int, default=2 * GiB, help="device staging slot = bytes per gather launch")
     ap.add_argument("--stage-slots", type=int, default=2)
-    ap.add_argument("--copy-streams", type=int, default=1)
+    ap.add_argument("--copy-streams", type=int, default=2)
     ap.add_argument("--first-launch-bytes", type=int, default=0, help="short first gather launch (0 = none)")
     ap.add_argument("--no-overlap", action="store_true", help="skip the concurrent-GEMM leg (configs[4])")
     ap.add_argument("--no-cpu-baseline", action="store_true")

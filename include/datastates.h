@@ -183,7 +183,8 @@ typedef struct ds_engine_opts {
   uint32_t stage_slots;      /* number of device staging slots (>= 1).  0 = 2                       */
   uint32_t pack_grid_limit;  /* max work-groups resident per gather launch; 0 = one per chunk       */
   uint32_t flags;            /* DS_ENGINE_*                                                         */
-  uint32_t copy_streams;     /* copy streams the chunks alternate over: 1 or 2.  0 = 1              */
+  uint32_t copy_streams;     /* copy streams the chunks alternate over: 1 or 2.  0 = 2 (the gap
+                                between two copies on one stream is hidden by the other stream's copy) */
   uint64_t first_launch_bytes; /* image bytes of the first gather launch of a snapshot; multiple of
                                 d2h_chunk_bytes, <= stage_slot_bytes.  A short first launch lets the
                                 first copy start earlier; the gather of the rest then runs beside that

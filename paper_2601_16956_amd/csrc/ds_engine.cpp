@@ -282,7 +282,7 @@ int ds_engine_create(const ds_engine_opts *o, ds_engine **out) {
   const uint64_t ring_bytes = o->host_ring_bytes ? o->host_ring_bytes : (2ull << 30);
   const uint64_t slot = o->stage_slot_bytes ? o->stage_slot_bytes : (1ull << 30);
   const uint32_t slots = o->stage_slots ? o->stage_slots : 2;
-  const uint32_t ncs = o->copy_streams ? o->copy_streams : 1;
+  const uint32_t ncs = o->copy_streams ? o->copy_streams : 2;
   const uint64_t first = o->first_launch_bytes ? o->first_launch_bytes : slot;
   if ((chunk & 4095) || slot % chunk || first % chunk || first > slot || ring_bytes < chunk ||
       ncs > (uint32_t)kMaxCopyStreams || slots > 1024)
@@ -685,9 +685,11 @@ int ds_restore_submit(ds_event *ev, const void *host_ptr) {
   const uint64_t ghi = glo + S < ev->plan->total_bytes ? glo + S : ev->plan->total_bytes;
   const uint32_t s = (uint32_t)(gi % g->stage_slots);
   uint8_t *slot = g->stage + (uint64_t)s * S;
-  hipStream_t cs = g->copy_stream[0];
-  // first chunk of a group: its staging slot must have been scattered out by the group that used it before
-  if (c.file_off == glo && gi >= g->stage_slots) W_TRY(hipStreamWaitEvent(cs, ev->group_done[gi - g->stage_slots], 0));
+  // chunks alternate over the copy streams, as in a snapshot
+  hipStream_t cs = g->copy_stream[k % (uint32_t)g->n_copy_streams];
+  // the staging slot must have been scattered out by the group that used it before (a wait per chunk:
+  // either stream may carry the group's first chunk; it costs nothing once the event has fired)
+  if (gi >= g->stage_slots) W_TRY(hipStreamWaitEvent(cs, ev->group_done[gi - g->stage_slots], 0));
   W_TRY(hipMemcpyAsync(slot + (c.file_off - glo), host_ptr, c.len, hipMemcpyHostToDevice, cs));
   W_TRY(hipEventRecord(g->ring_done[c.ring_slot], cs));
   g->ring_busy[c.ring_slot] = 1;
@@ -699,7 +701,11 @@ int ds_restore_submit(ds_event *ev, const void *host_ptr) {
     ev->pack_begin.push_back(b);
     W_TRY(hipEventCreate(&e));
     ev->pack_end.push_back(e);
+    // every copy of the group has landed: the last one, and the one before it, which is the last one of
+    // the other copy stream (each stream runs its copies in order)
     W_TRY(hipStreamWaitEvent(g->pack_stream, g->ring_done[c.ring_slot], 0));
+    if (g->n_copy_streams > 1 && k > 0)
+      W_TRY(hipStreamWaitEvent(g->pack_stream, g->ring_done[ev->chunks[k - 1].ring_slot], 0));
     W_TRY(hipEventRecord(b, g->pack_stream));
     int rc = ds_launch_move(ev->plan, false, slot, glo, ghi, g->grid_limit, g->pack_stream);
     if (rc != DS_OK) return rc;

@@ -128,7 +128,7 @@ def test_back_pressure_slow_consumer_and_queued_snapshots():
     w = W.tiny_gpt()
     want, _, _ = gu.oracle_image(w)
     dw = gu.DeviceWorkload(w)
-    eng = ds.ds_engine_create(2 * MiB, 1 * MiB, 2 * MiB, 2, 0, 0, 1)
+    eng = ds.ds_engine_create(2 * MiB, 1 * MiB, 2 * MiB, 2, 0, 0, 2)
     s = torch.cuda.current_stream().cuda_stream
     try:
         ev1 = ds.ds_snapshot_async(eng, dw.plan, s)
@@ -294,7 +294,7 @@ def test_flush_to_file_and_restore_from_file(tmp_path, flags_name):
     print(f"[case] file tier {flags_name}", flush=True)
     want, offs, tab = gu.oracle_image(w)
     dw = gu.DeviceWorkload(w)
-    eng = ds.ds_engine_create(6 * MiB, 1 * MiB, 8 * MiB, 2, 0, 0, 1)     # ring far smaller than the image
+    eng = ds.ds_engine_create(6 * MiB, 1 * MiB, 8 * MiB, 2, 0, 0, 2)     # ring far smaller than the image
     s = torch.cuda.current_stream().cuda_stream
     path = str(tmp_path / "image.bin")
     try:
@@ -341,7 +341,7 @@ def test_checkpoint_file_from_a_snapshot_with_concurrent_object_log(tmp_path):
     print("[case] checkpoint file", flush=True)
     want, offs, tab = gu.oracle_image(w)
     dw = gu.DeviceWorkload(w)
-    eng = ds.ds_engine_create(6 * MiB, 1 * MiB, 8 * MiB, 2, 0, 0, 1)
+    eng = ds.ds_engine_create(6 * MiB, 1 * MiB, 8 * MiB, 2, 0, 0, 0)
     s = torch.cuda.current_stream().cuda_stream
     path = str(tmp_path / "rank0.ckpt")
     sent = {}
