@@ -217,6 +217,9 @@ int ds_snapshot_async(ds_engine *engine, const ds_plan *plan, void *compute_stre
  * read into staging.  Returns when the wait has been enqueued; blocks the
  * host only while the engine has not yet issued the last gather (e.g. the
  * host ring is full and the consumer is behind: the paper's back-pressure).
+ * Hence, when staging is smaller than the image, the thread that calls the
+ * gate must not be the one that consumes the chunks: it would wait for room
+ * that only it can make.
  */
 int ds_event_wait_on_stream(ds_event *ev, void *stream);
 

@@ -3,6 +3,7 @@ configuration the benchmark times (default chunk size and kernel variant):
 the whole image and the whole restored arena are compared with the CPU oracle
 byte for byte (the oracle packs these sizes in seconds with host threads)."""
 import os
+import threading
 import time
 
 import numpy as np
@@ -63,5 +64,39 @@ def test_full_size_pack_and_restore(name):
         orc.unpack(tab, n, want)
         print(f"[step] restored arena back at {time.time() - t0:.1f}s", flush=True)
         assert gu.first_mismatch(back, w.arena) is None, gu.first_mismatch(back, w.arena)
+        # the same image through the engine as the benchmark configures it (2 GiB ring of 32 MiB slots,
+        # 2 x 2 GiB staging, two copy streams), with a consumer that copies every chunk out of the ring
+        import ctypes
+        del image                                                  # the tensors hold the oracle's image again
+        eng = ds.ds_engine_create(2 << 30, 32 << 20, 2 << 30, 2, 0, 0, 2)
+        try:
+            ev = ds.ds_snapshot_async(eng, dw.plan, s)
+            got = np.empty(total, dtype=np.uint8)
+            seen = [0]
+
+            def consumer():     # its own thread, as a flush would be: the gate below may block until it has made room
+                while True:
+                    ch = ds.ds_snapshot_next_chunk(ev)
+                    if ch is None:
+                        break
+                    ptr, off, ln = ch
+                    assert off == seen[0]
+                    ctypes.memmove(got.ctypes.data + off, ptr, ln)
+                    ds.ds_snapshot_release_chunk(ev, ptr)
+                    seen[0] += ln
+
+            th = threading.Thread(target=consumer)
+            th.start()
+            ds.ds_event_wait_on_stream(ev, s)
+            th.join()
+            seen = seen[0]
+            ds.ds_event_wait(ev)
+            st = ds.ds_event_stats(ev)
+            ds.ds_event_destroy(ev)
+            assert seen == total and st["n_pack_launches"] == (total + (2 << 30) - 1) // (2 << 30)
+            print(f"[step] engine snapshot consumed at {time.time() - t0:.1f}s", flush=True)
+            assert gu.first_mismatch(got, want) is None, gu.first_mismatch(got, want)
+        finally:
+            ds.ds_engine_destroy(eng)
     finally:
         dw.close()
