@@ -63,6 +63,9 @@ def main() -> int:
     ap.add_argument("--file-dir", default="/tmp", help="where the file-tier leg writes its image")
     ap.add_argument("--file-threads", type=int, default=8)
     ap.add_argument("--gemm-iters", type=int, default=12, help="iterations of the overlap leg")
+    ap.add_argument("--experiments", action="store_true",
+                    help="also run the capture variants that are measured, not shipped (direct gather into pinned "
+                         "host memory; grid-limited gathers under the GEMM stream)")
     ap.add_argument("--timed-only", action="store_true",
                     help="stop after the timed region (so that a kernel trace holds the timed launches only)")
     ap.add_argument("--kernels-only", action="store_true",
@@ -310,6 +313,7 @@ def main() -> int:
     rst = ds.ds_event_stats(rev)
     ds.ds_event_destroy(rev)
 
+    experiments = {}
     # ---- configs[4]: snapshots under a concurrent bf16 GEMM stream -----------------------------
     overlap = None
     if not args.no_overlap:
@@ -329,7 +333,7 @@ def main() -> int:
         gemm_ms = a.elapsed_time(b) / 20
         G = max(4, int(round(1.5 * one["total_ms"] / gemm_ms)))   # forward/backward ~1.5x one snapshot
 
-        def loop(with_snapshots: bool, G: int = G):
+        def loop(with_snapshots: bool, G: int = G, eng=eng):
             evs = []
             prev = None
             a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -374,7 +378,89 @@ def main() -> int:
             "snapshot_GBps_sustained": round(payload * args.gemm_iters / loop.wall_ms / 1e6, 2),
             "note": "compute window 1/6 of the default: the gate and the staging slots make the loop wait for the link",
         }
+        if args.experiments:
+            # capture variants, measured only.  (1) The gather limited to a few resident work-groups: does a
+            # slower, narrower gather disturb the GEMM stream less?
+            experiments["grid_limited_gather"] = []
+            for limit in (4096, 1024, 256):
+                eng_x = ds.ds_engine_create(args.ring_bytes, args.chunk_bytes, args.stage_slot_bytes, args.stage_slots,
+                                            limit, ds.DS_ENGINE_AUTO_RELEASE, args.copy_streams, args.first_launch_bytes)
+                ev = ds.ds_snapshot_async(eng_x, plan, stream)
+                ds.ds_event_wait(ev)
+                st = ds.ds_event_stats(ev)
+                ds.ds_event_destroy(ev)
+                loop(True, G, eng_x)
+                with_x = min(loop(True, G, eng_x) for _ in range(2))
+                experiments["grid_limited_gather"].append({
+                    "resident_workgroups": limit, "gather_ms": round(st["pack_ms"], 3),
+                    "capture_ms": round(st["capture_ms"], 3),
+                    "slowdown_pct": round(100.0 * (with_x - base) / base, 2)})
+                ds.ds_engine_destroy(eng_x)
         del A, B, C
+
+    if args.experiments:
+        # (2) No staging and no copy: the gather writes straight into pinned host memory over the link.
+        host_img = torch.empty(max(total, 16), dtype=torch.uint8, pin_memory=True)
+        d_med, d_best = timed(lambda: ds.ds_pack(plan, host_img.data_ptr(), 0, total, stream), reps=5, warm=1)
+        ok = None
+        if not args.no_cpu_baseline:
+            from oracle import ds_oracle as orc
+            arena.copy_(torch.from_numpy(w.arena))        # the overlap leg has mutated the tensors: same bytes on both sides
+            ds.ds_pack(plan, host_img.data_ptr(), 0, total, stream)
+            torch.cuda.synchronize()
+            tab = orc.table(w.shards, w.arena.ctypes.data)
+            assert orc.layout(tab, n, w.align) == total
+            want = orc.pack(tab, n, total, threads=cores)
+            got = host_img[:total].numpy()
+            ok = all(np.array_equal(got[lo:lo + (1 << 28)], want[lo:lo + (1 << 28)]) for lo in range(0, total, 1 << 28))
+            del want
+        direct = {
+            "ms": round(d_med, 3), "GBps": round(payload / d_med / 1e6, 2), "best_GBps": round(payload / d_best / 1e6, 2),
+            "byte_exact_vs_oracle": ok,
+            "note": "the kernel holds the tensors for the whole transfer, so the gate opens after this time, "
+                    "not after the 0.5 ms of the staged gather; resident_workgroups 0 = one work-group per chunk"}
+        if overlap is not None:
+            side = torch.cuda.Stream()                    # default priority
+
+            def loop_direct():
+                prev = None
+                a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                torch.cuda.synchronize()
+                a.record()
+                for _ in range(args.gemm_iters):
+                    for _ in range(overlap["gemms_per_iter"]):
+                        torch.matmul(gA, gB, out=gC)
+                    if prev is not None:
+                        torch.cuda.current_stream().wait_event(prev)   # the gate: the whole transfer
+                    arena.add_(1)
+                    req = torch.cuda.Event()
+                    req.record()
+                    side.wait_event(req)
+                    ds.ds_pack(plan, host_img.data_ptr(), 0, total, side.cuda_stream)
+                    prev = torch.cuda.Event()
+                    prev.record(side)
+                b.record()
+                torch.cuda.synchronize()
+                return a.elapsed_time(b)
+
+            M = 8192
+            gA = torch.randn(M, M, device=dev, dtype=torch.bfloat16)
+            gB = torch.randn(M, M, device=dev, dtype=torch.bfloat16)
+            gC = torch.empty(M, M, device=dev, dtype=torch.bfloat16)
+            direct["under_gemms"] = []
+            for limit in (0, 1024, 256, 64, 16):
+                ds.ds_config_set("grid_limit", limit)
+                x_med, _ = timed(lambda: ds.ds_pack(plan, host_img.data_ptr(), 0, total, stream), reps=3, warm=1)
+                loop_direct()
+                with_d = min(loop_direct() for _ in range(2))
+                direct["under_gemms"].append({
+                    "resident_workgroups": limit, "alone_GBps": round(payload / x_med / 1e6, 2),
+                    "gemm_slowdown_pct": round(100.0 * (with_d - overlap["ms_without_snapshots"]) /
+                                               overlap["ms_without_snapshots"], 2)})
+            ds.ds_config_set("grid_limit", 0)
+            del gA, gB, gC
+        experiments["gather_into_pinned_host"] = direct
+        del host_img
 
     ds.ds_engine_destroy(eng)
     torch.cuda.synchronize()
@@ -476,6 +562,7 @@ def main() -> int:
                     "scatter_ms": round(rst["pack_ms"], 3), "scatter_launches": rst["n_pack_launches"]},
         "overlap": overlap,
         "file_tier": file_tier,
+        **({"experiments": experiments} if experiments else {}),
         "hip_runtime": ds.hip_runtime_in_use(),
     }
     print(json.dumps(out), flush=True)

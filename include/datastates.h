@@ -454,6 +454,8 @@ int ds_copy_probe(void *dst_dev, const void *src_dev, uint64_t nbytes, void *str
  *                   write-through streaming buffer stores), 1 = plain loads and stores,
  *                   2 = non-temporal global loads and stores everywhere, 3 = default accesses but
  *                   work-group i takes chunk i (no XCD-contiguous order)
+ *   "grid_limit"    work-groups per launch of ds_pack / ds_unpack (each then walks several chunks);
+ *                   0 = one per chunk (default).  Engines have their own pack_grid_limit
  * Returns DS_EINVAL for an unknown key or a value out of range.
  */
 int ds_config_set(const char *key, uint64_t value);

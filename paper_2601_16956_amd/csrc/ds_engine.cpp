@@ -531,7 +531,8 @@ int ds_event_destroy(ds_event *ev) {
   int rc = DS_OK;
   if (ev->restore) {
     // whatever was submitted runs to its end; chunks never submitted are simply not restored
-    hipError_t e = hipStreamSynchronize(g->copy_stream[0]);
+    hipError_t e = hipSuccess;
+    for (int c = 0; c < g->n_copy_streams && e == hipSuccess; ++c) e = hipStreamSynchronize(g->copy_stream[c]);
     if (e == hipSuccess) e = hipStreamSynchronize(g->pack_stream);
     if (e != hipSuccess) rc = hip_fail(e);
     destroy_events(ev->group_done);

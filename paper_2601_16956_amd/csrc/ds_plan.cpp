@@ -16,6 +16,7 @@ thread_local int g_last_hip_error = 0;
 
 std::atomic<uint64_t> g_chunk_bytes{16u << 10};
 std::atomic<uint64_t> g_variant{0};
+std::atomic<uint64_t> g_grid_limit{0};
 
 inline bool is_pow2(uint64_t x) { return x && !(x & (x - 1)); }
 inline uint64_t round_up(uint64_t x, uint64_t a) { return (x + a - 1) & ~(a - 1); }
@@ -184,8 +185,13 @@ int ds_config_set(const char *key, uint64_t value) {
     return DS_OK;
   }
   if (!std::strcmp(key, "variant")) {
-    if (value > 0xFFFF) return DS_EINVAL;
+    if (value > 3) return DS_EINVAL;
     g_variant.store(value);
+    return DS_OK;
+  }
+  if (!std::strcmp(key, "grid_limit")) {
+    if (value > 0x7FFFFFFF) return DS_EINVAL;
+    g_grid_limit.store(value);
     return DS_OK;
   }
   return DS_EINVAL;
@@ -195,6 +201,7 @@ int ds_config_get(const char *key, uint64_t *value) {
   if (!key || !value) return DS_EINVAL;
   if (!std::strcmp(key, "chunk_bytes")) { *value = g_chunk_bytes.load(); return DS_OK; }
   if (!std::strcmp(key, "variant")) { *value = g_variant.load(); return DS_OK; }
+  if (!std::strcmp(key, "grid_limit")) { *value = g_grid_limit.load(); return DS_OK; }
   return DS_EINVAL;
 }
 
@@ -397,7 +404,7 @@ int ds_pack(const ds_plan *plan, void *dst_dev, uint64_t img_lo, uint64_t img_hi
   if (img_lo > img_hi || img_hi > plan->total_bytes || ((img_lo | img_hi) & 15)) return DS_ERANGE;
   if (img_lo == img_hi) return DS_OK;
   if (!dst_dev || ((uintptr_t)dst_dev & 15)) return DS_EINVAL;
-  return ds_launch_move(plan, true, (uint8_t *)dst_dev, img_lo, img_hi, 0, (hipStream_t)stream);
+  return ds_launch_move(plan, true, (uint8_t *)dst_dev, img_lo, img_hi, (uint32_t)g_grid_limit.load(), (hipStream_t)stream);
 }
 
 int ds_unpack(const ds_plan *plan, const void *src_dev, uint64_t img_lo, uint64_t img_hi, void *stream) {
@@ -405,7 +412,7 @@ int ds_unpack(const ds_plan *plan, const void *src_dev, uint64_t img_lo, uint64_
   if (img_lo > img_hi || img_hi > plan->total_bytes || ((img_lo | img_hi) & 15)) return DS_ERANGE;
   if (img_lo == img_hi) return DS_OK;
   if (!src_dev || ((uintptr_t)src_dev & 15)) return DS_EINVAL;
-  return ds_launch_move(plan, false, (uint8_t *)src_dev, img_lo, img_hi, 0, (hipStream_t)stream);
+  return ds_launch_move(plan, false, (uint8_t *)src_dev, img_lo, img_hi, (uint32_t)g_grid_limit.load(), (hipStream_t)stream);
 }
 
 }  // extern "C"

@@ -90,6 +90,39 @@ def test_chunk_sizes_and_kernel_variants(chunk_bytes, variant):
         ds.ds_config_set("variant", old_v)
 
 
+@pytest.mark.parametrize("grid_limit", [1, 7, 8, 100, 4096])
+def test_fewer_work_groups_than_chunks(grid_limit):
+    """A launch limited to a few work-groups walks the interleaved rows of general
+    and lean chunks in strides; every chunk must still be moved exactly once,
+    and a gather straight into pinned HOST memory gives the same bytes."""
+    ds, orc, gu = _mods()
+    import torch
+    w = W.fragmentation(700, max_bytes=1 << 18, seed=79)
+    print(f"[case] grid_limit={grid_limit}", flush=True)
+    want, offs, tab = gu.oracle_image(w)
+    ds.ds_config_set("grid_limit", grid_limit)
+    try:
+        assert ds.ds_config_get("grid_limit") == grid_limit
+        dw = gu.DeviceWorkload(w)
+        got = dw.pack()
+        assert gu.first_mismatch(got, want) is None, gu.first_mismatch(got, want)
+        lo, hi = 16 * 1001, dw.total - 16 * 77                 # a cut range as well
+        assert gu.first_mismatch(dw.pack(lo, hi), want[lo:hi]) is None
+        host = torch.full((dw.total,), 0xFF, dtype=torch.uint8, pin_memory=True)
+        ds.ds_pack(dw.plan, host.data_ptr(), 0, dw.total, torch.cuda.current_stream().cuda_stream)
+        torch.cuda.synchronize()
+        assert gu.first_mismatch(host.numpy(), want) is None
+        dw.arena.fill_(0xA5)
+        dw.unpack(want)
+        back = dw.arena_host()
+        w.arena[:] = 0xA5
+        orc.unpack(tab, len(w.shards), want)
+        assert gu.first_mismatch(back, w.arena) is None
+        dw.close()
+    finally:
+        ds.ds_config_set("grid_limit", 0)
+
+
 def test_image_ranges_concatenate_to_the_whole():
     """Sec. V-A4: a chunk need not be a whole object -- any partition of the
     image into ranges (multiples of 16) gives the same bytes."""

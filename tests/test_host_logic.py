@@ -136,6 +136,14 @@ def test_config_keys():
             ds.ds_config_set("chunk_bytes", bad)
     with pytest.raises(ds.DsError):
         ds.ds_config_set("no_such_key", 1)
+    with pytest.raises(ds.DsError):
+        ds.ds_config_set("variant", 4)
+    assert ds.ds_config_get("grid_limit") == 0
+    ds.ds_config_set("grid_limit", 64)
+    assert ds.ds_config_get("grid_limit") == 64
+    ds.ds_config_set("grid_limit", 0)
+    with pytest.raises(ds.DsError):
+        ds.ds_config_set("grid_limit", 1 << 31)
     ds.ds_config_set("chunk_bytes", 32 << 10)
     d = _descs([Shard("a", "u8", (1 << 20,), (1,), 0, 0)])
     ds.ds_layout_assign(d, 1, 64)
