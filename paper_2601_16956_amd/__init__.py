@@ -219,6 +219,34 @@ def make_descs(shards: Sequence, base_address: int):
     return arr
 
 
+def make_descs_from_tensors(tensors: Sequence, tensor_ids: Optional[Sequence[int]] = None):
+    """ctypes table straight from torch tensors on the GPU (any views: sliced,
+    transposed, expanded dimensions excluded): device address, dtype, shape and
+    element strides as torch reports them.  file_offset is left 0.  The caller
+    keeps the tensors alive for as long as a plan made from the table is used."""
+    import torch
+    codes = {torch.float32: DS_F32, torch.bfloat16: DS_BF16, torch.float16: DS_F16, torch.int64: DS_I64,
+             torch.uint8: DS_U8}
+    arr = (ds_shard_desc * max(len(tensors), 1))()
+    for i, t in enumerate(tensors):
+        if t.dtype not in codes:
+            raise TypeError(f"tensor {i}: dtype {t.dtype} has no ds_dtype")
+        if not t.is_cuda:
+            raise ValueError(f"tensor {i} is not in device memory")
+        if t.dim() > DS_MAX_DIMS:
+            raise ValueError(f"tensor {i} has more than {DS_MAX_DIMS} dimensions")
+        d = arr[i]
+        d.base = t.data_ptr()
+        d.dtype = codes[t.dtype]
+        d.ndim = t.dim()
+        for j, (e, st) in enumerate(zip(t.shape, t.stride())):
+            d.shape[j] = e
+            d.strides[j] = st
+        d.tensor_id = tensor_ids[i] if tensor_ids is not None else i
+        d.file_offset = 0
+    return arr
+
+
 # ---- the entry points, same names as the C ABI -------------------------------
 
 def ds_itemsize(dtype: int) -> int:
