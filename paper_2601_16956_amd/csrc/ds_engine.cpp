@@ -122,6 +122,9 @@ int issue_snapshot(ds_engine *g, ds_event *ev) {
     at = hi;
   }
   const size_t G = groups.size();
+  // A snapshot of only a few chunks keeps to one copy stream: there is no gap between copies for the
+  // second stream to hide, so the events that would tie it in are saved.
+  const int ncs = ev->chunks.size() < 4 ? 1 : g->n_copy_streams;
 
   auto mark_captured = [&]() -> int {
     W_TRY(hipEventRecord(ev->captured, g->pack_stream));
@@ -156,7 +159,7 @@ int issue_snapshot(ds_engine *g, ds_event *ev) {
   auto issue_copies = [&](size_t gi) -> int {
     const Group &gr = groups[gi];
     uint8_t *slot = g->stage + (uint64_t)gr.slot * g->stage_slot_bytes;
-    for (int c = 0; c < g->n_copy_streams; ++c) W_TRY(hipStreamWaitEvent(g->copy_stream[c], ev->pack_end[gi], 0));
+    for (int c = 0; c < ncs; ++c) W_TRY(hipStreamWaitEvent(g->copy_stream[c], ev->pack_end[gi], 0));
     if (gi == 0) W_TRY(hipEventRecord(ev->copy_begin, g->copy_stream[0]));
     for (uint64_t lo = gr.lo; lo < gr.hi; lo += g->chunk_bytes, ++k) {
       const uint64_t len = lo + g->chunk_bytes < gr.hi ? g->chunk_bytes : gr.hi - lo;
@@ -171,7 +174,7 @@ int issue_snapshot(ds_engine *g, ds_event *ev) {
         }
         g->ring_next = (r + 1) % g->ring_slots;
       }
-      const int c = (int)(g->copies_issued++ % (uint64_t)g->n_copy_streams);
+      const int c = (int)(g->copies_issued++ % (uint64_t)ncs);
       hipStream_t cs = g->copy_stream[c];
       // the slot's previous copy may have run on the other copy stream
       if (g->n_copy_streams > 1) W_TRY(hipStreamWaitEvent(cs, g->ring_done[r], 0));
@@ -184,7 +187,8 @@ int issue_snapshot(ds_engine *g, ds_event *ev) {
       }
       g->cv.notify_all();
     }
-    for (int c = 0; c < g->n_copy_streams; ++c) W_TRY(hipEventRecord(g->stage_free[c][gr.slot], g->copy_stream[c]));
+    // (a stream this snapshot did not use keeps the event of its own last copies out of the slot)
+    for (int c = 0; c < ncs; ++c) W_TRY(hipEventRecord(g->stage_free[c][gr.slot], g->copy_stream[c]));
     g->stage_used[gr.slot] = true;
     return DS_OK;
   };
@@ -203,7 +207,7 @@ int issue_snapshot(ds_engine *g, ds_event *ev) {
     if (rc != DS_OK) return rc;
   }
   W_TRY(hipStreamWaitEvent(g->copy_stream[0], ev->captured, 0));
-  if (g->n_copy_streams > 1 && !ev->chunks.empty()) {
+  if (ncs > 1) {
     hipEvent_t tail;
     W_TRY(hipEventCreate(&tail));
     ev->pack_begin.push_back(tail);  // kept only so that it is destroyed with the event

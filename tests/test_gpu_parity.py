@@ -334,3 +334,51 @@ def test_torch_views_pack_to_what_contiguous_holds():
     for t, keep in zip(tensors, saved):
         assert torch.equal(t.contiguous().reshape(-1).view(torch.uint8), keep.contiguous().reshape(-1).view(torch.uint8))
     ds.ds_plan_destroy(plan)
+
+
+def test_pack_and_unpack_inside_a_hip_graph():
+    """ds_pack / ds_unpack only enqueue a kernel, so a caller may capture them in a
+    HIP graph; every replay (with eager work and synchronisations in between, and
+    the tensors changed between replays) must give the oracle's bytes."""
+    ds, orc, gu = _mods()
+    import torch
+    w = W.fragmentation(900, max_bytes=1 << 17, seed=83)
+    print("[case] graph capture", flush=True)
+    dw = gu.DeviceWorkload(w)
+    n = len(w.shards)
+    tab = orc.table(w.shards, w.arena.ctypes.data)
+    total = orc.layout(tab, n, w.align)
+    image = torch.empty(total, dtype=torch.uint8, device="cuda")
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    try:
+        ds.ds_pack(dw.plan, image.data_ptr(), 0, total, torch.cuda.current_stream().cuda_stream)   # warm, eager
+        torch.cuda.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            ds.ds_pack(dw.plan, image.data_ptr(), 0, total, side.cuda_stream)
+        for rep in range(3):
+            w.arena[:] = (w.arena.astype(np.uint16) * 7 + rep + 1).astype(np.uint8)    # new tensor contents
+            dw.arena.copy_(torch.from_numpy(w.arena))
+            image.fill_(0xFF)
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            want = orc.pack(tab, n, total)
+            assert gu.first_mismatch(image.cpu().numpy(), want) is None, rep
+        # the scatter, captured: image -> wiped tensors
+        g2 = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g2, stream=side):
+            ds.ds_unpack(dw.plan, image.data_ptr(), 0, total, side.cuda_stream)
+        for rep in range(2):
+            dw.arena.fill_(0xA5)
+            torch.cuda.synchronize()
+            g2.replay()
+            torch.cuda.synchronize()
+            keep = w.arena.copy()
+            w.arena[:] = 0xA5
+            orc.unpack(tab, n, want)
+            assert gu.first_mismatch(dw.arena_host(), w.arena) is None, rep
+            w.arena[:] = keep
+    finally:
+        del graph
+        dw.close()
