@@ -130,8 +130,17 @@ def main() -> int:
         torch.cuda.synchronize()
         if i >= 2:
             link_best = max(link_best, GiB / (a.elapsed_time(b) * 1e-3) / 1e9)
+    h2d_best = 0.0
+    for i in range(8):
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        probe_dev.copy_(probe_host, non_blocking=True)
+        b.record()
+        torch.cuda.synchronize()
+        if i >= 2:
+            h2d_best = max(h2d_best, GiB / (a.elapsed_time(b) * 1e-3) / 1e9)
     del probe_dev, probe_host
-    log(f"[bench] measured D2H link peak {link_best:.1f} GB/s")
+    log(f"[bench] measured link peak: D2H {link_best:.1f} GB/s, H2D {h2d_best:.1f} GB/s")
 
     # ---- the timed region: K snapshots, back to back, each gated ------------------------------
     eng = ds.ds_engine_create(args.ring_bytes, args.chunk_bytes, args.stage_slot_bytes, args.stage_slots, 0,
@@ -559,6 +568,8 @@ def main() -> int:
             "pack_vs_copy_probe": round((algo_bytes / pack_med) / (2 * nprobe / probe_med), 4),
         },
         "restore": {"GBps_null_producer": round(payload / restore_s / 1e9, 2), "ms": round(restore_s * 1e3, 3),
+                    "h2d_link_peak_measured_GBps": round(h2d_best, 2),
+                    "frac_of_h2d_peak": round(payload / restore_s / 1e9 / h2d_best, 4),
                     "scatter_ms": round(rst["pack_ms"], 3), "scatter_launches": rst["n_pack_launches"]},
         "overlap": overlap,
         "file_tier": file_tier,
