@@ -286,3 +286,25 @@ def test_ckpt_argument_errors(tmp_path):
     assert e.value.code == ds.DS_ERANGE
     ds.ds_ckpt_finish(ck)
     ds.ds_plan_destroy(plan)
+
+
+def test_io_errors_are_reported_with_errno(tmp_path):
+    """A device that takes no bytes (/dev/full: every write fails with ENOSPC):
+    the failing call says DS_EIO with the errno, and so does ds_ckpt_finish for
+    an append that failed earlier."""
+    if not os.path.exists("/dev/full"):
+        pytest.skip("no /dev/full here")
+    w = W.tiny_gpt()
+    plan, d, n, total, image = _host_plan(w)
+    img = np.ascontiguousarray(image)
+    ck = ds.ds_ckpt_create("/dev/full", plan, 0)
+    with pytest.raises(ds.DsError) as e:
+        ds.ds_ckpt_write_region(ck, 0, img.ctypes.data, 4096)
+    assert e.value.code == ds.DS_EIO and ds.ds_last_errno() == 28
+    with pytest.raises(ds.DsError) as e:
+        ds.ds_ckpt_append(ck, 1, b"abc")
+    assert e.value.code == ds.DS_EIO
+    with pytest.raises(ds.DsError) as e:
+        ds.ds_ckpt_finish(ck)
+    assert e.value.code == ds.DS_EIO and ds.ds_last_errno() == 28
+    ds.ds_plan_destroy(plan)

@@ -401,3 +401,41 @@ def test_checkpoint_file_from_a_snapshot_with_concurrent_object_log(tmp_path):
     finally:
         ds.ds_engine_destroy(eng)
         dw.close()
+
+
+def test_flush_io_error_does_not_stall_the_snapshot():
+    """Writers that fail (/dev/full: ENOSPC) still hand every ring slot back, so the
+    snapshot runs to its end; the flush reports DS_EIO with the errno."""
+    import os
+    if not os.path.exists("/dev/full"):
+        pytest.skip("no /dev/full here")
+    ds, orc, gu, torch = _mods()
+    w = W.fragmentation(1200, max_bytes=1 << 16, seed=95)
+    print("[case] flush error path", flush=True)
+    dw = gu.DeviceWorkload(w)
+    eng = ds.ds_engine_create(4 * MiB, 1 * MiB, 4 * MiB, 2, 0, 0, 2)      # ring smaller than the image
+    s = torch.cuda.current_stream().cuda_stream
+    try:
+        ev = ds.ds_snapshot_async(eng, dw.plan, s)
+        fl = ds.ds_flush_start(ev, "/dev/full", 2, 0)
+        ds.ds_event_wait_on_stream(ev, s)
+        with pytest.raises(ds.DsError) as e:
+            ds.ds_flush_wait(fl)
+        assert e.value.code == ds.DS_EIO and ds.ds_last_errno() == 28
+        ds.ds_event_wait(ev)                      # the snapshot itself completed
+        ds.ds_event_destroy(ev)
+        # and the engine is usable afterwards
+        ev = ds.ds_snapshot_async(eng, dw.plan, s)
+        n = 0
+        while True:
+            ch = ds.ds_snapshot_next_chunk(ev)
+            if ch is None:
+                break
+            n += ch[2]
+            ds.ds_snapshot_release_chunk(ev, ch[0])
+        assert n == dw.total
+        ds.ds_event_wait(ev)
+        ds.ds_event_destroy(ev)
+    finally:
+        ds.ds_engine_destroy(eng)
+        dw.close()
