@@ -62,7 +62,7 @@ def main() -> int:
     ap.add_argument("--no-file", action="store_true", help="skip the file-tier leg")
     ap.add_argument("--file-dir", default="/tmp", help="where the file-tier leg writes its image")
     ap.add_argument("--file-threads", type=int, default=8)
-    ap.add_argument("--gemm-iters", type=int, default=12, help="iterations of the overlap leg")
+    ap.add_argument("--gemm-iters", type=int, default=20, help="iterations of the overlap leg")
     ap.add_argument("--experiments", action="store_true",
                     help="also run the capture variants that are measured, not shipped (direct gather into pinned "
                          "host memory; grid-limited gathers under the GEMM stream)")
@@ -85,6 +85,7 @@ def main() -> int:
     assert torch.cuda.is_available(), "needs the MI355X"
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+    props = torch.cuda.get_device_properties(dev)
     cores = len(os.sched_getaffinity(0))
     cores = min(cores, int(os.environ.get("OMP_NUM_THREADS", cores)))
 
@@ -227,7 +228,7 @@ def main() -> int:
     # ---- gather and scatter alone, whole image, device to device ------------------------------
     image_dev = torch.empty(max(total, 16), dtype=torch.uint8, device=dev)
 
-    def timed(fn, reps=10, warm=2):
+    def timed(fn, reps=20, warm=3):
         for _ in range(warm):
             fn()
         torch.cuda.synchronize()
@@ -574,6 +575,8 @@ def main() -> int:
         "overlap": overlap,
         "file_tier": file_tier,
         **({"experiments": experiments} if experiments else {}),
+        "device": {"name": props.name, "compute_units": props.multi_processor_count,
+                   "hbm_bytes": props.total_memory},
         "hip_runtime": ds.hip_runtime_in_use(),
     }
     print(json.dumps(out), flush=True)
