@@ -123,6 +123,33 @@ def test_fewer_work_groups_than_chunks(grid_limit):
         ds.ds_config_set("grid_limit", 0)
 
 
+@pytest.mark.parametrize("variant", [0, 1])
+def test_repeated_launches_give_the_same_bytes(variant):
+    """Thirty gathers and ten scatters in a row, each compared with the oracle: a
+    result that depends on timing (a missing wait, a hazard) shows up as a
+    mismatch in some of them."""
+    ds, orc, gu = _mods()
+    w = W.fragmentation(1500, max_bytes=1 << 19, seed=77)
+    print(f"[case] repeated launches variant={variant}", flush=True)
+    want, offs, tab = gu.oracle_image(w)
+    ds.ds_config_set("variant", variant)
+    try:
+        dw = gu.DeviceWorkload(w)
+        bad = [rep for rep in range(30) if gu.first_mismatch(dw.pack(), want) is not None]
+        assert not bad, bad
+        keep = w.arena.copy()
+        w.arena[:] = 0xA5
+        orc.unpack(tab, len(w.shards), want)
+        for rep in range(10):
+            dw.arena.fill_(0xA5)
+            dw.unpack(want)
+            assert gu.first_mismatch(dw.arena_host(), w.arena) is None, rep
+        w.arena[:] = keep
+        dw.close()
+    finally:
+        ds.ds_config_set("variant", 0)
+
+
 def test_image_ranges_concatenate_to_the_whole():
     """Sec. V-A4: a chunk need not be a whole object -- any partition of the
     image into ranges (multiples of 16) gives the same bytes."""
