@@ -296,10 +296,11 @@ int ds_restore_submit(ds_event *ev, const void *host_ptr);
 /* ---- host <-> file tier (Sec. V-A4: a chunk goes on to the next tier as soon
  *      as it is resident; Sec. V-C: persistence on background threads) -------- */
 
-#define DS_FILE_DIRECT 1u /* O_DIRECT for every transfer whose address, offset and length are multiples
-                             of 4 KiB (ring slots are); anything else, and everything once the kernel
-                             refuses direct I/O on the ring's pages (EFAULT/EINVAL), goes through a
-                             buffered descriptor */
+#define DS_FILE_DIRECT 1u /* O_DIRECT for every transfer whose offset and length are multiples of 4 KiB
+                             (ring slots are): straight from / into the ring where the kernel can pin the
+                             ring's pages, else through an aligned buffer of ordinary memory (one extra
+                             memory-speed copy, no page cache); anything else, and everything on a file
+                             system without direct I/O, goes through a buffered descriptor */
 #define DS_FILE_SYNC 2u   /* fsync before ds_flush_wait returns                                        */
 
 /*

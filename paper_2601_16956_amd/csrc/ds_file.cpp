@@ -15,6 +15,8 @@
 
 #include <atomic>
 #include <cerrno>
+#include <cstdlib>
+#include <cstring>
 #include <chrono>
 #include <condition_variable>
 #include <deque>
@@ -88,7 +90,8 @@ struct ds_flush {
   std::atomic<int> status{DS_OK};
   std::atomic<int> err_no{0};
   std::atomic<uint64_t> bytes{0};
-  std::atomic<bool> direct_usable{true};
+  std::atomic<bool> direct_usable{true};  // direct I/O straight from the ring's pages
+  std::atomic<bool> bounce_usable{true};  // direct I/O from a copy in ordinary memory
   double t0 = 0, t1 = 0;
 };
 
@@ -99,7 +102,29 @@ void flush_fail(ds_flush *f, int status, int e) {
   if (f->status.compare_exchange_strong(expect, status)) f->err_no.store(e);
 }
 
+// A 4 KiB-aligned buffer of ordinary memory, grown on demand: direct I/O cannot take the pinned ring's pages
+// (the kernel refuses to pin them a second time), so a slot is copied here first -- one memory-speed copy
+// instead of a trip through the page cache.
+struct Bounce {
+  uint8_t *p = nullptr;
+  uint64_t cap = 0;
+  ~Bounce() { free(p); }
+  uint8_t *fit(uint64_t n) {
+    if (n > cap) {
+      free(p);
+      p = nullptr;
+      cap = 0;
+      void *q = nullptr;
+      if (posix_memalign(&q, 4096, (size_t)n) != 0) return nullptr;
+      p = (uint8_t *)q;
+      cap = n;
+    }
+    return p;
+  }
+};
+
 void writer_main(ds_flush *f) {
+  Bounce bounce;
   for (;;) {
     IoJob j;
     {
@@ -110,14 +135,27 @@ void writer_main(ds_flush *f) {
       f->queue.pop_front();
     }
     if (f->status.load() == DS_OK) {
-      const bool direct = f->direct_usable.load() && f->fd_direct >= 0 && direct_ok(j.ptr, j.off, j.len);
-      int e = write_all(direct ? f->fd_direct : f->fd_buffered, (const uint8_t *)j.ptr, j.len, j.off);
-      if (e && direct && (e == EFAULT || e == EINVAL)) {
-        // direct I/O has to pin the pages of the buffer itself, which the kernel refuses for some mappings
-        // (the HIP pinned ring among them on this system): go on through the page cache
-        f->direct_usable.store(false);
-        e = write_all(f->fd_buffered, (const uint8_t *)j.ptr, j.len, j.off);
+      const bool direct = f->fd_direct >= 0 && direct_ok(j.ptr, j.off, j.len);
+      int e = -1;  // -1: not written yet, try the next way
+      if (direct && f->direct_usable.load()) {           // straight from the ring, where the kernel allows it
+        e = write_all(f->fd_direct, (const uint8_t *)j.ptr, j.len, j.off);
+        if (e == EFAULT || e == EINVAL) {
+          f->direct_usable.store(false);
+          e = -1;
+        }
       }
+      if (e == -1 && direct && f->bounce_usable.load()) {  // through an aligned buffer of ordinary memory
+        uint8_t *b = bounce.fit(j.len);
+        if (b) {
+          std::memcpy(b, j.ptr, j.len);
+          e = write_all(f->fd_direct, b, j.len, j.off);
+          if (e == EINVAL) {                             // the file system has no direct I/O after all
+            f->bounce_usable.store(false);
+            e = -1;
+          }
+        }
+      }
+      if (e == -1) e = write_all(f->fd_buffered, (const uint8_t *)j.ptr, j.len, j.off);
       if (e) flush_fail(f, DS_EIO, e);
       else f->bytes.fetch_add(j.len);
     }
@@ -274,12 +312,13 @@ int ds_restore_from_file(ds_engine *engine, const ds_plan *plan, const char *pat
     std::vector<int> done;  // per window position: 0 pending, 1 read, <0 = -errno
     bool stop = false;
   } sh;
-  std::atomic<bool> direct_usable{true};
+  std::atomic<bool> direct_usable{true}, bounce_usable{true};
   const uint32_t window = threads;
   sh.done.assign(window, 0);
   std::vector<IoJob> win(window);
   std::vector<std::thread> readers;
   auto reader = [&]() {
+    Bounce bounce;
     for (;;) {
       IoJob j;
       {
@@ -289,12 +328,29 @@ int ds_restore_from_file(ds_engine *engine, const ds_plan *plan, const char *pat
         j = sh.todo.front();
         sh.todo.pop_front();
       }
-      const bool direct = direct_usable.load() && fd_direct >= 0 && direct_ok(j.ptr, j.off, j.len);
-      int e = read_all(direct ? fd_direct : fd_buffered, (uint8_t *)j.ptr, j.len, j.off);
-      if (e && direct && (e == EFAULT || e == EINVAL)) {  // see writer_main
-        direct_usable.store(false);
-        e = read_all(fd_buffered, (uint8_t *)j.ptr, j.len, j.off);
+      // the same three ways as in writer_main: direct into the ring, direct into an aligned buffer of
+      // ordinary memory and a copy, buffered
+      const bool direct = fd_direct >= 0 && direct_ok(j.ptr, j.off, j.len);
+      int e = -1;
+      if (direct && direct_usable.load()) {
+        e = read_all(fd_direct, (uint8_t *)j.ptr, j.len, j.off);
+        if (e == EFAULT || e == EINVAL) {
+          direct_usable.store(false);
+          e = -1;
+        }
       }
+      if (e == -1 && direct && bounce_usable.load()) {
+        uint8_t *b = bounce.fit(j.len);
+        if (b) {
+          e = read_all(fd_direct, b, j.len, j.off);
+          if (e == 0) std::memcpy(j.ptr, b, j.len);
+          if (e == EINVAL) {
+            bounce_usable.store(false);
+            e = -1;
+          }
+        }
+      }
+      if (e == -1) e = read_all(fd_buffered, (uint8_t *)j.ptr, j.len, j.off);
       {
         std::lock_guard<std::mutex> lk(sh.mu);
         sh.done[j.slot] = e ? -e : 1;
