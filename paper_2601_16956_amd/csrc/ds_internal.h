@@ -26,13 +26,13 @@ static_assert(sizeof(DsTile) == 128, "DsTile is one 128-byte line");
 // What the kernel's lean path needs to move one whole chunk, in one 32-byte load.
 // Chunks that are not "simple" (a tile boundary, the end of a payload or
 // padding inside the chunk, more than one outer dimension, rows shorter than
-// 16 bytes) are of kind DS_CHUNK_GENERAL and take the general path, which
-// finds its tiles through first_tile[].
+// 16 bytes) are of kind DS_CHUNK_GENERAL and take the general path; their
+// record names the tiles they hold (tile, col0).
 enum : uint32_t { DS_CHUNK_CONTIG = 0, DS_CHUNK_ROWS = 1, DS_CHUNK_GENERAL = 2 };
 struct DsChunkRec {
   uint64_t addr;   // CONTIG: tensor address of the chunk's first byte; ROWS: address of the run that holds it
   uint64_t pitch;  // ROWS: distance between runs in bytes
-  uint32_t col0;   // ROWS: position of the chunk's first byte inside its run
+  uint32_t col0;   // ROWS: position of the chunk's first byte inside its run.  GENERAL: number of tiles after the first
   uint32_t run;    // ROWS: run length in bytes (>= 16, multiple of the itemsize)
   uint32_t kind;   // low byte: DS_CHUNK_*; bits 8..: log2(itemsize) (ROWS)
   uint32_t tile;   // GENERAL: first tile of the chunk.  ROWS: (step / run) << 16 | (step % run), step = bytes
@@ -66,7 +66,7 @@ struct ds_plan {
   std::vector<uint64_t> tile_off;          // n_tiles + 1 entries, last = total_bytes
   std::vector<uint32_t> first_tile;        // n_chunks + 1 entries, last = n_tiles
   std::vector<DsChunkRec> recs;            // one per chunk
-  std::vector<uint32_t> general_ids;       // chunks of kind DS_CHUNK_GENERAL, ascending
+  uint64_t n_general = 0;                  // chunks of kind DS_CHUNK_GENERAL
   // device copies (one allocation)
   int device = -1;
   void *dev_blob = nullptr;
@@ -74,7 +74,6 @@ struct ds_plan {
   const uint64_t *d_tile_off = nullptr;
   const uint32_t *d_first_tile = nullptr;
   const DsChunkRec *d_recs = nullptr;
-  const uint32_t *d_general_ids = nullptr;
   uint64_t n_chunks() const { return first_tile.empty() ? 0 : first_tile.size() - 1; }
 };
 

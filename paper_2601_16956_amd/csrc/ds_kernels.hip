@@ -23,7 +23,7 @@
 //   of at least 16 bytes each).
 //
 // general path: the remaining chunks (tile boundaries, payload tails, padding,
-//   N-D views), taken from the plan's list of them:
+//   N-D views); their record names the tiles they hold:
 //   - A chunk that holds a few tiles walks them one after the other with the
 //     whole work-group ("direct" path).
 //   - A chunk that holds many small tiles takes them 64 at a time: every lane
@@ -55,14 +55,12 @@ struct MoveArgs {
   const DsTile *tiles;
   const uint64_t *tile_off;
   const uint32_t *first_tile;
-  const uint32_t *ids;  // chunk numbers this launch works on (after the `extra` ones)
   uint8_t *img;         // points at image byte img_lo
   uint64_t img_lo, img_hi;
   uint64_t total;       // image length
   uint32_t chunk_log2;
-  uint32_t n_extra;     // 0..2 chunks cut by img_lo / img_hi
+  uint32_t n_extra;     // 0..2 chunks cut by img_lo / img_hi: they take the general path whatever their kind
   uint32_t extra[2];
-  uint32_t n_chunks;    // n_extra + number of ids
 };
 
 struct LeanArgs {
@@ -296,24 +294,21 @@ __device__ __forceinline__ uint32_t wave_inclusive_scan(uint32_t x, uint32_t lan
   return x;
 }
 
-// One general chunk (number ci of the launch's list), whole work-group.
+// One general chunk, whole work-group: chunk number c, which holds (parts of) tiles t0 .. t1.
 // s_incl: inclusive scan of unit counts of the 64 tiles of a batch; s_begin: where each tile's clipped
 // range starts, relative to the chunk (both kWave words of LDS).
 template <bool PACK, int NT, int UNROLL, bool NTL, bool NTS>
-__device__ __forceinline__ void general_chunk(const MoveArgs &a, uint32_t ci, uint32_t *s_incl, uint32_t *s_begin) {
+__device__ __forceinline__ void general_chunk(const MoveArgs &a, uint64_t c, uint32_t t0, uint32_t t1, uint32_t *s_incl,
+                                              uint32_t *s_begin) {
   const uint32_t tid = threadIdx.x;
   const uint32_t lane = tid & (kWave - 1);
   {
-    const uint64_t c = ci < a.n_extra ? a.extra[ci] : a.ids[ci - a.n_extra];
     const uint64_t c_begin = c << a.chunk_log2;
     uint64_t c_end = (c + 1) << a.chunk_log2;
     if (c_end > a.total) c_end = a.total;
     const uint64_t cb = c_begin > a.img_lo ? c_begin : a.img_lo;
     const uint64_t ce = c_end < a.img_hi ? c_end : a.img_hi;
     if (cb >= ce) return;
-    const uint32_t t0 = a.first_tile[c];
-    uint32_t t1 = a.first_tile[c + 1];
-    if (a.tile_off[t1] >= c_end) --t1;  // that tile starts where this chunk ends
 
     if (t1 - t0 < kDirectMaxTiles) {
       for (uint32_t t = t0; t <= t1; ++t) {
@@ -418,7 +413,8 @@ constexpr int kStorePolicySc0Sc1Nt = 1 | 2 | 16;  // sc0 | nt | sc1 in the intri
 __device__ __forceinline__ uint32_t lean_items(const LeanArgs &a) { return a.xcd_span ? a.xcd_span * 8u : a.n_chunks; }
 
 template <bool PACK, int NT, int UNROLL, bool NTL, bool NTS, bool BUFST>
-__device__ __forceinline__ void lean_chunk(const LeanArgs &a, uint32_t ci) {
+__device__ __forceinline__ void lean_chunk(const LeanArgs &a, const MoveArgs &ma, uint32_t ci, uint32_t *s_incl,
+                                           uint32_t *s_begin) {
   const uint32_t tid = threadIdx.x;
   {
     // Work-groups are dealt to the 8 XCDs round-robin (work-group i runs on XCD i mod 8).  Chunk
@@ -433,7 +429,11 @@ __device__ __forceinline__ void lean_chunk(const LeanArgs &a, uint32_t ci) {
     const uint32_t c = a.c_lo + cm;
     const DsChunkRec r = a.recs[c];
     const uint32_t kind = r.kind & 0xFF;  // bits 8.. hold log2(itemsize)
-    if (kind == DS_CHUNK_GENERAL) return;
+    if (kind == DS_CHUNK_GENERAL) {
+      // its record names the tiles it holds: one load away from them, and in place among its neighbours
+      general_chunk<PACK, 256, 4, NTL, NTS>(ma, c, r.tile, r.tile + r.col0, s_incl, s_begin);
+      return;
+    }
     uint8_t *imgp = a.img + (((uint64_t)c << a.chunk_log2) - a.img_lo);
     __amdgpu_buffer_rsrc_t image_rsrc;
     if (PACK && BUFST) image_rsrc = __builtin_amdgcn_make_buffer_rsrc(imgp, 0, NT * UNROLL * 16, 0x00020000);
@@ -511,53 +511,52 @@ __device__ __forceinline__ void lean_chunk(const LeanArgs &a, uint32_t ci) {
   }
 }
 
-// Both paths in one launch.  Work items are taken in rows of 8 (one per XCD, so that the lean items keep
-// their XCDs); every period-th row, gen_rows of them in all, holds 8 general chunks, the others 8 lean
-// items.  The general chunks are latency-bound (chains of table loads): spread evenly, from the first row
-// on, their bubbles are filled by the lean work-groups beside them and none is left for the tail.
-// Measured against two launches (lean kernel, then general kernel, or both side by side on two streams):
-// +2.7 % on the gather of the 7B rank, whose few general chunks cost a launch gap of their own, and
-// 0 to +1 % elsewhere.
+// Both paths in one launch: work item i takes whole chunk number i of the range (in the XCD-contiguous
+// order) down the path its record names, so a general chunk is moved in place, among its neighbours in the
+// image, one record load away from its tiles; the at most two chunks cut by the ends of the range follow
+// as work items of their own.  History, measured on the gather: lean kernel then general kernel in two
+// launches cost the 7B rank a launch gap plus the general kernel's 9 us (5.78 TB/s in the timed region
+// against 6.17 now); the general kernel on a side stream beside the lean one gave the fragmentation set
+// 5.30 -> 5.54 TB/s, one launch 5.85 TB/s.
 //
-// At most 5 waves per SIMD (the attribute makes the compiler pad the register allocation): measured, the
-// lean scatter runs 5 % faster with 4-5 resident waves than with the 8 its own registers would allow, and
-// the gather is at its best there too -- fewer work-groups in flight keep the addresses in a more compact
-// window of HBM; with 3 or fewer both lose ~9 %.
+// At most 4 waves per SIMD (the attribute makes the compiler pad the register allocation): fewer
+// work-groups in flight keep the addresses in a more compact window of HBM.  Measured with the cap at 4
+// against 5: gather +0.8 % on the 7B and 70B ranks, -0.8 % on the fragmentation set, scatter +0.5 to +1 %
+// everywhere; the scatter, whose own registers would allow 8, loses 5 % there; with 3 or fewer both
+// directions lose ~9 %.
 //
 // A lean chunk is exactly 256 threads x UNROLL x 16 bytes; the general path always works in passes of
 // 256 x 4 units.
 template <bool PACK, int UNROLL, bool NTL, bool NTS, bool BUFST>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 5))) void ds_move_kernel(
-    LeanArgs la, MoveArgs ma, uint32_t gen_rows, uint32_t period) {
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 4))) void ds_move_kernel(LeanArgs la,
+                                                                                                 MoveArgs ma) {
   __shared__ uint32_t s_incl[kWave];
   __shared__ uint32_t s_begin[kWave];
   const uint32_t n_lean = lean_items(la);
-  const uint32_t n_iter = (gen_rows + (n_lean + 7u) / 8u) * 8u;
+  const uint32_t n_iter = n_lean + ma.n_extra;
   for (uint32_t wi = blockIdx.x; wi < n_iter; wi += gridDim.x) {
-    const uint32_t row = wi >> 3, q = row / period;
-    uint32_t before = (row + period - 1) / period;  // general rows before this one
-    if (before > gen_rows) before = gen_rows;
-    if (q * period == row && q < gen_rows) {
-      const uint32_t gi = q * 8u + (wi & 7u);
-      if (gi < ma.n_chunks) general_chunk<PACK, 256, 4, NTL, NTS>(ma, gi, s_incl, s_begin);
+    if (wi < n_lean) {
+      lean_chunk<PACK, 256, UNROLL, NTL, NTS, BUFST>(la, ma, wi, s_incl, s_begin);
     } else {
-      const uint32_t ci = (row - before) * 8u + (wi & 7u);
-      if (ci < n_lean) lean_chunk<PACK, 256, UNROLL, NTL, NTS, BUFST>(la, ci);
+      // a chunk cut by the range: the general path clips to the range, whatever the chunk's kind
+      const uint64_t c = ma.extra[wi - n_lean];
+      uint64_t c_end = (c + 1) << ma.chunk_log2;
+      if (c_end > ma.total) c_end = ma.total;
+      const uint32_t t0 = ma.first_tile[c];
+      uint32_t t1 = ma.first_tile[c + 1];
+      if (ma.tile_off[t1] >= c_end) --t1;  // that tile starts where this chunk ends
+      general_chunk<PACK, 256, 4, NTL, NTS>(ma, c, t0, t1, s_incl, s_begin);
     }
   }
 }
 
 template <bool PACK, bool NTL, bool NTS, bool BUFST>
 int launch_move(uint32_t chunk_log2, const LeanArgs &la, const MoveArgs &ma, uint32_t grid_limit, hipStream_t stream) {
-  const uint32_t gen_rows = (ma.n_chunks + 7u) / 8u;
-  const uint32_t lean_rows = ((la.xcd_span ? la.xcd_span * 8 : la.n_chunks) + 7u) / 8u;
-  const uint32_t rows = gen_rows + lean_rows;
-  if (rows == 0) return DS_OK;
-  const uint32_t period = gen_rows ? rows / gen_rows : 1u;  // >= 1
-  uint32_t grid = rows * 8u;
+  uint32_t grid = (la.xcd_span ? la.xcd_span * 8 : la.n_chunks) + ma.n_extra;
+  if (grid == 0) return DS_OK;
   if (grid_limit && grid > grid_limit) grid = grid_limit;
 #define DS_MOVE(UN) \
-  hipLaunchKernelGGL((ds_move_kernel<PACK, UN, NTL, NTS, BUFST>), dim3(grid), dim3(256), 0, stream, la, ma, gen_rows, period)
+  hipLaunchKernelGGL((ds_move_kernel<PACK, UN, NTL, NTS, BUFST>), dim3(grid), dim3(256), 0, stream, la, ma)
   switch (chunk_log2) {
     case 13: DS_MOVE(2); break;
     case 14: DS_MOVE(4); break;
@@ -613,10 +612,10 @@ int ds_launch_move(const ds_plan *plan, bool pack, uint8_t *img, uint64_t img_lo
   const uint64_t C = (uint64_t)1 << lg;
   const uint64_t n_total = plan->n_chunks();
   if (img_hi > plan->total_bytes || img_lo >= img_hi) return DS_ERANGE;
-  // whole chunks inside the range go down the lean path (which skips the general ones) ...
+  // whole chunks inside the range: one work item each, lean or general by their record ...
   uint64_t w_lo = (img_lo + C - 1) >> lg;
   uint64_t w_hi = img_hi >> lg;
-  if (img_hi == plan->total_bytes) w_hi = n_total;  // the last chunk may be short; it is 'general' then
+  if (img_hi == plan->total_bytes) w_hi = n_total;  // the last chunk may be short; its record says 'general' then
   LeanArgs la;
   la.recs = plan->d_recs;
   la.img = img;
@@ -625,7 +624,7 @@ int ds_launch_move(const ds_plan *plan, bool pack, uint8_t *img, uint64_t img_lo
   la.c_lo = (uint32_t)w_lo;
   la.n_chunks = w_hi > w_lo ? (uint32_t)(w_hi - w_lo) : 0;
   la.xcd_span = ds_cfg_variant() == 3 ? 0 : (la.n_chunks + 7) / 8;
-  // ... the general ones among them, and the chunks cut by the range, down the general path
+  // ... and the one or two chunks cut by the ends of the range, clipped by the general path
   MoveArgs ma;
   ma.tiles = plan->d_tiles;
   ma.tile_off = plan->d_tile_off;
@@ -642,16 +641,9 @@ int ds_launch_move(const ds_plan *plan, bool pack, uint8_t *img, uint64_t img_lo
     // no whole chunk: the range touches one or two chunks, both cut
     ma.extra[ma.n_extra++] = (uint32_t)c_first;
     if (c_last != c_first) ma.extra[ma.n_extra++] = (uint32_t)c_last;
-    ma.ids = plan->d_general_ids;
-    ma.n_chunks = ma.n_extra;
   } else {
     if (c_first < w_lo) ma.extra[ma.n_extra++] = (uint32_t)c_first;
     if (c_last >= w_hi) ma.extra[ma.n_extra++] = (uint32_t)c_last;
-    const auto &g = plan->general_ids;
-    const size_t lo = std::lower_bound(g.begin(), g.end(), (uint32_t)w_lo) - g.begin();
-    const size_t hi = std::lower_bound(g.begin(), g.end(), (uint32_t)w_hi) - g.begin();
-    ma.ids = plan->d_general_ids + lo;
-    ma.n_chunks = ma.n_extra + (uint32_t)(hi - lo);
   }
   const uint64_t variant = ds_cfg_variant();
   if (variant == 1) {  // plain loads and stores

@@ -113,8 +113,7 @@ int upload(ds_plan *p) {
   const size_t b_off = round_up(p->tile_off.size() * sizeof(uint64_t), 128);
   const size_t b_first = round_up(p->first_tile.size() * sizeof(uint32_t), 128);
   const size_t b_recs = round_up(p->recs.size() * sizeof(DsChunkRec), 128);
-  const size_t b_gen = round_up(p->general_ids.size() * sizeof(uint32_t), 128);
-  const size_t total = std::max<size_t>(b_tiles + b_off + b_first + b_recs + b_gen, 128);
+  const size_t total = std::max<size_t>(b_tiles + b_off + b_first + b_recs, 128);
   DS_HIP_TRY(hipMalloc(&p->dev_blob, total));
   uint8_t *base = (uint8_t *)p->dev_blob;
   p->d_tiles = (const DsTile *)base;
@@ -126,13 +125,9 @@ int upload(ds_plan *p) {
   DS_HIP_TRY(hipMemcpy(base + b_tiles + b_off, p->first_tile.data(), p->first_tile.size() * sizeof(uint32_t),
                        hipMemcpyHostToDevice));
   p->d_recs = (const DsChunkRec *)(base + b_tiles + b_off + b_first);
-  p->d_general_ids = (const uint32_t *)(base + b_tiles + b_off + b_first + b_recs);
   if (!p->recs.empty())
     DS_HIP_TRY(hipMemcpy(base + b_tiles + b_off + b_first, p->recs.data(), p->recs.size() * sizeof(DsChunkRec),
                          hipMemcpyHostToDevice));
-  if (!p->general_ids.empty())
-    DS_HIP_TRY(hipMemcpy(base + b_tiles + b_off + b_first + b_recs, p->general_ids.data(),
-                         p->general_ids.size() * sizeof(uint32_t), hipMemcpyHostToDevice));
   return DS_OK;
 }
 
@@ -336,7 +331,14 @@ int ds_plan_create(const ds_shard_desc *desc, size_t n, uint64_t align, uint32_t
                 r.tile = (uint32_t)(((step / tl.run_bytes) << 16) | (step % tl.run_bytes));
               }
             }
-            if ((r.kind & 0xFF) == DS_CHUNK_GENERAL) p->general_ids.push_back((uint32_t)c);
+            if ((r.kind & 0xFF) == DS_CHUNK_GENERAL) {
+              // the tiles the chunk holds, so that the kernel is one load away from them
+              uint32_t t1 = p->first_tile[c + 1];
+              const uint64_t c_end = std::min(ce, p->total_bytes);
+              if (p->tile_off[t1] >= c_end) --t1;  // that tile starts where this chunk ends
+              r.col0 = t1 - ti;
+              ++p->n_general;
+            }
           }
         }
       }
@@ -374,7 +376,7 @@ int ds_plan_info(const ds_plan *plan, ds_plan_stats *out) {
   out->n_chunks = plan->n_chunks();
   out->chunk_bytes = (uint64_t)1 << plan->chunk_log2;
   out->n_strided = plan->n_strided;
-  out->n_general_chunks = plan->general_ids.size();
+  out->n_general_chunks = plan->n_general;
   out->align = plan->align;
   return DS_OK;
 }
