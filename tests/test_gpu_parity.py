@@ -409,3 +409,76 @@ def test_pack_and_unpack_inside_a_hip_graph():
     finally:
         del graph
         dw.close()
+
+
+def _random_table(rng, arena_bytes):
+    """Shards with 0..6 dimensions, extents from 0/1 up to hundreds, strides that keep the view free of
+    self-overlap (built innermost first with random slack, then the dimensions are permuted, so transposed
+    and interleaved layouts occur), any dtype, element-aligned bases."""
+    from workloads.configs import DTYPES
+    shards = []
+    for i in range(int(rng.integers(1, 25))):
+        dtype = list(DTYPES)[int(rng.integers(0, 5))]
+        es = DTYPES[dtype][1]
+        nd = int(rng.integers(0, 7))
+        budget = int(2 ** rng.uniform(4, 17))             # elements, roughly
+        shape = []
+        for _ in range(nd):
+            e = int(rng.choice([0, 1, 1, 2, 3, 5, 8, 16, 31, 64, 100, 257]))
+            shape.append(min(e, max(budget, 1)))
+            budget = max(budget // max(e, 1), 1)
+        strides, acc = [], 1
+        for e in reversed(shape):
+            here = acc + int(rng.choice([0, 0, 0, 1, 3, 16]))
+            strides.append(here)
+            acc = here * max(e, 1)
+        strides.reverse()
+        perm = rng.permutation(nd) if nd and rng.random() < 0.4 else np.arange(nd)
+        shape = tuple(int(shape[j]) for j in perm)
+        strides = tuple(int(strides[j]) for j in perm)
+        span = 1 + sum((max(e, 1) - 1) * st for e, st in zip(shape, strides))
+        if span * es >= arena_bytes // 2:
+            continue
+        start = int(rng.integers(0, (arena_bytes - span * es) // es)) * es
+        shards.append(Shard(f"r{i}", dtype, shape, strides, start, 1000 + i))
+    return shards
+
+
+def test_random_tables_pack_and_unpack():
+    """Sixty random shard tables (see _random_table), random alignments; half of them with offsets given by
+    the caller in shuffled order with holes.  Gather and scatter against the oracle, whole image, whole arena."""
+    ds, orc, gu = _mods()
+    rng = np.random.default_rng(2601)
+    arena_bytes = 1 << 22
+    for trial in range(60):
+        arena = rng.integers(0, 256, size=arena_bytes, dtype=np.uint8)
+        shards = _random_table(rng, arena_bytes)
+        if not shards:
+            continue
+        align = int(2 ** rng.integers(4, 13))
+        w = _adhoc(arena, shards, align)
+        offsets = None
+        if trial % 2:
+            sizes = [int(np.prod(s.shape, dtype=np.int64)) * s.itemsize if len(s.shape) else s.itemsize for s in shards]
+            order = rng.permutation(len(shards))
+            at, offsets = int(rng.integers(0, 3)) * align, [0] * len(shards)
+            for j in order:
+                offsets[j] = at
+                at = -(-(at + sizes[j]) // align) * align + int(rng.integers(0, 3)) * align
+        print(f"[case] random table trial={trial} shards={len(shards)} align={align} given={offsets is not None}", flush=True)
+        want, offs, tab = gu.oracle_image(w, offsets=offsets)
+        dw = gu.DeviceWorkload(w, offsets=offsets)
+        try:
+            assert dw.total == want.size
+            got = dw.pack()
+            assert gu.first_mismatch(got, want) is None, (trial, gu.first_mismatch(got, want))
+            if want.size:
+                # shards of a table may share arena bytes; the image was gathered from ONE arena, so they
+                # agree on every shared byte and the scatter is the same in whatever order it writes
+                dw.arena.fill_(0)
+                dw.unpack(want)
+                w.arena[:] = 0
+                orc.unpack(tab, len(shards), want)
+                assert gu.first_mismatch(dw.arena_host(), w.arena) is None, trial
+        finally:
+            dw.close()
