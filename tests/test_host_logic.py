@@ -151,3 +151,47 @@ def test_config_keys():
     assert ds.ds_plan_info(plan)["n_chunks"] == 32
     ds.ds_plan_destroy(plan)
     ds.ds_config_set("chunk_bytes", 16 << 10)
+
+
+def test_plain_c_program_uses_the_header_and_the_library(tmp_path):
+    """The header is C: a C99 program built with gcc against it and the shared
+    library reports the struct layouts (compared with the binding's ctypes
+    mirrors) and runs layout, a host-only plan and a checkpoint file."""
+    import shutil
+    import subprocess
+    if shutil.which("gcc") is None:
+        pytest.skip("no gcc here")
+    exe = str(tmp_path / "abi_check")
+    libdir = os.path.dirname(ds.LIB_PATH)
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Werror", "-pedantic", "-I", os.path.join(ROOT, "include"),
+                    os.path.join(ROOT, "tests", "c_abi", "abi_check.c"), "-o", exe,
+                    "-L", libdir, "-ldatastates_hip", "-Wl,-rpath," + libdir,
+                    "-Wl,--allow-shlib-undefined"], check=True)
+    hip_dirs = [os.path.dirname(p) for p in ds.hip_runtime_in_use()] + ["/opt/rocm/lib"]
+    env = dict(os.environ, LD_LIBRARY_PATH=":".join(hip_dirs + [os.environ.get("LD_LIBRARY_PATH", "")]))
+    ckpt = str(tmp_path / "c.ckpt")
+    out = subprocess.run([exe, ckpt], check=True, capture_output=True, text=True, env=env).stdout
+    facts = dict(line.rsplit(" ", 1) for line in out.splitlines() if line.startswith(("sizeof", "offsetof")))
+    assert int(facts["sizeof ds_shard_desc"]) == ctypes.sizeof(ds.ds_shard_desc)
+    for f in ("shape", "strides", "tensor_id", "file_offset"):
+        assert int(facts[f"offsetof ds_shard_desc.{f}"]) == getattr(ds.ds_shard_desc, f).offset
+    assert int(facts["sizeof ds_plan_stats"]) == ctypes.sizeof(ds.ds_plan_stats)
+    assert int(facts["sizeof ds_engine_opts"]) == ctypes.sizeof(ds.ds_engine_opts)
+    assert int(facts["offsetof ds_engine_opts.first_launch_bytes"]) == ds.ds_engine_opts.first_launch_bytes.offset
+    assert int(facts["sizeof ds_snapshot_stats"]) == ctypes.sizeof(ds.ds_snapshot_stats)
+    assert int(facts["sizeof ds_ckpt_layout"]) == ctypes.sizeof(ds.ds_ckpt_layout)
+    assert int(facts["sizeof ds_ckpt_tensor"]) == ctypes.sizeof(ds.ds_ckpt_tensor)
+    assert int(facts["offsetof ds_ckpt_tensor.file_offset"]) == ds.ds_ckpt_tensor.file_offset.offset
+    assert "total 3328 offsets 0 512 3072" in out                 # 400 B, 2400 B, 4 B at multiples of 256
+    assert "payload 2804 shards 3 strided 1" in out
+    assert "tensors 3 objects 2 chunks 3 object42 'hello world' tensor1 id 12 ndim 2 shape 30 20" in out
+    # the file the C program wrote, read by the oracle's parser
+    from oracle import ckpt_format as fmt
+    back = fmt.parse_file(open(ckpt, "rb").read())
+    assert back["objects"] == {7: b"x", 42: b"hello world"}
+    assert [t[0] for t in back["tensors"]] == [11, 12, 13] and back["tensor_bytes"] == 3328
+    floats = np.frombuffer(back["image"], dtype=np.float32)
+    assert floats[0:100].tolist() == [float(i) for i in range(100)]
+    assert floats[128 + 20 * 3: 128 + 20 * 3 + 3].tolist() == [7 + 48 * 3, 8 + 48 * 3, 9 + 48 * 3]
+    assert floats[3072 // 4] == 5.0
+    assert len(open(ckpt, "rb").read()) == 3328 + 24 + 3 * 80 + 3 * 32 + 64
