@@ -66,6 +66,9 @@ def main() -> int:
     ap.add_argument("--experiments", action="store_true",
                     help="also run the capture variants that are measured, not shipped (direct gather into pinned "
                          "host memory; grid-limited gathers under the GEMM stream)")
+    ap.add_argument("--timeline", default=None, metavar="FILE",
+                    help="also trace one snapshot step by step (gather launches, every chunk copy) and write the "
+                         "timeline to FILE as text")
     ap.add_argument("--timed-only", action="store_true",
                     help="stop after the timed region (so that a kernel trace holds the timed launches only)")
     ap.add_argument("--kernels-only", action="store_true",
@@ -224,6 +227,58 @@ def main() -> int:
     pipelined_gbps = payload * args.steps / (time.perf_counter() - t0) / 1e9
     for ev in pevs:
         ds.ds_event_destroy(ev)
+
+    # ---- optional: the timeline of one snapshot, tier by tier ----------------------------------
+    if args.timeline:
+        eng_t = ds.ds_engine_create(args.ring_bytes, args.chunk_bytes, args.stage_slot_bytes, args.stage_slots, 0,
+                                    ds.DS_ENGINE_AUTO_RELEASE | ds.DS_ENGINE_TRACE, args.copy_streams,
+                                    args.first_launch_bytes)
+        for _ in range(2):                                   # the second one is reported
+            ev = ds.ds_snapshot_async(eng_t, plan, stream)
+            ds.ds_event_wait(ev)
+            recs = ds.ds_event_trace(ev)
+            tst = ds.ds_event_stats(ev)
+            ds.ds_event_destroy(ev)
+        ds.ds_engine_destroy(eng_t)
+        gat = [r for r in recs if r["kind"] == 0]
+        cop = [r for r in recs if r["kind"] == 1]
+        busy, cur_b, cur_e = 0.0, None, None                 # union of the copy intervals = time the link works
+        for r in sorted(cop, key=lambda r: r["begin_ms"]):
+            if cur_e is None or r["begin_ms"] > cur_e:
+                busy += (cur_e - cur_b) if cur_e is not None else 0.0
+                cur_b, cur_e = r["begin_ms"], r["end_ms"]
+            else:
+                cur_e = max(cur_e, r["end_ms"])
+        busy += (cur_e - cur_b) if cur_e is not None else 0.0
+        lines = [f"# Timeline of one snapshot, workload {args.workload} (device clock, ms since the request)", "",
+                 "Command:", "",
+                 "    python3 bench.py " + " ".join(a for a in sys.argv[1:]), "",
+                 f"image {total} B; ring slot / copy {args.chunk_bytes} B; staging {args.stage_slots} x "
+                 f"{args.stage_slot_bytes} B; copy streams {args.copy_streams}", "",
+                 "| step | image range | begin ms | end ms | duration ms | rate |", "|---|---|---|---|---|---|"]
+        for r in gat:
+            d = r["end_ms"] - r["begin_ms"]
+            lines.append(f"| gather launch {r['index']} | [{r['file_off']}, {r['file_off'] + r['len']}) | {r['begin_ms']:.3f} | "
+                         f"{r['end_ms']:.3f} | {d:.3f} | {2 * r['len'] / d / 1e6:.0f} GB/s read+write |")
+        show = cop if len(cop) <= 8 else cop[:4] + [None] + cop[-3:]
+        for r in show:
+            if r is None:
+                lines.append("| ... | | | | | |")
+                continue
+            d = r["end_ms"] - r["begin_ms"]
+            lines.append(f"| copy of chunk {r['index']} | [{r['file_off']}, {r['file_off'] + r['len']}) | {r['begin_ms']:.3f} | "
+                         f"{r['end_ms']:.3f} | {d:.3f} | {r['len'] / d / 1e6:.1f} GB/s |")
+        if cop:
+            durs = sorted(r["end_ms"] - r["begin_ms"] for r in cop)
+            first, last = min(r["begin_ms"] for r in cop), max(r["end_ms"] for r in cop)
+            lines += ["", f"{len(cop)} copies: median duration {durs[len(durs) // 2]:.3f} ms; first copy starts at "
+                      f"{first:.3f} ms ({first - gat[0]['end_ms']:.3f} ms after the first gather ended), last one ends at "
+                      f"{last:.3f} ms; the link is busy {busy:.3f} ms of the {last - first:.3f} ms between them "
+                      f"({100 * busy / (last - first):.1f} %); the tensors are free again at {tst['capture_ms']:.3f} ms, "
+                      f"the image is in the host ring at {tst['total_ms']:.3f} ms = {payload / tst['total_ms'] / 1e6:.2f} GB/s."]
+        with open(args.timeline, "w") as f:
+            f.write("\n".join(lines) + "\n")
+        log(f"[bench] timeline written to {args.timeline}")
 
     # ---- gather and scatter alone, whole image, device to device ------------------------------
     image_dev = torch.empty(max(total, 16), dtype=torch.uint8, device=dev)

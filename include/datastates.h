@@ -172,6 +172,8 @@ int ds_unpack(const ds_plan *plan, const void *src_dev, uint64_t img_lo, uint64_
  *      capture, Sec. V-A4 chunked streaming, Sec. V-C dedicated streams) ----- */
 
 #define DS_ENGINE_AUTO_RELEASE 1u /* no consumer: a ring slot is reusable as soon as its copy is done */
+#define DS_ENGINE_TRACE 2u        /* time every device-to-host copy of a snapshot (two events per chunk), for
+                                     ds_event_trace */
 
 typedef struct ds_engine_opts {
   uint64_t host_ring_bytes;  /* pinned host ring capacity, allocated and pinned once; the paper's
@@ -260,6 +262,25 @@ typedef struct ds_snapshot_stats {
 
 /* Valid after ds_event_wait returned DS_OK. */
 int ds_event_stats(ds_event *ev, ds_snapshot_stats *out);
+
+/* One step of a snapshot on the device's clock, in milliseconds since the request
+ * (the per-tier timeline of Sec. VI-D, Fig. 13, for this pipeline). */
+typedef struct ds_trace_rec {
+  uint32_t kind;      /* 0 = gather launch, 1 = device-to-host copy of one chunk */
+  uint32_t index;     /* launch number / chunk number                           */
+  uint64_t file_off;  /* image range the step covers                            */
+  uint64_t len;
+  double begin_ms;
+  double end_ms;
+} ds_trace_rec;
+
+/*
+ * Writes the records of a finished snapshot to out[0 .. cap): the gather
+ * launches, then -- on an engine with DS_ENGINE_TRACE -- the copies in chunk
+ * order.  *n = number of records there are (call with cap = 0 to ask).
+ * Errors: DS_EBUSY (not finished), DS_ESTATE (a restore event), DS_EHIP.
+ */
+int ds_event_trace(ds_event *ev, ds_trace_rec *out, size_t cap, size_t *n);
 
 /* Waits for the snapshot, releases chunks still held, frees the event. */
 int ds_event_destroy(ds_event *ev);

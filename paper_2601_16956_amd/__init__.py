@@ -22,7 +22,7 @@ DS_EINVAL, DS_EALIGN, DS_EOVERLAP, DS_EGAP, DS_ERANGE, DS_ENOMEM, DS_EHIP, DS_EB
 DS_EFORMAT = -11
 DS_FILE_DIRECT, DS_FILE_SYNC = 1, 2
 DS_PLAN_STRICT, DS_PLAN_HOST_ONLY = 1, 2
-DS_ENGINE_AUTO_RELEASE = 1
+DS_ENGINE_AUTO_RELEASE, DS_ENGINE_TRACE = 1, 2
 
 # every symbol include/datastates.h declares
 EXPORTS = [
@@ -35,7 +35,7 @@ EXPORTS = [
     "ds_flush_start", "ds_flush_wait", "ds_restore_from_file", "ds_last_errno",
     "ds_plan_shard_shape", "ds_ckpt_create", "ds_ckpt_flush_snapshot", "ds_ckpt_write_region", "ds_ckpt_append",
     "ds_ckpt_finish", "ds_ckpt_open", "ds_ckpt_close", "ds_ckpt_layout_info", "ds_ckpt_tensor_info",
-    "ds_ckpt_object_at", "ds_ckpt_object_read", "ds_ckpt_matches_plan", "ds_ckpt_restore",
+    "ds_ckpt_object_at", "ds_ckpt_object_read", "ds_ckpt_matches_plan", "ds_ckpt_restore", "ds_event_trace",
 ]
 
 
@@ -81,6 +81,17 @@ class ds_snapshot_stats(ctypes.Structure):
         ("capture_ms", ctypes.c_double),
         ("total_ms", ctypes.c_double),
         ("submit_host_ms", ctypes.c_double),
+    ]
+
+
+class ds_trace_rec(ctypes.Structure):
+    _fields_ = [
+        ("kind", ctypes.c_uint32),
+        ("index", ctypes.c_uint32),
+        ("file_off", ctypes.c_uint64),
+        ("len", ctypes.c_uint64),
+        ("begin_ms", ctypes.c_double),
+        ("end_ms", ctypes.c_double),
     ]
 
 
@@ -181,6 +192,7 @@ def _load() -> ctypes.CDLL:
         "ds_ckpt_object_read": ([vp, u64, vp, u64, P(u64)], ctypes.c_int),
         "ds_ckpt_matches_plan": ([vp, vp], ctypes.c_int),
         "ds_ckpt_restore": ([vp, vp, vp, u32, u32, vp, P(vp)], ctypes.c_int),
+        "ds_event_trace": ([vp, P(ds_trace_rec), sz, P(sz)], ctypes.c_int),
     }
     for name, (args, res) in sig.items():
         fn = getattr(L, name)
@@ -499,3 +511,13 @@ def ds_ckpt_restore(reader: int, engine: int, plan: int, threads: int = 0, flags
     _check(_lib.ds_ckpt_restore(reader, engine, plan, threads, flags, compute_stream, ctypes.byref(out)),
            "ds_ckpt_restore")
     return int(out.value)
+
+
+def ds_event_trace(ev: int) -> List[dict]:
+    """Records of a finished snapshot: gather launches (kind 0), then, on a tracing engine, the chunk copies
+    (kind 1); times in milliseconds since the request."""
+    n = ctypes.c_size_t(0)
+    _check(_lib.ds_event_trace(ev, None, 0, ctypes.byref(n)), "ds_event_trace")
+    recs = (ds_trace_rec * max(n.value, 1))()
+    _check(_lib.ds_event_trace(ev, recs, n.value, ctypes.byref(n)), "ds_event_trace")
+    return [{f: getattr(recs[i], f) for f, _ in ds_trace_rec._fields_} for i in range(n.value)]

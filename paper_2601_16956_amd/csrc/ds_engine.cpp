@@ -74,6 +74,8 @@ struct ds_event {
   const ds_plan *plan = nullptr;
   hipEvent_t requested = nullptr, captured = nullptr, final_ev = nullptr, copy_begin = nullptr;
   std::vector<hipEvent_t> pack_begin, pack_end;
+  std::vector<uint64_t> pack_lo, pack_hi;          // image range of each gather launch
+  std::vector<hipEvent_t> copy_b, copy_e;           // DS_ENGINE_TRACE: around every chunk's copy
   std::vector<DsChunk> chunks;
   uint32_t cursor = 0;  // next chunk the consumer gets
   bool capture_issued = false;  // the last gather (and the `captured` event) is enqueued
@@ -147,6 +149,8 @@ int issue_snapshot(ds_engine *g, ds_event *ev) {
     ev->pack_begin.push_back(b);
     W_TRY(hipEventCreate(&e));
     ev->pack_end.push_back(e);
+    ev->pack_lo.push_back(gr.lo);
+    ev->pack_hi.push_back(gr.hi);
     W_TRY(hipEventRecord(b, g->pack_stream));
     int rc = ds_launch_move(plan, true, slot, gr.lo, gr.hi, g->grid_limit, g->pack_stream);
     if (rc != DS_OK) return rc;
@@ -178,7 +182,16 @@ int issue_snapshot(ds_engine *g, ds_event *ev) {
       hipStream_t cs = g->copy_stream[c];
       // the slot's previous copy may have run on the other copy stream
       if (g->n_copy_streams > 1) W_TRY(hipStreamWaitEvent(cs, g->ring_done[r], 0));
+      if (g->flags & DS_ENGINE_TRACE) {
+        hipEvent_t tb, te;
+        W_TRY(hipEventCreate(&tb));
+        ev->copy_b.push_back(tb);
+        W_TRY(hipEventCreate(&te));
+        ev->copy_e.push_back(te);
+        W_TRY(hipEventRecord(tb, cs));
+      }
       W_TRY(hipMemcpyAsync(g->ring + (uint64_t)r * g->chunk_bytes, slot + (lo - gr.lo), len, hipMemcpyDeviceToHost, cs));
+      if (g->flags & DS_ENGINE_TRACE) W_TRY(hipEventRecord(ev->copy_e.back(), cs));
       W_TRY(hipEventRecord(g->ring_done[r], cs));
       {
         std::lock_guard<std::mutex> lk(g->mu);
@@ -281,7 +294,7 @@ extern "C" {
 
 int ds_engine_create(const ds_engine_opts *o, ds_engine **out) {
   if (!o || !out) return DS_EINVAL;
-  if (o->flags & ~DS_ENGINE_AUTO_RELEASE) return DS_EINVAL;
+  if (o->flags & ~(DS_ENGINE_AUTO_RELEASE | DS_ENGINE_TRACE)) return DS_EINVAL;
   const uint64_t chunk = o->d2h_chunk_bytes ? o->d2h_chunk_bytes : (32ull << 20);
   const uint64_t ring_bytes = o->host_ring_bytes ? o->host_ring_bytes : (2ull << 30);
   const uint64_t slot = o->stage_slot_bytes ? o->stage_slot_bytes : (1ull << 30);
@@ -529,6 +542,35 @@ int ds_event_stats(ds_event *ev, ds_snapshot_stats *out) {
   return DS_OK;
 }
 
+int ds_event_trace(ds_event *ev, ds_trace_rec *out, size_t cap, size_t *n) {
+  if (!ev || !n || (!out && cap)) return DS_EINVAL;
+  if (ev->restore) return DS_ESTATE;
+  int rc = ds_event_query(ev);
+  if (rc == DS_NOT_READY) return DS_EBUSY;
+  if (rc != DS_OK) return rc;
+  size_t k = 0;
+  auto put = [&](uint32_t kind, uint32_t index, uint64_t off, uint64_t len, hipEvent_t b, hipEvent_t e) -> int {
+    if (k < cap) {
+      float tb = 0, te = 0;
+      DS_HIP_TRY(hipEventElapsedTime(&tb, ev->requested, b));
+      DS_HIP_TRY(hipEventElapsedTime(&te, ev->requested, e));
+      out[k] = {kind, index, off, len, (double)tb, (double)te};
+    }
+    ++k;
+    return DS_OK;
+  };
+  for (size_t i = 0; i < ev->pack_lo.size(); ++i) {
+    rc = put(0, (uint32_t)i, ev->pack_lo[i], ev->pack_hi[i] - ev->pack_lo[i], ev->pack_begin[i], ev->pack_end[i]);
+    if (rc != DS_OK) return rc;
+  }
+  for (size_t i = 0; i < ev->copy_b.size() && i < ev->copy_e.size(); ++i) {
+    rc = put(1, (uint32_t)i, ev->chunks[i].file_off, ev->chunks[i].len, ev->copy_b[i], ev->copy_e[i]);
+    if (rc != DS_OK) return rc;
+  }
+  *n = k;
+  return DS_OK;
+}
+
 int ds_event_destroy(ds_event *ev) {
   if (!ev) return DS_EINVAL;
   ds_engine *g = ev->eng;
@@ -583,6 +625,8 @@ int ds_event_destroy(ds_event *ev) {
   }
   destroy_events(ev->pack_begin);
   destroy_events(ev->pack_end);
+  destroy_events(ev->copy_b);
+  destroy_events(ev->copy_e);
   for (hipEvent_t e : {ev->requested, ev->captured, ev->final_ev, ev->copy_begin})
     if (e) (void)hipEventDestroy(e);
   {

@@ -439,3 +439,51 @@ def test_flush_io_error_does_not_stall_the_snapshot():
     finally:
         ds.ds_engine_destroy(eng)
         dw.close()
+
+
+def test_timeline_trace_of_a_snapshot():
+    """An engine with DS_ENGINE_TRACE times every chunk copy: the records cover the
+    image exactly once per tier, every copy starts after the gather that filled its
+    staging slot has ended, and copies on one stream do not overlap."""
+    ds, orc, gu, torch = _mods()
+    w = W.fragmentation(1500, max_bytes=1 << 17, seed=97)
+    print("[case] timeline trace", flush=True)
+    dw = gu.DeviceWorkload(w)
+    eng = ds.ds_engine_create(64 * MiB, 2 * MiB, 16 * MiB, 2, 0, ds.DS_ENGINE_AUTO_RELEASE | ds.DS_ENGINE_TRACE, 1)
+    s = torch.cuda.current_stream().cuda_stream
+    try:
+        ev = ds.ds_snapshot_async(eng, dw.plan, s)
+        try:
+            ds.ds_event_trace(ev)              # most likely still in flight
+        except ds.DsError as e:
+            assert e.code == ds.DS_EBUSY
+        ds.ds_event_wait(ev)
+        recs = ds.ds_event_trace(ev)
+        st = ds.ds_event_stats(ev)
+        gathers = [r for r in recs if r["kind"] == 0]
+        copies = [r for r in recs if r["kind"] == 1]
+        assert len(gathers) == st["n_pack_launches"] == -(-dw.total // (16 * MiB))
+        assert len(copies) == st["n_copies"]
+        for tier in (gathers, copies):
+            at = 0
+            for r in tier:
+                assert r["file_off"] == at and r["len"] > 0 and r["end_ms"] >= r["begin_ms"] >= 0
+                at += r["len"]
+            assert at == dw.total
+        for c in copies:
+            g = gathers[c["file_off"] // (16 * MiB)]
+            assert c["begin_ms"] >= g["end_ms"] - 1e-3
+        for a, b in zip(copies, copies[1:]):
+            assert b["begin_ms"] >= a["end_ms"] - 1e-3            # one copy stream: in order
+        assert abs(max(c["end_ms"] for c in copies) - st["total_ms"]) < 0.5
+        ds.ds_event_destroy(ev)
+        # without the flag only the gathers are reported
+        eng2 = ds.ds_engine_create(64 * MiB, 2 * MiB, 16 * MiB, 2, 0, ds.DS_ENGINE_AUTO_RELEASE, 1)
+        ev = ds.ds_snapshot_async(eng2, dw.plan, s)
+        ds.ds_event_wait(ev)
+        assert {r["kind"] for r in ds.ds_event_trace(ev)} == {0}
+        ds.ds_event_destroy(ev)
+        ds.ds_engine_destroy(eng2)
+    finally:
+        ds.ds_engine_destroy(eng)
+        dw.close()
