@@ -66,6 +66,9 @@ def main() -> int:
     ap.add_argument("--experiments", action="store_true",
                     help="also run the capture variants that are measured, not shipped (direct gather into pinned "
                          "host memory; grid-limited gathers under the GEMM stream)")
+    ap.add_argument("--variant", type=int, default=0, choices=[0, 1, 2, 3],
+                    help="kernel variant (ds_config_set): 0 default, 1 plain accesses, 2 non-temporal global accesses, "
+                         "3 default accesses with work-group i on chunk i")
     ap.add_argument("--timeline", default=None, metavar="FILE",
                     help="also trace one snapshot step by step (gather launches, every chunk copy) and write the "
                          "timeline to FILE as text")
@@ -106,6 +109,7 @@ def main() -> int:
     info = ds.ds_plan_info(plan)
     payload = info["payload_bytes"]
     stream = torch.cuda.current_stream().cuda_stream
+    ds.ds_config_set("variant", args.variant)
 
     if args.kernels_only:
         image_dev = torch.empty(max(total, 16), dtype=torch.uint8, device=dev)
