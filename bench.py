@@ -406,6 +406,7 @@ def main() -> int:
             evs = []
             prev = None
             a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            loop.gate_host_ms = 0.0
             torch.cuda.synchronize()
             w0 = time.perf_counter()
             a.record()
@@ -413,7 +414,9 @@ def main() -> int:
                 for _ in range(G):                                # state is only read here
                     torch.matmul(A, B, out=C)
                 if prev is not None:
+                    g0 = time.perf_counter()
                     ds.ds_event_wait_on_stream(prev, stream)      # the lazy gate
+                    loop.gate_host_ms += (time.perf_counter() - g0) * 1e3
                 arena.add_(1)                                     # the mutating update phase
                 if with_snapshots:
                     prev = ds.ds_snapshot_async(eng, plan, stream)
@@ -429,7 +432,12 @@ def main() -> int:
         loop(True)
         base = min(loop(False) for _ in range(2))
         with_s = min(loop(True) for _ in range(2))
+        blocked_ms = max(with_s - base, 1e-6) / args.gemm_iters
         overlap = {
+            # the paper's measure (Sec. VI-B): checkpoint size over the time training is blocked by it
+            "blocked_ms_per_iter": round(blocked_ms, 4),
+            "effective_checkpoint_GBps": round(payload / blocked_ms / 1e6, 1),
+            "gate_call_host_ms_per_iter": round(loop.gate_host_ms / args.gemm_iters, 4),
             "gemm": "bf16 8192x8192x8192 (torch.matmul)", "gemm_ms": round(gemm_ms, 3),
             "gemm_tflops": round(2 * M ** 3 / gemm_ms / 1e9, 1), "gemms_per_iter": G, "iters": args.gemm_iters,
             "ms_without_snapshots": round(base, 2), "ms_with_snapshots": round(with_s, 2),
