@@ -434,7 +434,7 @@ def main() -> int:
         with_s = min(loop(True) for _ in range(2))
         blocked_ms = max(with_s - base, 1e-6) / args.gemm_iters
         overlap = {
-            # the paper's measure (Sec. VI-B): checkpoint size over the time training is blocked by it
+            # the paper's measure (Sec. VI-D, scaling of model sizes): checkpoint size over the time training is blocked by it
             "blocked_ms_per_iter": round(blocked_ms, 4),
             "effective_checkpoint_GBps": round(payload / blocked_ms / 1e6, 1),
             "gate_call_host_ms_per_iter": round(loop.gate_host_ms / args.gemm_iters, 4),

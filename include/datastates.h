@@ -264,7 +264,7 @@ typedef struct ds_snapshot_stats {
 int ds_event_stats(ds_event *ev, ds_snapshot_stats *out);
 
 /* One step of a snapshot on the device's clock, in milliseconds since the request
- * (the per-tier timeline of Sec. VI-D, Fig. 13, for this pipeline). */
+ * (what Sec. VI-D's timeline of tensors across the tiers shows, for this pipeline). */
 typedef struct ds_trace_rec {
   uint32_t kind;      /* 0 = gather launch, 1 = device-to-host copy of one chunk */
   uint32_t index;     /* launch number / chunk number                           */
