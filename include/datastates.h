@@ -19,8 +19,13 @@
  *   - Every function returns an int: DS_OK (0), a positive status
  *     (DS_NOT_READY, DS_EOF) or a negative error.  Nothing throws or aborts.
  *     Out-parameters are written only on DS_OK (or the documented status).
- *   - A plan is immutable once created and may be used from several threads;
- *     calls on one engine are serialised by the caller.
+ *   - A plan is immutable once created and may be used from several threads.
+ *     Requests on one engine (create / destroy, ds_snapshot_async,
+ *     ds_restore_*) are serialised by the caller; the calls on an event may
+ *     come from other threads than the request -- the gate from the training
+ *     thread, ds_snapshot_next_chunk from ONE consumer thread, and
+ *     ds_snapshot_release_chunk from any number of threads (a flush does
+ *     exactly that).
  *   - The image.  For shard i:  bytes_i = itemsize(dtype_i) * prod(shape_i)
  *     (empty product = 1).  Image byte  file_offset_i + r*itemsize + b  is byte
  *     b of the element of rank r in the row-major (last index fastest)
