@@ -487,3 +487,53 @@ def test_timeline_trace_of_a_snapshot():
     finally:
         ds.ds_engine_destroy(eng)
         dw.close()
+
+
+def test_two_engines_from_two_threads():
+    """Two engines, each driven by its own thread with its own plan and stream,
+    at the same time: nothing is shared but the device, so both images must be
+    the oracle's."""
+    import threading
+    ds, orc, gu, torch = _mods()
+    ws = [W.fragmentation(1200, max_bytes=1 << 17, seed=201), W.llama_rank("mini", 256, 704, 4, 2, 1024, 2, 4, 8, seed=7, workers=2)]
+    print("[case] two engines", flush=True)
+    wants = [gu.oracle_image(w)[0] for w in ws]
+    dws = [gu.DeviceWorkload(w) for w in ws]
+    torch.cuda.synchronize()
+    results, errors = [None, None], []
+
+    def run(i):
+        try:
+            torch.cuda.set_device(0)
+            st = torch.cuda.Stream()
+            eng = ds.ds_engine_create(8 * MiB, 1 * MiB, 8 * MiB, 2, 0, 0, 2)
+            try:
+                for rep in range(3):
+                    ev = ds.ds_snapshot_async(eng, dws[i].plan, st.cuda_stream)
+                    got = np.empty(dws[i].total, dtype=np.uint8)
+                    while True:
+                        ch = ds.ds_snapshot_next_chunk(ev)
+                        if ch is None:
+                            break
+                        ptr, off, ln = ch
+                        ctypes.memmove(got.ctypes.data + off, ptr, ln)
+                        ds.ds_snapshot_release_chunk(ev, ptr)
+                    ds.ds_event_wait(ev)
+                    ds.ds_event_destroy(ev)
+                    assert gu.first_mismatch(got, wants[i]) is None, (i, rep)
+                results[i] = True
+            finally:
+                ds.ds_engine_destroy(eng)
+        except BaseException as e:   # noqa: BLE001 - reported in the main thread
+            errors.append((i, repr(e)))
+
+    import ctypes
+    ts = [threading.Thread(target=run, args=(i,)) for i in range(2)]
+    for t in ts:
+        t.start()
+    for t in ts:
+        t.join()
+    for dw in dws:
+        dw.close()
+    assert not errors, errors
+    assert results == [True, True]
