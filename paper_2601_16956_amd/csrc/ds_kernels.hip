@@ -38,7 +38,6 @@
 // is one (possibly unaligned) dwordx4 access; a unit that is cut by the end of
 // a run or of the payload is moved element by element with exact bounds, so no
 // byte outside the described views is ever read or written.
-#include <algorithm>
 
 #include "ds_internal.h"
 
