@@ -62,6 +62,9 @@ def main() -> int:
     ap.add_argument("--no-file", action="store_true", help="skip the file-tier leg")
     ap.add_argument("--file-dir", default="/tmp", help="where the file-tier leg writes its image")
     ap.add_argument("--file-threads", type=int, default=8)
+    ap.add_argument("--file-engine", default="threads", choices=["threads", "uring"],
+                    help="writers of the file tier: pwrite threads, or one thread with that many writes in flight "
+                         "through io_uring")
     ap.add_argument("--gemm-iters", type=int, default=20, help="iterations of the overlap leg")
     ap.add_argument("--experiments", action="store_true",
                     help="also run the capture variants that are measured, not shipped (direct gather into pinned "
@@ -558,7 +561,8 @@ def main() -> int:
                 torch.cuda.synchronize()
                 t0 = time.perf_counter()
                 ev = ds.ds_snapshot_async(eng2, plan, stream)
-                ck = ds.ds_ckpt_create(path, plan, ds.DS_FILE_DIRECT)
+                ck = ds.ds_ckpt_create(path, plan, ds.DS_FILE_DIRECT |
+                                       (ds.DS_FILE_URING if args.file_engine == "uring" else 0))
                 ds.ds_ckpt_flush_snapshot(ck, ev, args.file_threads)
 
                 def objects(t):
@@ -594,7 +598,8 @@ def main() -> int:
 
         try:
             dirs = [args.file_dir] + (["/dev/shm"] if os.path.isdir("/dev/shm") and args.file_dir != "/dev/shm" else [])
-            file_tier = {"threads": args.file_threads,
+            file_tier = {"threads": args.file_threads, "engine": args.file_engine,
+                         "io_uring_available": ds.ds_config_get("io_uring_available"),
                          "note": "request -> trailer written (page cache, no fsync); open + check -> tensors restored; "
                                  "/dev/shm is memory-backed: the software path without the disk",
                          "runs": [one_dir(d) for d in dirs]}

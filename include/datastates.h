@@ -327,6 +327,9 @@ int ds_restore_submit(ds_event *ev, const void *host_ptr);
                              ring's pages, else through an aligned buffer of ordinary memory (one extra
                              memory-speed copy, no page cache); anything else, and everything on a file
                              system without direct I/O, goes through a buffered descriptor */
+#define DS_FILE_URING 4u  /* writes of a flush go through the kernel's io_uring interface: one thread keeps up
+                             to `threads` writes in flight (Sec. V-C); where the process may not have an
+                             io_uring (ds_config_get("io_uring_available") = 0) the pwrite threads are used */
 #define DS_FILE_SYNC 2u   /* fsync before ds_flush_wait returns                                        */
 
 /*
@@ -383,7 +386,7 @@ int ds_last_errno(void);
 /*
  * Creates / truncates `path` for a checkpoint of `plan` (which may be a
  * DS_PLAN_HOST_ONLY plan when the tensor region comes from host memory).
- * flags: DS_FILE_DIRECT / DS_FILE_SYNC as for a flush.  The plan must outlive
+ * flags: DS_FILE_DIRECT / DS_FILE_SYNC / DS_FILE_URING as for a flush.  The plan must outlive
  * the ds_ckpt.  Errors: DS_EINVAL, DS_ENOMEM, DS_EIO.
  */
 int ds_ckpt_create(const char *path, const ds_plan *plan, uint32_t flags, ds_ckpt **out);
@@ -483,6 +486,7 @@ int ds_copy_probe(void *dst_dev, const void *src_dev, uint64_t nbytes, void *str
  *                   work-group i takes chunk i (no XCD-contiguous order)
  *   "grid_limit"    work-groups per launch of ds_pack / ds_unpack (each then walks several chunks);
  *                   0 = one per chunk (default).  Engines have their own pack_grid_limit
+ *   "io_uring_available"  (get only) 1 if this process can set up an io_uring, else 0
  * Returns DS_EINVAL for an unknown key or a value out of range.
  */
 int ds_config_set(const char *key, uint64_t value);

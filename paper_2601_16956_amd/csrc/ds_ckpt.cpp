@@ -124,7 +124,7 @@ struct ds_ckpt_reader {
 extern "C" {
 
 int ds_ckpt_create(const char *path, const ds_plan *plan, uint32_t flags, ds_ckpt **out) {
-  if (!path || !plan || !out || (flags & ~(DS_FILE_DIRECT | DS_FILE_SYNC))) return DS_EINVAL;
+  if (!path || !plan || !out || (flags & ~(DS_FILE_DIRECT | DS_FILE_SYNC | DS_FILE_URING))) return DS_EINVAL;
   ds_ckpt *c = new (std::nothrow) ds_ckpt;
   if (!c) return DS_ENOMEM;
   c->fd = open(path, O_RDWR | O_CREAT | O_TRUNC | O_CLOEXEC, 0644);
@@ -145,7 +145,8 @@ int ds_ckpt_create(const char *path, const ds_plan *plan, uint32_t flags, ds_ckp
 int ds_ckpt_flush_snapshot(ds_ckpt *c, ds_event *snapshot, uint32_t threads) {
   if (!c || !snapshot) return DS_EINVAL;
   if (c->flush) return DS_ESTATE;
-  return ds_flush_start_fds(snapshot, c->fd, c->fd_direct, threads, c->flags & DS_FILE_DIRECT, &c->flush);
+  return ds_flush_start_fds(snapshot, c->fd, c->fd_direct, threads, c->flags & (DS_FILE_DIRECT | DS_FILE_URING),
+                            &c->flush);
 }
 
 int ds_ckpt_write_region(ds_ckpt *c, uint64_t file_off, const void *host, uint64_t len) {

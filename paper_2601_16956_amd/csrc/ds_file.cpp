@@ -6,13 +6,19 @@
 // ds_snapshot_next_chunk / ds_snapshot_release_chunk, a file restore is a
 // producer for ds_restore_next_slot / ds_restore_submit.  Writes and reads go
 // to the byte offsets the plan fixed (Sec. V-A5 rule (1)), so several threads
-// work on one file without coordination.  Plain pwrite/pread: liburing is not
-// installed here, and the point is the overlap of file I/O with the copies,
-// not the submission interface.
+// work on one file without coordination.  Writes go out either from a pool of
+// threads that call pwrite, or -- DS_FILE_URING -- from ONE thread that keeps
+// up to `threads` writes in flight through the kernel's io_uring interface
+// (Sec. V-C names liburing; that library is not installed here, so the rings
+// are set up and driven with the raw system calls).  Reads use pread threads.
 #include <fcntl.h>
+#include <linux/io_uring.h>
+#include <sys/mman.h>
 #include <sys/stat.h>
+#include <sys/syscall.h>
 #include <unistd.h>
 
+#include <algorithm>
 #include <atomic>
 #include <cerrno>
 #include <cstdlib>
@@ -165,6 +171,218 @@ void writer_main(ds_flush *f) {
   }
 }
 
+// ---- io_uring, by system call ---------------------------------------------------------------
+// The submission ring holds indices into an array of request entries, the completion ring the results;
+// both are shared with the kernel and updated with acquire / release accesses to their head and tail.
+struct Uring {
+  int fd = -1;
+  unsigned entries = 0, pending = 0, tail_local = 0;
+  unsigned *sq_head = nullptr, *sq_tail = nullptr, *sq_mask = nullptr, *sq_array = nullptr;
+  unsigned *cq_head = nullptr, *cq_tail = nullptr, *cq_mask = nullptr;
+  io_uring_sqe *sqes = nullptr;
+  io_uring_cqe *cqes = nullptr;
+  void *sq_map = MAP_FAILED, *cq_map = MAP_FAILED, *sqe_map = MAP_FAILED;
+  size_t sq_len = 0, cq_len = 0, sqe_len = 0;
+
+  int open_ring(unsigned want) {  // 0 or errno
+    io_uring_params p;
+    std::memset(&p, 0, sizeof(p));
+    fd = (int)syscall(__NR_io_uring_setup, want, &p);
+    if (fd < 0) return errno;
+    sq_len = p.sq_off.array + p.sq_entries * sizeof(unsigned);
+    cq_len = p.cq_off.cqes + p.cq_entries * sizeof(io_uring_cqe);
+    const bool single = (p.features & IORING_FEAT_SINGLE_MMAP) != 0;
+    if (single) sq_len = cq_len = std::max(sq_len, cq_len);
+    sq_map = mmap(nullptr, sq_len, PROT_READ | PROT_WRITE, MAP_SHARED | MAP_POPULATE, fd, IORING_OFF_SQ_RING);
+    if (sq_map == MAP_FAILED) return errno ? errno : ENOMEM;
+    cq_map = single ? sq_map
+                    : mmap(nullptr, cq_len, PROT_READ | PROT_WRITE, MAP_SHARED | MAP_POPULATE, fd, IORING_OFF_CQ_RING);
+    if (cq_map == MAP_FAILED) return errno ? errno : ENOMEM;
+    sqe_len = p.sq_entries * sizeof(io_uring_sqe);
+    sqe_map = mmap(nullptr, sqe_len, PROT_READ | PROT_WRITE, MAP_SHARED | MAP_POPULATE, fd, IORING_OFF_SQES);
+    if (sqe_map == MAP_FAILED) return errno ? errno : ENOMEM;
+    uint8_t *sq = (uint8_t *)sq_map, *cq = (uint8_t *)cq_map;
+    sq_head = (unsigned *)(sq + p.sq_off.head);
+    sq_tail = (unsigned *)(sq + p.sq_off.tail);
+    sq_mask = (unsigned *)(sq + p.sq_off.ring_mask);
+    sq_array = (unsigned *)(sq + p.sq_off.array);
+    cq_head = (unsigned *)(cq + p.cq_off.head);
+    cq_tail = (unsigned *)(cq + p.cq_off.tail);
+    cq_mask = (unsigned *)(cq + p.cq_off.ring_mask);
+    cqes = (io_uring_cqe *)(cq + p.cq_off.cqes);
+    sqes = (io_uring_sqe *)sqe_map;
+    entries = p.sq_entries;
+    tail_local = *sq_tail;
+    return 0;
+  }
+  void close_ring() {
+    if (sqe_map != MAP_FAILED) munmap(sqe_map, sqe_len);
+    if (cq_map != MAP_FAILED && cq_map != sq_map) munmap(cq_map, cq_len);
+    if (sq_map != MAP_FAILED) munmap(sq_map, sq_len);
+    if (fd >= 0) close(fd);
+    sqe_map = cq_map = sq_map = MAP_FAILED;
+    fd = -1;
+  }
+  // queues one write; false if the submission ring is full
+  bool queue_write(int file, const void *buf, uint64_t len, uint64_t off, uint64_t user) {
+    const unsigned head = __atomic_load_n(sq_head, __ATOMIC_ACQUIRE);
+    if (tail_local - head >= entries) return false;
+    const unsigned idx = tail_local & *sq_mask;
+    io_uring_sqe *e = &sqes[idx];
+    std::memset(e, 0, sizeof(*e));
+    e->opcode = IORING_OP_WRITE;
+    e->fd = file;
+    e->addr = (uint64_t)(uintptr_t)buf;
+    e->len = (uint32_t)len;
+    e->off = off;
+    e->user_data = user;
+    sq_array[idx] = idx;
+    ++tail_local;
+    ++pending;
+    return true;
+  }
+  // hands the queued requests to the kernel and waits for at least min_complete results; 0 or errno
+  int submit_and_wait(unsigned min_complete) {
+    __atomic_store_n(sq_tail, tail_local, __ATOMIC_RELEASE);
+    for (;;) {
+      const long r = syscall(__NR_io_uring_enter, fd, pending, min_complete, IORING_ENTER_GETEVENTS, nullptr, 0);
+      if (r < 0) {
+        if (errno == EINTR) continue;
+        return errno;
+      }
+      pending -= (unsigned)r < pending ? (unsigned)r : pending;
+      return 0;
+    }
+  }
+  bool pop(uint64_t *user, int *res) {
+    const unsigned head = *cq_head;
+    if (head == __atomic_load_n(cq_tail, __ATOMIC_ACQUIRE)) return false;
+    const io_uring_cqe &c = cqes[head & *cq_mask];
+    *user = c.user_data;
+    *res = c.res;
+    __atomic_store_n(cq_head, head + 1, __ATOMIC_RELEASE);
+    return true;
+  }
+};
+
+constexpr uint64_t kUringMaxWrite = 1u << 30;  // one request carries a 32-bit length
+
+// One thread, up to `depth` writes in flight.  With direct I/O a slot is copied into an aligned buffer of
+// ordinary memory and given back to the ring at once; a buffered write goes out of the slot itself, which
+// is given back when the write has completed.
+void uring_writer_main(ds_flush *f, Uring *ring, unsigned depth) {
+  struct Op {
+    bool busy = false, direct = false, holds_slot = false;
+    IoJob j;
+    Bounce bounce;
+    const uint8_t *src = nullptr;
+    uint64_t off = 0, left = 0;
+  };
+  std::vector<Op> ops(depth);
+  unsigned inflight = 0;
+  auto release = [&](Op &op) {
+    if (op.holds_slot) {
+      int rc = ds_snapshot_release_chunk(f->ev, op.j.ptr);
+      if (rc != DS_OK) flush_fail(f, rc, 0);
+      op.holds_slot = false;
+    }
+  };
+  auto queue_op = [&](unsigned i) {
+    Op &op = ops[i];
+    const uint64_t n = op.left < kUringMaxWrite ? op.left : kUringMaxWrite;
+    // the ring has 2 x depth entries and at most depth requests are ever queued: this cannot fail
+    (void)ring->queue_write(op.direct ? f->fd_direct : f->fd_buffered, op.src, n, op.off, i);
+  };
+  for (;;) {
+    // take new jobs while there is room
+    while (inflight < depth) {
+      IoJob j;
+      {
+        std::unique_lock<std::mutex> lk(f->mu);
+        if (inflight == 0) f->cv.wait(lk, [&] { return f->no_more || !f->queue.empty(); });
+        if (f->queue.empty()) break;
+        j = f->queue.front();
+        f->queue.pop_front();
+      }
+      unsigned i = 0;
+      while (ops[i].busy) ++i;
+      Op &op = ops[i];
+      op.j = j;
+      op.holds_slot = true;
+      if (f->status.load() != DS_OK) {  // after a failure the slots only go back
+        release(op);
+        continue;
+      }
+      op.direct = f->fd_direct >= 0 && f->bounce_usable.load() && direct_ok(j.ptr, j.off, j.len);
+      uint8_t *b = op.direct ? op.bounce.fit(j.len) : nullptr;
+      if (op.direct && !b) op.direct = false;
+      if (op.direct) {
+        std::memcpy(b, j.ptr, j.len);
+        release(op);  // the ring slot is free for the next copy while this write is under way
+        op.src = b;
+      } else {
+        op.src = (const uint8_t *)j.ptr;
+      }
+      op.off = j.off;
+      op.left = j.len;
+      op.busy = true;
+      ++inflight;
+      queue_op(i);
+    }
+    if (inflight == 0) {
+      std::lock_guard<std::mutex> lk(f->mu);
+      if (f->no_more && f->queue.empty()) break;
+      continue;
+    }
+    const int e = ring->submit_and_wait(1);
+    if (e) {  // the interface itself failed: give everything back and stop
+      flush_fail(f, DS_EIO, e);
+      for (Op &op : ops)
+        if (op.busy) release(op);
+      for (;;) {
+        IoJob j;
+        {
+          std::unique_lock<std::mutex> lk(f->mu);
+          f->cv.wait(lk, [&] { return f->no_more || !f->queue.empty(); });
+          if (f->queue.empty()) break;
+          j = f->queue.front();
+          f->queue.pop_front();
+        }
+        (void)ds_snapshot_release_chunk(f->ev, j.ptr);
+      }
+      break;
+    }
+    uint64_t user;
+    int res;
+    while (ring->pop(&user, &res)) {
+      Op &op = ops[(unsigned)user];
+      if (res < 0 && op.direct && res == -EINVAL) {
+        // the file system has no direct I/O after all: the same bytes through the buffered descriptor
+        f->bounce_usable.store(false);
+        op.direct = false;
+        queue_op((unsigned)user);
+        continue;
+      }
+      if (res < 0 || res == 0) {
+        flush_fail(f, DS_EIO, res < 0 ? -res : EIO);
+      } else if ((uint64_t)res < op.left) {  // a short write: the rest goes out as a new request
+        op.src += res;
+        op.off += (uint64_t)res;
+        op.left -= (uint64_t)res;
+        queue_op((unsigned)user);
+        continue;
+      } else {
+        f->bytes.fetch_add(op.j.len);
+      }
+      release(op);
+      op.busy = false;
+      --inflight;
+    }
+  }
+  ring->close_ring();
+  delete ring;
+}
+
 void dispatcher_main(ds_flush *f) {
   for (;;) {
     const void *p = nullptr;
@@ -196,11 +414,21 @@ void dispatcher_main(ds_flush *f) {
 
 int ds_flush_start_fds(ds_event *ev, int fd_buffered, int fd_direct, uint32_t threads, uint32_t flags,
                        ds_flush **out) {
-  if (!ev || !out || fd_buffered < 0 || (flags & ~(DS_FILE_DIRECT | DS_FILE_SYNC))) return DS_EINVAL;
+  if (!ev || !out || fd_buffered < 0 || (flags & ~(DS_FILE_DIRECT | DS_FILE_SYNC | DS_FILE_URING))) return DS_EINVAL;
   if (threads == 0) threads = 4;
   if (threads > 64) return DS_EINVAL;
   ds_flush *f = new (std::nothrow) ds_flush;
   if (!f) return DS_ENOMEM;
+  // io_uring if asked for and the kernel lets this process have it; else the pwrite threads
+  Uring *ring = nullptr;
+  if (flags & DS_FILE_URING) {
+    ring = new (std::nothrow) Uring;
+    if (ring && ring->open_ring(2 * threads) != 0) {
+      ring->close_ring();
+      delete ring;
+      ring = nullptr;
+    }
+  }
   f->ev = ev;
   f->flags = flags;
   f->own_fds = false;
@@ -209,8 +437,17 @@ int ds_flush_start_fds(ds_event *ev, int fd_buffered, int fd_direct, uint32_t th
   f->t0 = now_s();
   // writers first: a dispatcher without anyone to release slots would wait for ever
   try {
-    for (uint32_t i = 0; i < threads; ++i) f->writers.emplace_back(writer_main, f);
+    if (ring) {
+      f->writers.emplace_back(uring_writer_main, f, ring, threads);
+      ring = nullptr;  // the thread owns it now
+    } else {
+      for (uint32_t i = 0; i < threads; ++i) f->writers.emplace_back(writer_main, f);
+    }
   } catch (...) {
+  }
+  if (ring) {
+    ring->close_ring();
+    delete ring;
   }
   bool started = !f->writers.empty();
   if (started) {
@@ -236,12 +473,19 @@ int ds_flush_start_fds(ds_event *ev, int fd_buffered, int fd_direct, uint32_t th
 
 void ds_set_errno(int e) { g_last_errno = e; }
 
+bool ds_io_uring_available() {
+  Uring r;
+  const bool ok = r.open_ring(4) == 0;
+  r.close_ring();
+  return ok;
+}
+
 extern "C" {
 
 int ds_last_errno(void) { return g_last_errno; }
 
 int ds_flush_start(ds_event *ev, const char *path, uint32_t threads, uint32_t flags, ds_flush **out) {
-  if (!ev || !path || !out || (flags & ~(DS_FILE_DIRECT | DS_FILE_SYNC))) return DS_EINVAL;
+  if (!ev || !path || !out || (flags & ~(DS_FILE_DIRECT | DS_FILE_SYNC | DS_FILE_URING))) return DS_EINVAL;
   if (threads > 64) return DS_EINVAL;
   const int fd_buffered = open(path, O_WRONLY | O_CREAT | O_TRUNC | O_CLOEXEC, 0644);
   if (fd_buffered < 0) {

@@ -197,6 +197,7 @@ int ds_config_get(const char *key, uint64_t *value) {
   if (!std::strcmp(key, "chunk_bytes")) { *value = g_chunk_bytes.load(); return DS_OK; }
   if (!std::strcmp(key, "variant")) { *value = g_variant.load(); return DS_OK; }
   if (!std::strcmp(key, "grid_limit")) { *value = g_grid_limit.load(); return DS_OK; }
+  if (!std::strcmp(key, "io_uring_available")) { *value = ds_io_uring_available() ? 1 : 0; return DS_OK; }
   return DS_EINVAL;
 }
 

@@ -283,13 +283,16 @@ def test_restore_state_errors():
         dw.close()
 
 
-@pytest.mark.parametrize("flags_name", ["buffered", "direct_sync"])
+@pytest.mark.parametrize("flags_name", ["buffered", "direct_sync", "uring", "uring_direct"])
 def test_flush_to_file_and_restore_from_file(tmp_path, flags_name):
     """GPU -> ring -> file with background writer threads, then file -> ring ->
     GPU; the file must be the oracle's image, the restored arena the oracle's
     unpack of it."""
     ds, orc, gu, torch = _mods()
-    flags = 0 if flags_name == "buffered" else (ds.DS_FILE_DIRECT | ds.DS_FILE_SYNC)
+    flags = {"buffered": 0, "direct_sync": ds.DS_FILE_DIRECT | ds.DS_FILE_SYNC, "uring": ds.DS_FILE_URING,
+             "uring_direct": ds.DS_FILE_URING | ds.DS_FILE_DIRECT}[flags_name]
+    if flags & ds.DS_FILE_URING:
+        print(f"[info] io_uring available: {ds.ds_config_get('io_uring_available')}", flush=True)
     w = W.fragmentation(2500, max_bytes=1 << 17, seed=91)
     print(f"[case] file tier {flags_name}", flush=True)
     want, offs, tab = gu.oracle_image(w)
@@ -416,14 +419,15 @@ def test_flush_io_error_does_not_stall_the_snapshot():
     eng = ds.ds_engine_create(4 * MiB, 1 * MiB, 4 * MiB, 2, 0, 0, 2)      # ring smaller than the image
     s = torch.cuda.current_stream().cuda_stream
     try:
-        ev = ds.ds_snapshot_async(eng, dw.plan, s)
-        fl = ds.ds_flush_start(ev, "/dev/full", 2, 0)
-        ds.ds_event_wait_on_stream(ev, s)
-        with pytest.raises(ds.DsError) as e:
-            ds.ds_flush_wait(fl)
-        assert e.value.code == ds.DS_EIO and ds.ds_last_errno() == 28
-        ds.ds_event_wait(ev)                      # the snapshot itself completed
-        ds.ds_event_destroy(ev)
+        for fflags in (0, ds.DS_FILE_URING):
+            ev = ds.ds_snapshot_async(eng, dw.plan, s)
+            fl = ds.ds_flush_start(ev, "/dev/full", 2, fflags)
+            ds.ds_event_wait_on_stream(ev, s)
+            with pytest.raises(ds.DsError) as e:
+                ds.ds_flush_wait(fl)
+            assert e.value.code == ds.DS_EIO and ds.ds_last_errno() == 28
+            ds.ds_event_wait(ev)                  # the snapshot itself completed
+            ds.ds_event_destroy(ev)
         # and the engine is usable afterwards
         ev = ds.ds_snapshot_async(eng, dw.plan, s)
         n = 0

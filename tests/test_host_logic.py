@@ -144,6 +144,9 @@ def test_config_keys():
     ds.ds_config_set("grid_limit", 0)
     with pytest.raises(ds.DsError):
         ds.ds_config_set("grid_limit", 1 << 31)
+    assert ds.ds_config_get("io_uring_available") in (0, 1)
+    with pytest.raises(ds.DsError):
+        ds.ds_config_set("io_uring_available", 1)
     ds.ds_config_set("chunk_bytes", 32 << 10)
     d = _descs([Shard("a", "u8", (1 << 20,), (1,), 0, 0)])
     ds.ds_layout_assign(d, 1, 64)
