@@ -542,6 +542,47 @@ def main() -> int:
         experiments["gather_into_pinned_host"] = direct
         del host_img
 
+    if args.experiments:
+        # (3) Differential snapshot (the paper's future work): keep the previous image in HBM, gather the new
+        # one beside it, compare them chunk by chunk on the device, copy only the chunks that changed.
+        cb = args.chunk_bytes
+        n_blocks = -(-total // cb)
+        img_a = torch.empty(max(total, 16), dtype=torch.uint8, device=dev)
+        img_b = torch.empty(max(total, 16), dtype=torch.uint8, device=dev)
+        flags_dev = torch.zeros(n_blocks, dtype=torch.int32, device=dev)
+        host_img = torch.empty(max(total, 16), dtype=torch.uint8, pin_memory=True)
+        keep = arena.clone()
+        rows = []
+        for frac in (1.0, 0.25, 0.05, 0.0):
+            # the reference: image of the unchanged state, on the device and (whole) in host memory
+            arena.copy_(keep)
+            ds.ds_pack(plan, img_a.data_ptr(), 0, total, stream)
+            torch.cuda.synchronize()
+            host_img[:total].copy_(img_a[:total])
+            n_mut = int(arena.numel() * frac)
+            if n_mut:
+                arena[:n_mut].add_(1)                                  # this share of the rank's memory changes
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            ds.ds_pack(plan, img_b.data_ptr(), 0, total, stream)
+            ds.ds_image_diff(img_a.data_ptr(), img_b.data_ptr(), total, cb, flags_dev.data_ptr(), stream)
+            dirty = flags_dev.cpu().nonzero().flatten().tolist()       # the one host synchronisation
+            for k in dirty:
+                lo, hi = k * cb, min((k + 1) * cb, total)
+                host_img[lo:hi].copy_(img_b[lo:hi], non_blocking=True)
+            torch.cuda.synchronize()
+            ms = (time.perf_counter() - t0) * 1e3
+            ok = bool(torch.equal(host_img[:total], img_b[:total].cpu()))   # the host image is the new image
+            rows.append({"share_of_memory_changed": frac, "dirty_chunks": len(dirty), "chunks": n_blocks,
+                         "ms": round(ms, 3), "effective_GBps": round(payload / ms / 1e6, 1),
+                         "host_image_equals_new_image": ok})
+        arena.copy_(keep)
+        experiments["differential_snapshot"] = {
+            "rows": rows,
+            "note": "gather + device compare of two images (ds_image_diff, one flag per ring-slot-sized chunk) + "
+                    "copies of the changed chunks only; costs a second image in HBM and one host synchronisation"}
+        del img_a, img_b, host_img, keep
+
     ds.ds_engine_destroy(eng)
     torch.cuda.synchronize()
 

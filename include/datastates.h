@@ -478,6 +478,18 @@ int ds_last_hip_error(void);
 int ds_copy_probe(void *dst_dev, const void *src_dev, uint64_t nbytes, void *stream);
 
 /*
+ * For differential snapshots (the data reduction the paper's conclusions name as
+ * future work; an experiment here, the engine does not use it): compares two
+ * images of nbytes (multiple of 16; both pointers device memory, 16-byte
+ * aligned) block by block and sets changed_dev[k] (device memory, one uint32 per
+ * block, ceil(nbytes / block_bytes) of them) to 1 if block k differs anywhere,
+ * else to 0.  block_bytes: a power of two >= 16 KiB.  Asynchronous on `stream`.
+ * Errors: DS_EINVAL, DS_ERANGE, DS_EHIP.
+ */
+int ds_image_diff(const void *image_a_dev, const void *image_b_dev, uint64_t nbytes, uint64_t block_bytes,
+                  uint32_t *changed_dev, void *stream);
+
+/*
  * Tunables for experiments, read when a plan is created / a kernel launched:
  *   "chunk_bytes"   image bytes per work-group chunk: 8, 16 (default) or 32 KiB
  *   "variant"       0 = default (non-temporal accesses; the lean gather writes the image with

@@ -592,7 +592,64 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 4))) voi
       __builtin_amdgcn_raw_buffer_store_b128(v[i], out, (int)(16u * (threadIdx.x + 256u * i)), 0, kStorePolicySc0Sc1Nt);
 }
 
+// ---- which blocks of two images differ ----------------------------------------------------------
+__global__ __launch_bounds__(256) void ds_clear_flags_kernel(uint32_t *flags, uint64_t n) {
+  const uint64_t i = (uint64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i < n) flags[i] = 0;
+}
+
+// One work-group compares 1024 units (16 KiB) of the two images, in the lean path's shape and order; a
+// wavefront that saw a difference sets the flag of the block its units belong to (a 16 KiB piece never
+// straddles two blocks: the block size is a multiple of 16 KiB).
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 4))) void ds_diff_kernel(
+    const u32x4 *__restrict__ a, const u32x4 *__restrict__ b, uint64_t n_units, uint32_t units_per_block_log2,
+    uint32_t *__restrict__ flags) {
+  const uint32_t n_groups = (uint32_t)((n_units + 1023) / 1024), span = (n_groups + 7) / 8;
+  const uint32_t g = (blockIdx.x & 7u) * span + (blockIdx.x >> 3);
+  if (g >= n_groups) return;
+  const uint64_t first = (uint64_t)g * 1024;
+  const uint64_t left = n_units - first;
+  const uint32_t mine = left < 1024 ? (uint32_t)left : 1024u;
+  u32x4 x[4], y[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+    if (threadIdx.x + 256u * i < mine) {
+      x[i] = __builtin_nontemporal_load(a + first + threadIdx.x + 256 * i);
+      y[i] = __builtin_nontemporal_load(b + first + threadIdx.x + 256 * i);
+    }
+  uint32_t diff = 0;
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+    if (threadIdx.x + 256u * i < mine) {
+      const u32x4 d = x[i] ^ y[i];
+      diff |= d.x | d.y | d.z | d.w;
+    }
+  if (__ballot(diff != 0) != 0 && (threadIdx.x & (kWave - 1)) == 0) atomicOr(flags + (first >> units_per_block_log2), 1u);
+}
+
 }  // namespace
+
+extern "C" int ds_image_diff(const void *image_a_dev, const void *image_b_dev, uint64_t nbytes, uint64_t block_bytes,
+                             uint32_t *changed_dev, void *stream) {
+  if (nbytes == 0) return DS_OK;
+  if (!image_a_dev || !image_b_dev || !changed_dev || (((uintptr_t)image_a_dev | (uintptr_t)image_b_dev) & 15) ||
+      ((uintptr_t)changed_dev & 3))
+    return DS_EINVAL;
+  // a power of two of at least 16 KiB, so that a work-group's piece lies in one block
+  if (block_bytes < 16384 || (block_bytes & (block_bytes - 1)) || (nbytes & 15)) return DS_ERANGE;
+  const uint64_t n_units = nbytes >> 4;
+  const uint64_t groups = (n_units + 1023) / 1024;
+  if (groups > 0x7FFFFFF0ull) return DS_ERANGE;
+  const uint64_t n_blocks = (nbytes + block_bytes - 1) / block_bytes;
+  hipLaunchKernelGGL(ds_clear_flags_kernel, dim3((uint32_t)((n_blocks + 255) / 256)), dim3(256), 0, (hipStream_t)stream,
+                     changed_dev, n_blocks);
+  DS_HIP_TRY(hipGetLastError());
+  const uint64_t grid = ((groups + 7) / 8) * 8;
+  hipLaunchKernelGGL(ds_diff_kernel, dim3((uint32_t)grid), dim3(256), 0, (hipStream_t)stream, (const u32x4 *)image_a_dev,
+                     (const u32x4 *)image_b_dev, n_units, (uint32_t)__builtin_ctzll(block_bytes >> 4), changed_dev);
+  DS_HIP_TRY(hipGetLastError());
+  return DS_OK;
+}
 
 extern "C" int ds_copy_probe(void *dst_dev, const void *src_dev, uint64_t nbytes, void *stream) {
   if (nbytes == 0) return DS_OK;

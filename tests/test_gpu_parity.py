@@ -482,3 +482,38 @@ def test_random_tables_pack_and_unpack():
                 assert gu.first_mismatch(dw.arena_host(), w.arena) is None, trial
         finally:
             dw.close()
+
+
+@pytest.mark.parametrize("block_bytes", [16384, 65536, 1 << 20])
+def test_image_diff_flags_exactly_the_blocks_that_differ(block_bytes):
+    """ds_image_diff against its definition (a block is flagged iff some byte of it differs) on image pairs
+    with planted differences: none, one byte at the first / last position of a block, of the image, of
+    the ragged last block, and many."""
+    import torch
+    import paper_2601_16956_amd as ds
+    rng = np.random.default_rng(31)
+    for nbytes in (16, 16384, 16384 * 3 + 4096, (5 << 20) + 16 * 37):
+        base = rng.integers(0, 256, size=nbytes, dtype=np.uint8)
+        n_blocks = -(-nbytes // block_bytes)
+        cases = [[], [0], [nbytes - 1], [min(block_bytes, nbytes) - 1], list(rng.integers(0, nbytes, size=40))]
+        if n_blocks > 1:
+            cases += [[block_bytes], [block_bytes * (n_blocks - 1)], [block_bytes * (n_blocks - 1) - 1]]
+        a = torch.from_numpy(base).cuda()
+        for pos in cases:
+            other = base.copy()
+            for p in pos:
+                other[p] ^= 0x01 << int(rng.integers(0, 8))
+            b = torch.from_numpy(other).cuda()
+            flags = torch.full((n_blocks,), 7, dtype=torch.int32, device="cuda")     # stale values must be cleared
+            ds.ds_image_diff(a.data_ptr(), b.data_ptr(), nbytes, block_bytes, flags.data_ptr(),
+                             torch.cuda.current_stream().cuda_stream)
+            torch.cuda.synchronize()
+            want = [int((base[k * block_bytes:(k + 1) * block_bytes] != other[k * block_bytes:(k + 1) * block_bytes]).any())
+                    for k in range(n_blocks)]
+            assert flags.cpu().tolist() == want, (nbytes, pos[:4])
+    with pytest.raises(ds.DsError) as e:
+        ds.ds_image_diff(a.data_ptr(), b.data_ptr(), nbytes, 4096, flags.data_ptr(), 0)
+    assert e.value.code == ds.DS_ERANGE
+    with pytest.raises(ds.DsError) as e:
+        ds.ds_image_diff(a.data_ptr() + 4, b.data_ptr(), 1024, block_bytes, flags.data_ptr(), 0)
+    assert e.value.code == ds.DS_EINVAL
