@@ -167,3 +167,13 @@ def twin_pack(w, offsets: Sequence[int], total: int) -> np.ndarray:
         raw = np.frombuffer(np.ascontiguousarray(view).tobytes(), dtype=np.uint8)
         image[off:off + raw.size] = raw
     return image
+
+
+def image_diff(a: np.ndarray, b: np.ndarray, block_bytes: int) -> List[int]:
+    """Which blocks of two equally long byte images differ: entry k is 1 if
+    bytes [k*block_bytes, (k+1)*block_bytes) differ anywhere, else 0 (the last
+    block may be short).  The definition the device-side comparison for
+    differential snapshots is held to (the paper's conclusions name
+    differential checkpointing as future work; there is nothing to cite for how)."""
+    assert a.dtype == np.uint8 and b.dtype == np.uint8 and a.size == b.size and block_bytes > 0
+    return [int(bool(np.any(a[lo:lo + block_bytes] != b[lo:lo + block_bytes]))) for lo in range(0, a.size, block_bytes)]

@@ -337,3 +337,24 @@ def test_llama_rank_structure_small():
     assert bf16 == 2 * n and f32 == 3 * 4 * n // 8
     # at DP=1 the ratio would be 2 : 12 bytes per parameter (Table I: 13 GB : 82 GB)
     assert math.isclose((f32 * 8) / bf16, 6.0)
+
+
+def test_image_diff_by_brute_force():
+    """The block comparison, byte by byte in plain Python, on small random pairs."""
+    rng = np.random.default_rng(8)
+    for trial in range(50):
+        n = int(rng.integers(1, 200))
+        block = int(rng.integers(1, 40))
+        a = rng.integers(0, 4, size=n, dtype=np.uint8)
+        b = a.copy()
+        for p in rng.integers(0, n, size=int(rng.integers(0, 4))):
+            b[p] ^= 1
+        want = []
+        for lo in range(0, n, block):
+            flag = 0
+            for i in range(lo, min(lo + block, n)):
+                if a[i] != b[i]:
+                    flag = 1
+            want.append(flag)
+        assert orc.image_diff(a, b, block) == want
+        assert len(want) == -(-n // block)
