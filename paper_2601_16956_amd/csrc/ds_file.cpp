@@ -363,6 +363,10 @@ void uring_writer_main(ds_flush *f, Uring *ring, unsigned depth) {
         queue_op((unsigned)user);
         continue;
       }
+      if (res == -EAGAIN || res == -EINTR) {  // not an error: the same request once more
+        queue_op((unsigned)user);
+        continue;
+      }
       if (res < 0 || res == 0) {
         flush_fail(f, DS_EIO, res < 0 ? -res : EIO);
       } else if ((uint64_t)res < op.left) {  // a short write: the rest goes out as a new request
