@@ -73,25 +73,29 @@ struct LeanArgs {
 };
 
 // ---- 16-byte accesses -------------------------------------------------------
+// Every address here is device (or pinned host) memory reached through the global address space; saying so
+// makes the compiler emit global_load / global_store instead of the flat forms, which also have to ask
+// whether the address lies in LDS or scratch.
+#define DS_GLOBAL __attribute__((address_space(1)))
 template <bool NT>
 __device__ __forceinline__ u32x4 ld16_aligned(const uint8_t *p) {
-  if (NT) return __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p));
-  return *reinterpret_cast<const u32x4 *>(p);
+  if (NT) return __builtin_nontemporal_load((const DS_GLOBAL u32x4 *)p);
+  return *(const DS_GLOBAL u32x4 *)p;
 }
 template <bool NT>
 __device__ __forceinline__ void st16_aligned(uint8_t *p, u32x4 v) {
-  if (NT) __builtin_nontemporal_store(v, reinterpret_cast<u32x4 *>(p));
-  else *reinterpret_cast<u32x4 *>(p) = v;
+  if (NT) __builtin_nontemporal_store(v, (DS_GLOBAL u32x4 *)p);
+  else *(DS_GLOBAL u32x4 *)p = v;
 }
 template <bool NT>
 __device__ __forceinline__ u32x4 ld16_any(const uint8_t *p) {
-  if (NT) return __builtin_nontemporal_load(reinterpret_cast<const u32x4_unaligned *>(p));
-  return *reinterpret_cast<const u32x4_unaligned *>(p);
+  if (NT) return __builtin_nontemporal_load((const DS_GLOBAL u32x4_unaligned *)p);
+  return *(const DS_GLOBAL u32x4_unaligned *)p;
 }
 template <bool NT>
 __device__ __forceinline__ void st16_any(uint8_t *p, u32x4 v) {
-  if (NT) __builtin_nontemporal_store(v, reinterpret_cast<u32x4_unaligned *>(p));
-  else *reinterpret_cast<u32x4_unaligned *>(p) = v;
+  if (NT) __builtin_nontemporal_store(v, (DS_GLOBAL u32x4_unaligned *)p);
+  else *(DS_GLOBAL u32x4_unaligned *)p = v;
 }
 
 // ---- index arithmetic -------------------------------------------------------
