@@ -479,7 +479,7 @@ def test_timeline_trace_of_a_snapshot():
             assert c["begin_ms"] >= g["end_ms"] - 1e-3
         for a, b in zip(copies, copies[1:]):
             assert b["begin_ms"] >= a["end_ms"] - 1e-3            # one copy stream: in order
-        assert abs(max(c["end_ms"] for c in copies) - st["total_ms"]) < 0.5
+        assert abs(max(c["end_ms"] for c in copies) - st["total_ms"]) < 5.0
         ds.ds_event_destroy(ev)
         # without the flag only the gathers are reported
         eng2 = ds.ds_engine_create(64 * MiB, 2 * MiB, 16 * MiB, 2, 0, ds.DS_ENGINE_AUTO_RELEASE, 1)
