@@ -140,6 +140,7 @@ void writer_main(ds_flush *f) {
       j = f->queue.front();
       f->queue.pop_front();
     }
+    bool released = false;
     if (f->status.load() == DS_OK) {
       const bool direct = f->fd_direct >= 0 && direct_ok(j.ptr, j.off, j.len);
       int e = -1;  // -1: not written yet, try the next way
@@ -154,10 +155,14 @@ void writer_main(ds_flush *f) {
         uint8_t *b = bounce.fit(j.len);
         if (b) {
           std::memcpy(b, j.ptr, j.len);
+          // the copy is what the file gets: the ring slot is free for the next device-to-host copy already
+          int rc = ds_snapshot_release_chunk(f->ev, j.ptr);
+          if (rc != DS_OK) flush_fail(f, rc, 0);
+          released = true;
           e = write_all(f->fd_direct, b, j.len, j.off);
           if (e == EINVAL) {                             // the file system has no direct I/O after all
             f->bounce_usable.store(false);
-            e = -1;
+            e = write_all(f->fd_buffered, b, j.len, j.off);
           }
         }
       }
@@ -166,8 +171,10 @@ void writer_main(ds_flush *f) {
       else f->bytes.fetch_add(j.len);
     }
     // the slot goes back whatever happened, so that the snapshot itself can finish
-    int rc = ds_snapshot_release_chunk(f->ev, j.ptr);
-    if (rc != DS_OK) flush_fail(f, rc, 0);
+    if (!released) {
+      int rc = ds_snapshot_release_chunk(f->ev, j.ptr);
+      if (rc != DS_OK) flush_fail(f, rc, 0);
+    }
   }
 }
 
