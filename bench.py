@@ -618,6 +618,7 @@ def main() -> int:
                 nbytes, _ = ds.ds_ckpt_finish(ck)
                 flush_s = time.perf_counter() - t0
                 ds.ds_event_wait(ev)
+                fst = ds.ds_event_stats(ev)
                 ds.ds_event_destroy(ev)
                 t0 = time.perf_counter()
                 rd = ds.ds_ckpt_open(path)
@@ -630,6 +631,8 @@ def main() -> int:
                 return {"dir": d, "file_bytes": nbytes, "object_log_bytes": lay["log_end"] - lay["tensor_bytes"],
                         "object_chunks": lay["n_chunks"],
                         "snapshot_to_file_GBps": round(nbytes / flush_s / 1e9, 2),
+                        "capture_ms": round(fst["capture_ms"], 3),   # tensors free again, whatever the storage does
+                        "image_in_host_ring_ms": round(fst["total_ms"], 3),
                         "file_to_gpu_GBps": round(payload / load_s / 1e9, 2)}
             except ds.DsError as e:
                 return {"dir": d, "error": str(e)}
