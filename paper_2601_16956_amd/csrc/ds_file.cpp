@@ -568,7 +568,7 @@ int ds_restore_from_file(ds_engine *engine, const ds_plan *plan, const char *pat
     bool stop = false;
   } sh;
   std::atomic<bool> direct_usable{true}, bounce_usable{true};
-  const uint32_t window = threads;
+  const uint32_t window = 2 * threads;  // slots beyond the readers, so that one slow read does not idle the others
   sh.done.assign(window, 0);
   std::vector<IoJob> win(window);
   std::vector<std::thread> readers;
