@@ -159,8 +159,9 @@ int ds_plan_shard_shape(const ds_plan *plan, size_t i, uint32_t *ndim, int64_t *
  * start of a full-size buffer with img_lo = 0).  Padding bytes are written as
  * zero, so the destination need not be cleared.  img_lo <= img_hi <= total,
  * both multiples of 16; dst_dev 16-byte aligned.  Asynchronous: enqueued on
- * `stream`; the tensors must not change until it has run.
- * Errors: DS_EINVAL, DS_ERANGE, DS_EHIP.
+ * `stream`; the tensors must not change until it has run.  The device the
+ * plan was created on must be the calling thread's current device (DS_ESTATE).
+ * Errors: DS_EINVAL, DS_ERANGE, DS_ESTATE, DS_EHIP.
  */
 int ds_pack(const ds_plan *plan, void *dst_dev, uint64_t img_lo, uint64_t img_hi, void *stream);
 
@@ -215,6 +216,7 @@ int ds_engine_destroy(ds_engine *engine);
  * (ds_event_wait_on_stream / ds_event_wait_captured) the caller must not
  * enqueue work that writes the tensors.  Snapshots on one engine run in the
  * order requested.  *out is owned by the caller (ds_event_destroy).
+ * DS_EBUSY while a restore event of the engine is alive.
  */
 int ds_snapshot_async(ds_engine *engine, const ds_plan *plan, void *compute_stream, ds_event **out);
 

@@ -60,6 +60,7 @@ struct ds_engine {
   std::deque<ds_event *> queue;
   bool stop = false;
   int live_events = 0;
+  bool restoring = false;  // a restore event is alive: ring and staging are its own
   std::thread worker;
 };
 
@@ -378,6 +379,10 @@ int ds_engine_destroy(ds_engine *g) {
 int ds_snapshot_async(ds_engine *g, const ds_plan *plan, void *compute_stream, ds_event **out) {
   if (!g || !plan || !out || !plan->dev_blob) return DS_EINVAL;
   const auto t0 = std::chrono::steady_clock::now();
+  {
+    std::lock_guard<std::mutex> lk(g->mu);
+    if (g->restoring) return DS_EBUSY;
+  }
   ds_event *ev = new (std::nothrow) ds_event;
   if (!ev) return DS_ENOMEM;
   ev->eng = g;
@@ -590,6 +595,7 @@ int ds_event_destroy(ds_event *ev) {
       std::lock_guard<std::mutex> lk(g->mu);
       std::fill(g->ring_busy.begin(), g->ring_busy.end(), 0);  // the ring is empty again for snapshots
       --g->live_events;
+      g->restoring = false;
     }
     delete ev;
     return rc;
@@ -646,6 +652,7 @@ int ds_restore_begin(ds_engine *g, const ds_plan *plan, void *compute_stream, ds
     std::lock_guard<std::mutex> lk(g->mu);
     if (g->live_events > 0) return DS_EBUSY;  // ring and staging are shared with snapshots
     ++g->live_events;
+    g->restoring = true;
   }
   ds_event *ev = new (std::nothrow) ds_event;
   int rc = ev ? DS_OK : DS_ENOMEM;
@@ -694,6 +701,7 @@ int ds_restore_begin(ds_engine *g, const ds_plan *plan, void *compute_stream, ds
     }
     std::lock_guard<std::mutex> lk(g->mu);
     --g->live_events;
+    g->restoring = false;
     return rc;
   }
   std::fill(g->ring_busy.begin(), g->ring_busy.end(), 0);

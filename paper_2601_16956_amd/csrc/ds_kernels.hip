@@ -674,6 +674,10 @@ int ds_launch_move(const ds_plan *plan, bool pack, uint8_t *img, uint64_t img_lo
   const uint64_t C = (uint64_t)1 << lg;
   const uint64_t n_total = plan->n_chunks();
   if (img_hi > plan->total_bytes || img_lo >= img_hi) return DS_ERANGE;
+  // the tables live on the device the plan was made on: a launch from another one would read them remotely
+  int dev = -1;
+  DS_HIP_TRY(hipGetDevice(&dev));
+  if (dev != plan->device) return DS_ESTATE;
   // whole chunks inside the range: one work item each, lean or general by their record ...
   uint64_t w_lo = (img_lo + C - 1) >> lg;
   uint64_t w_hi = img_hi >> lg;

@@ -268,6 +268,9 @@ def test_restore_state_errors():
         with pytest.raises(ds.DsError) as e:
             ds.ds_snapshot_next_chunk(ev)
         assert e.value.code == ds.DS_ESTATE
+        with pytest.raises(ds.DsError) as e:                      # ring and staging belong to the restore
+            ds.ds_snapshot_async(eng, dw.plan, s)
+        assert e.value.code == ds.DS_EBUSY
         ds.ds_restore_submit(ev, a[0])
         ds.ds_event_destroy(ev)                                   # abandoning a restore is allowed
         ev = ds.ds_snapshot_async(eng, dw.plan, s)                # the engine is usable again
