@@ -62,6 +62,7 @@ def main() -> int:
     ap.add_argument("--no-file", action="store_true", help="skip the file-tier leg")
     ap.add_argument("--file-dir", default="/tmp", help="where the file-tier leg writes its image")
     ap.add_argument("--file-threads", type=int, default=8)
+    ap.add_argument("--files", type=int, default=20, help="--experiments: files the rank's state is split over")
     ap.add_argument("--file-engine", default="threads", choices=["threads", "uring"],
                     help="writers of the file tier: pwrite threads, or one thread with that many writes in flight "
                          "through io_uring")
@@ -583,6 +584,45 @@ def main() -> int:
                     "copies of the changed chunks only; costs a second image in HBM and one host synchronisation"}
         del img_a, img_b, host_img, keep
 
+    file_plans = []
+    if args.experiments:
+        # (4) One rank's checkpoint split over several files (the paper's 7B rank writes 20, Sec. VI-D): one plan
+        # per file over consecutive shards of about equal bytes, all through the one engine, back to back.
+        F = min(args.files, n)
+        cuts, acc, sizes = [0], 0, [ds.ds_plan_shard(plan, i)[3] for i in range(n)]
+        for i in range(n):
+            acc += sizes[i]
+            if acc >= payload * len(cuts) / F and len(cuts) < F and i + 1 < n:
+                cuts.append(i + 1)
+        cuts.append(n)
+        for a, b in zip(cuts[:-1], cuts[1:]):
+            dg = ds.make_descs(w.shards[a:b], arena.data_ptr())
+            ds.ds_layout_assign(dg, b - a, w.align)
+            file_plans.append(ds.ds_plan_create(dg, b - a, w.align, ds.DS_PLAN_STRICT))
+
+        def several():
+            t0 = time.perf_counter()
+            evs = [ds.ds_snapshot_async(eng, pl, stream) for pl in file_plans]
+            ds.ds_event_wait_on_stream(evs[-1], stream)      # snapshots run in order: the last gate covers all
+            ds.ds_event_wait_captured(evs[-1])
+            t_cap = time.perf_counter() - t0                 # first request -> every tensor may be mutated (host clock)
+            for ev in evs:
+                ds.ds_event_wait(ev)
+            return evs, t_cap, time.perf_counter() - t0
+        for ev in several()[0]:
+            ds.ds_event_destroy(ev)
+        torch.cuda.synchronize()
+        evs, cap_s, several_s = several()
+        cap = cap_s * 1e3
+        for ev in evs:
+            ds.ds_event_destroy(ev)
+        experiments["rank_state_as_several_plans"] = {
+            "plans": len(file_plans), "smallest_image_bytes": min(ds.ds_plan_info(pl)["total_bytes"] for pl in file_plans),
+            "largest_image_bytes": max(ds.ds_plan_info(pl)["total_bytes"] for pl in file_plans),
+            "GBps_into_host_ring": round(payload / several_s / 1e9, 2),
+            "first_request_to_all_captured_ms": round(cap, 3),
+            "note": "the same bytes as one image, requested as one snapshot per file; compare with `value`"}
+
     ds.ds_engine_destroy(eng)
     torch.cuda.synchronize()
 
@@ -647,9 +687,39 @@ def main() -> int:
                          "note": "request -> trailer written (page cache, no fsync); open + check -> tensors restored; "
                                  "/dev/shm is memory-backed: the software path without the disk",
                          "runs": [one_dir(d) for d in dirs]}
+            if file_plans:
+                # the same split, each plan into a checkpoint file of its own, all flushes in flight at once
+                paths = [os.path.join(dirs[0], f"ds_bench_{os.getpid()}_{k}.ckpt") for k in range(len(file_plans))]
+                try:
+                    torch.cuda.synchronize()
+                    t0 = time.perf_counter()
+                    evs, cks = [], []
+                    for pl, path in zip(file_plans, paths):
+                        ev = ds.ds_snapshot_async(eng2, pl, stream)
+                        ck = ds.ds_ckpt_create(path, pl, ds.DS_FILE_DIRECT)
+                        ds.ds_ckpt_flush_snapshot(ck, ev, max(1, args.file_threads // 2))
+                        evs.append(ev)
+                        cks.append(ck)
+                    ds.ds_event_wait_on_stream(evs[-1], stream)
+                    nbytes = sum(ds.ds_ckpt_finish(ck)[0] for ck in cks)
+                    files_s = time.perf_counter() - t0
+                    for ev in evs:
+                        ds.ds_event_wait(ev)
+                        ds.ds_event_destroy(ev)
+                    file_tier["several_files"] = {"dir": dirs[0], "files": len(paths), "file_bytes": nbytes,
+                                                  "threads_per_file": max(1, args.file_threads // 2),
+                                                  "snapshot_to_files_GBps": round(nbytes / files_s / 1e9, 2)}
+                except ds.DsError as e:
+                    file_tier["several_files"] = {"error": str(e)}
+                finally:
+                    for path in paths:
+                        if os.path.exists(path):
+                            os.remove(path)
         finally:
             ds.ds_engine_destroy(eng2)
     torch.cuda.synchronize()
+    for pl in file_plans:
+        ds.ds_plan_destroy(pl)
     ds.ds_plan_destroy(plan)
 
     out = {

@@ -186,9 +186,13 @@ typedef struct ds_engine_opts {
                                 single tunable (Sec. V-B).  0 = 2 GiB                              */
   uint64_t d2h_chunk_bytes;  /* size of one ring slot = one device-to-host copy; multiple of 4096.
                                 0 = 32 MiB                                                          */
-  uint64_t stage_slot_bytes; /* device staging slot = image bytes per gather launch; multiple of
-                                d2h_chunk_bytes.  0 = 1 GiB                                         */
-  uint32_t stage_slots;      /* number of device staging slots (>= 1).  0 = 2                       */
+  uint64_t stage_slot_bytes; /* image bytes per gather launch (the last launch of an image may be
+                                shorter); multiple of d2h_chunk_bytes.  0 = 1 GiB                   */
+  uint32_t stage_slots;      /* device staging is one ring of stage_slots * stage_slot_bytes bytes
+                                (>= 1; 0 = 2): a launch takes the next piece of it, of its own length,
+                                so queued snapshots of small images share it.  With staging as large
+                                as everything requested at a time, every gate opens after the gathers
+                                alone, whatever the link, the host ring or the storage are doing    */
   uint32_t pack_grid_limit;  /* max work-groups resident per gather launch; 0 = one per chunk       */
   uint32_t flags;            /* DS_ENGINE_*                                                         */
   uint32_t copy_streams;     /* copy streams the chunks alternate over: 1 or 2.  0 = 2 (the gap
@@ -226,9 +230,9 @@ int ds_snapshot_async(ds_engine *engine, const ds_plan *plan, void *compute_stre
  * read into staging.  Returns when the wait has been enqueued; blocks the
  * host only while the engine has not yet issued the last gather (e.g. the
  * host ring is full and the consumer is behind: the paper's back-pressure).
- * Hence, when staging is smaller than the image, the thread that calls the
- * gate must not be the one that consumes the chunks: it would wait for room
- * that only it can make.
+ * Hence, when staging is smaller than the images requested and not yet
+ * copied out, the thread that calls the gate must not be the one that
+ * consumes the chunks: it would wait for room that only it can make.
  */
 int ds_event_wait_on_stream(ds_event *ev, void *stream);
 

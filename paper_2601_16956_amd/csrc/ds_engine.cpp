@@ -5,10 +5,17 @@
 //
 // Data path of one snapshot, image bytes [0, T):
 //
-//   compute stream --E_requested--> gather stream: one gather launch per staging
-//   slot (optionally a shorter first launch, so that the link starts working
-//   sooner)  --E_packed--> copy stream(s): one hipMemcpyAsync per ring slot,
-//   device staging -> pinned ring  --E_done[slot]--> consumer.
+//   compute stream --E_requested--> gather stream: one gather launch per
+//   stage_slot_bytes of image (optionally a shorter first launch, so that the
+//   link starts working sooner)  --E_packed--> copy stream(s): one hipMemcpyAsync
+//   per ring slot, device staging -> pinned ring  --E_done[slot]--> consumer.
+//
+// Device staging is one ring of bytes: a gather launch takes the next piece of it,
+// after the copies that last read those bytes.  Gathers are issued ahead of the
+// copies as far as staging has room -- across queued snapshots too -- so when
+// staging holds what has been requested (a rank's whole state, written as several
+// files = several snapshots, say) every gate opens after the gathers alone, however
+// far behind the link, the host ring or the storage are.
 //
 // The caller's stream is touched twice only: the record at the request and the
 // wait at the gate.  The gate waits for the LAST GATHER, not for the last
@@ -20,6 +27,7 @@
 #include <chrono>
 #include <condition_variable>
 #include <deque>
+#include <list>
 #include <mutex>
 #include <new>
 #include <thread>
@@ -31,6 +39,14 @@ constexpr int kMaxCopyStreams = 2;
 }
 
 struct ds_event;
+
+// A piece of staging that a gather launch has filled (or is about to).
+struct StageRegion {
+  uint64_t off = 0, len = 0;
+  bool copies_enqueued = false;  // the copies that read it have been enqueued and `done` recorded behind them
+  int n_done = 0;
+  hipEvent_t done[kMaxCopyStreams] = {nullptr, nullptr};
+};
 
 struct ds_engine {
   int device = 0;
@@ -48,12 +64,13 @@ struct ds_engine {
   uint8_t *ring = nullptr;   // pinned host
   // engine-owned events, reused by every snapshot
   std::vector<hipEvent_t> ring_done;                    // copy into ring slot r finished
-  std::vector<hipEvent_t> stage_free[kMaxCopyStreams];  // copies out of staging slot s finished (per copy stream)
-  std::vector<bool> stage_used;
   std::vector<uint8_t> ring_busy;  // consumer mode: slot holds data not yet released
   uint32_t ring_next = 0;
   uint64_t copies_issued = 0;
-  uint64_t groups_issued = 0;  // staging slots rotate across snapshots
+  // staging as a ring of bytes (touched by the engine thread; by a restore only while the engine is idle)
+  uint64_t stage_bytes = 0, stage_head = 0;
+  std::list<StageRegion> regions;      // pieces of staging whose last gather may still be read by copies
+  std::vector<hipEvent_t> event_pool;  // spare events of regions that have been taken over
 
   std::mutex mu;
   std::condition_variable cv;
@@ -102,126 +119,201 @@ int hip_fail(hipError_t e) {
     if (_e != hipSuccess) return hip_fail(_e); \
   } while (0)
 
-// Issues every launch and copy of one snapshot.  Runs on the engine's thread.
-// Gathers are issued as far ahead as staging allows (a gather into a slot may be
-// enqueued once the copies that last read that slot have been enqueued), so with
-// staging as large as the image every gather -- and with it the gate -- is out
-// before the first wait for a ring slot.
-int issue_snapshot(ds_engine *g, ds_event *ev) {
-  const ds_plan *plan = ev->plan;
-  const uint64_t T = plan->total_bytes;
-  W_TRY(hipStreamWaitEvent(g->pack_stream, ev->requested, 0));
+// One snapshot in the hands of the engine thread.
+struct Job {
+  ds_event *ev = nullptr;
+  struct Group {
+    uint64_t lo = 0, hi = 0;  // image range of one gather launch
+    std::list<StageRegion>::iterator region;
+  };
+  std::vector<Group> groups;
+  bool prepared = false;
+  size_t np = 0;             // gathers issued
+  size_t nc = 0;             // groups whose copies have all been issued
+  bool group_begun = false;  // the copy streams already wait for the gather of group nc
+  uint64_t at = 0;           // image offset of the next copy of group nc
+  uint32_t k = 0;            // its chunk number
+  int ncs = 1;               // copy streams this snapshot uses
+};
+
+int pool_event(ds_engine *g, hipEvent_t *out) {
+  if (!g->event_pool.empty()) {
+    *out = g->event_pool.back();
+    g->event_pool.pop_back();
+    return DS_OK;
+  }
+  W_TRY(hipEventCreateWithFlags(out, hipEventDisableTiming));
+  return DS_OK;
+}
+
+void recycle_region(ds_engine *g, StageRegion &r) {
+  for (int c = 0; c < kMaxCopyStreams; ++c)
+    if (r.done[c]) {
+      g->event_pool.push_back(r.done[c]);
+      r.done[c] = nullptr;
+    }
+}
+
+void forget_regions(ds_engine *g) {
+  for (StageRegion &r : g->regions) recycle_region(g, r);
+  g->regions.clear();
+  g->stage_head = 0;
+}
+
+int mark_captured(ds_engine *g, ds_event *ev) {
+  W_TRY(hipEventRecord(ev->captured, g->pack_stream));
+  {
+    std::lock_guard<std::mutex> lk(g->mu);
+    ev->capture_issued = true;
+  }
+  g->cv.notify_all();
+  return DS_OK;
+}
+
+int prepare_job(ds_engine *g, Job &j) {
+  ds_event *ev = j.ev;
+  const uint64_t T = ev->plan->total_bytes;
+  j.prepared = true;
   W_TRY(hipEventCreate(&ev->captured));
   W_TRY(hipEventCreate(&ev->final_ev));
   W_TRY(hipEventCreate(&ev->copy_begin));
-
-  struct Group { uint64_t lo, hi; uint32_t slot; };
-  std::vector<Group> groups;
   for (uint64_t at = 0; at < T;) {
-    // the first launch may be shorter than a staging slot (first_launch_bytes)
-    const uint64_t want = groups.empty() ? g->first_launch_bytes : g->stage_slot_bytes;
-    const uint64_t hi = at + want < T ? at + want : T;
-    groups.push_back({at, hi, (uint32_t)(g->groups_issued++ % g->stage_slots)});
-    at = hi;
+    // the first launch may be shorter than the others (first_launch_bytes)
+    const uint64_t want = j.groups.empty() ? g->first_launch_bytes : g->stage_slot_bytes;
+    Job::Group gr;
+    gr.lo = at;
+    gr.hi = at + want < T ? at + want : T;
+    j.groups.push_back(gr);
+    at = gr.hi;
   }
-  const size_t G = groups.size();
   // A snapshot of only a few chunks keeps to one copy stream: there is no gap between copies for the
   // second stream to hide, so the events that would tie it in are saved.
-  const int ncs = ev->chunks.size() < 4 ? 1 : g->n_copy_streams;
+  j.ncs = ev->chunks.size() < 4 ? 1 : g->n_copy_streams;
+  if (j.groups.empty()) {
+    W_TRY(hipStreamWaitEvent(g->pack_stream, ev->requested, 0));
+    return mark_captured(g, ev);
+  }
+  return DS_OK;
+}
 
-  auto mark_captured = [&]() -> int {
-    W_TRY(hipEventRecord(ev->captured, g->pack_stream));
+// The next gather of the snapshot, if staging has room for it: *issued = false means that the bytes it
+// would take are still waiting for copies that have not been enqueued yet.
+int try_issue_pack(ds_engine *g, Job &j, bool *issued) {
+  ds_event *ev = j.ev;
+  Job::Group &gr = j.groups[j.np];
+  const uint64_t len = gr.hi - gr.lo;
+  uint64_t off = g->stage_head;
+  if (off + len > g->stage_bytes) off = 0;  // a launch's piece is contiguous: the rest of the ring's end stays unused
+  auto overlaps = [&](const StageRegion &r) { return r.off < off + len && off < r.off + r.len; };
+  for (const StageRegion &r : g->regions)
+    if (overlaps(r) && !r.copies_enqueued) {
+      *issued = false;
+      return DS_OK;
+    }
+  if (j.np == 0) W_TRY(hipStreamWaitEvent(g->pack_stream, ev->requested, 0));
+  for (auto it = g->regions.begin(); it != g->regions.end();) {
+    if (overlaps(*it)) {
+      for (int c = 0; c < it->n_done; ++c) W_TRY(hipStreamWaitEvent(g->pack_stream, it->done[c], 0));
+      recycle_region(g, *it);
+      it = g->regions.erase(it);
+    } else {
+      ++it;
+    }
+  }
+  g->regions.emplace_back();
+  gr.region = std::prev(g->regions.end());
+  gr.region->off = off;
+  gr.region->len = len;
+  g->stage_head = off + len;
+  hipEvent_t b, e;
+  W_TRY(hipEventCreate(&b));
+  ev->pack_begin.push_back(b);
+  W_TRY(hipEventCreate(&e));
+  ev->pack_end.push_back(e);
+  ev->pack_lo.push_back(gr.lo);
+  ev->pack_hi.push_back(gr.hi);
+  W_TRY(hipEventRecord(b, g->pack_stream));
+  int rc = ds_launch_move(ev->plan, true, g->stage + off, gr.lo, gr.hi, g->grid_limit, g->pack_stream);
+  if (rc != DS_OK) return rc;
+  W_TRY(hipEventRecord(e, g->pack_stream));
+  *issued = true;
+  if (++j.np == j.groups.size()) return mark_captured(g, ev);
+  return DS_OK;
+}
+
+// Copies of the snapshot's next group whose gather has been issued.  Returns after one group, or earlier
+// with *blocked = true when the host ring is full and a new request has arrived: its gathers need not wait
+// for the ring.
+int issue_group_copies(ds_engine *g, Job &j, bool *blocked) {
+  ds_event *ev = j.ev;
+  if (j.nc >= j.np) return DS_OK;
+  Job::Group &gr = j.groups[j.nc];
+  uint8_t *slot = g->stage + gr.region->off;
+  const int ncs = j.ncs;
+  if (!j.group_begun) {
+    for (int c = 0; c < ncs; ++c) W_TRY(hipStreamWaitEvent(g->copy_stream[c], ev->pack_end[j.nc], 0));
+    if (j.nc == 0) W_TRY(hipEventRecord(ev->copy_begin, g->copy_stream[0]));
+    j.at = gr.lo;
+    j.group_begun = true;
+  }
+  for (; j.at < gr.hi; j.at += g->chunk_bytes, ++j.k) {
+    const uint64_t lo = j.at;
+    const uint64_t len = lo + g->chunk_bytes < gr.hi ? g->chunk_bytes : gr.hi - lo;
+    uint32_t r;
+    {
+      std::unique_lock<std::mutex> lk(g->mu);
+      r = g->ring_next;
+      if (!(g->flags & DS_ENGINE_AUTO_RELEASE)) {
+        // back-pressure: the ring is full until the consumer releases a slot
+        g->cv.wait(lk, [&] { return !g->ring_busy[r] || !g->queue.empty(); });
+        if (g->ring_busy[r]) {
+          *blocked = true;
+          return DS_OK;
+        }
+        g->ring_busy[r] = 1;
+      }
+      g->ring_next = (r + 1) % g->ring_slots;
+    }
+    const int c = (int)(g->copies_issued++ % (uint64_t)ncs);
+    hipStream_t cs = g->copy_stream[c];
+    // the slot's previous copy may have run on the other copy stream
+    if (g->n_copy_streams > 1) W_TRY(hipStreamWaitEvent(cs, g->ring_done[r], 0));
+    if (g->flags & DS_ENGINE_TRACE) {
+      hipEvent_t tb, te;
+      W_TRY(hipEventCreate(&tb));
+      ev->copy_b.push_back(tb);
+      W_TRY(hipEventCreate(&te));
+      ev->copy_e.push_back(te);
+      W_TRY(hipEventRecord(tb, cs));
+    }
+    W_TRY(hipMemcpyAsync(g->ring + (uint64_t)r * g->chunk_bytes, slot + (lo - gr.lo), len, hipMemcpyDeviceToHost, cs));
+    if (g->flags & DS_ENGINE_TRACE) W_TRY(hipEventRecord(ev->copy_e.back(), cs));
+    W_TRY(hipEventRecord(g->ring_done[r], cs));
     {
       std::lock_guard<std::mutex> lk(g->mu);
-      ev->capture_issued = true;
+      ev->chunks[j.k].ring_slot = r;
+      ev->chunks[j.k].state = 1;
     }
     g->cv.notify_all();
-    return DS_OK;
-  };
-
-  auto issue_pack = [&](size_t gi) -> int {
-    const Group &gr = groups[gi];
-    uint8_t *slot = g->stage + (uint64_t)gr.slot * g->stage_slot_bytes;
-    if (g->stage_used[gr.slot])
-      for (int c = 0; c < g->n_copy_streams; ++c)
-        W_TRY(hipStreamWaitEvent(g->pack_stream, g->stage_free[c][gr.slot], 0));
-    hipEvent_t b, e;
-    W_TRY(hipEventCreate(&b));
-    ev->pack_begin.push_back(b);
-    W_TRY(hipEventCreate(&e));
-    ev->pack_end.push_back(e);
-    ev->pack_lo.push_back(gr.lo);
-    ev->pack_hi.push_back(gr.hi);
-    W_TRY(hipEventRecord(b, g->pack_stream));
-    int rc = ds_launch_move(plan, true, slot, gr.lo, gr.hi, g->grid_limit, g->pack_stream);
-    if (rc != DS_OK) return rc;
-    W_TRY(hipEventRecord(e, g->pack_stream));
-    if (gi + 1 == G) return mark_captured();
-    return DS_OK;
-  };
-
-  uint32_t k = 0;
-  auto issue_copies = [&](size_t gi) -> int {
-    const Group &gr = groups[gi];
-    uint8_t *slot = g->stage + (uint64_t)gr.slot * g->stage_slot_bytes;
-    for (int c = 0; c < ncs; ++c) W_TRY(hipStreamWaitEvent(g->copy_stream[c], ev->pack_end[gi], 0));
-    if (gi == 0) W_TRY(hipEventRecord(ev->copy_begin, g->copy_stream[0]));
-    for (uint64_t lo = gr.lo; lo < gr.hi; lo += g->chunk_bytes, ++k) {
-      const uint64_t len = lo + g->chunk_bytes < gr.hi ? g->chunk_bytes : gr.hi - lo;
-      uint32_t r;
-      {
-        std::unique_lock<std::mutex> lk(g->mu);
-        r = g->ring_next;
-        if (!(g->flags & DS_ENGINE_AUTO_RELEASE)) {
-          // back-pressure: the ring is full until the consumer releases a slot
-          g->cv.wait(lk, [&] { return !g->ring_busy[r]; });
-          g->ring_busy[r] = 1;
-        }
-        g->ring_next = (r + 1) % g->ring_slots;
-      }
-      const int c = (int)(g->copies_issued++ % (uint64_t)ncs);
-      hipStream_t cs = g->copy_stream[c];
-      // the slot's previous copy may have run on the other copy stream
-      if (g->n_copy_streams > 1) W_TRY(hipStreamWaitEvent(cs, g->ring_done[r], 0));
-      if (g->flags & DS_ENGINE_TRACE) {
-        hipEvent_t tb, te;
-        W_TRY(hipEventCreate(&tb));
-        ev->copy_b.push_back(tb);
-        W_TRY(hipEventCreate(&te));
-        ev->copy_e.push_back(te);
-        W_TRY(hipEventRecord(tb, cs));
-      }
-      W_TRY(hipMemcpyAsync(g->ring + (uint64_t)r * g->chunk_bytes, slot + (lo - gr.lo), len, hipMemcpyDeviceToHost, cs));
-      if (g->flags & DS_ENGINE_TRACE) W_TRY(hipEventRecord(ev->copy_e.back(), cs));
-      W_TRY(hipEventRecord(g->ring_done[r], cs));
-      {
-        std::lock_guard<std::mutex> lk(g->mu);
-        ev->chunks[k].ring_slot = r;
-        ev->chunks[k].state = 1;
-      }
-      g->cv.notify_all();
-    }
-    // (a stream this snapshot did not use keeps the event of its own last copies out of the slot)
-    for (int c = 0; c < ncs; ++c) W_TRY(hipEventRecord(g->stage_free[c][gr.slot], g->copy_stream[c]));
-    g->stage_used[gr.slot] = true;
-    return DS_OK;
-  };
-
-  if (G == 0) {
-    int rc = mark_captured();
-    if (rc != DS_OK) return rc;
   }
-  size_t np = 0;
-  for (size_t nc = 0; nc < G; ++nc) {
-    for (; np < G && np < nc + g->stage_slots; ++np) {
-      int rc = issue_pack(np);
-      if (rc != DS_OK) return rc;
-    }
-    int rc = issue_copies(nc);
+  // the piece of staging may be gathered into again once these copies have run
+  for (int c = 0; c < ncs; ++c) {
+    const int rc = pool_event(g, &gr.region->done[c]);
     if (rc != DS_OK) return rc;
+    gr.region->n_done = c + 1;
+    W_TRY(hipEventRecord(gr.region->done[c], g->copy_stream[c]));
   }
+  gr.region->copies_enqueued = true;
+  j.group_begun = false;
+  ++j.nc;
+  return DS_OK;
+}
+
+// the event that says "the whole image is in the host ring"
+int finish_job(ds_engine *g, Job &j) {
+  ds_event *ev = j.ev;
   W_TRY(hipStreamWaitEvent(g->copy_stream[0], ev->captured, 0));
-  if (ncs > 1) {
+  if (j.ncs > 1) {
     hipEvent_t tail;
     W_TRY(hipEventCreate(&tail));
     ev->pack_begin.push_back(tail);  // kept only so that it is destroyed with the event
@@ -229,29 +321,74 @@ int issue_snapshot(ds_engine *g, ds_event *ev) {
     W_TRY(hipEventRecord(tail, g->copy_stream[1]));
     W_TRY(hipStreamWaitEvent(g->copy_stream[0], tail, 0));
   }
-  if (T == 0) W_TRY(hipEventRecord(ev->copy_begin, g->copy_stream[0]));
+  if (j.groups.empty()) W_TRY(hipEventRecord(ev->copy_begin, g->copy_stream[0]));
   W_TRY(hipEventRecord(ev->final_ev, g->copy_stream[0]));
   return DS_OK;
 }
 
+// The engine thread.  Snapshots are served in the order requested; in every round it (1) takes in new
+// requests, (2) issues gathers, oldest snapshot first, for as long as staging has room, (3) issues the
+// copies of one more group of the oldest snapshot -- so a gather into a piece of staging is enqueued as soon
+// as the copies that last read that piece have been, and with staging as large as what has been requested
+// every gather, and with it every gate, is out before the first wait for a ring slot.
 void worker_main(ds_engine *g) {
   (void)hipSetDevice(g->device);
+  std::deque<Job> active;
   for (;;) {
-    ds_event *ev = nullptr;
-    {
-      std::unique_lock<std::mutex> lk(g->mu);
-      g->cv.wait(lk, [&] { return g->stop || !g->queue.empty(); });
-      if (g->queue.empty()) return;  // stop requested and nothing left
-      ev = g->queue.front();
-      g->queue.pop_front();
+    int rc = DS_OK;
+    try {
+      {
+        std::unique_lock<std::mutex> lk(g->mu);
+        if (active.empty()) g->cv.wait(lk, [&] { return g->stop || !g->queue.empty(); });
+        if (active.empty() && g->queue.empty()) return;  // stop requested and nothing left
+        while (!g->queue.empty()) {
+          active.emplace_back();
+          active.back().ev = g->queue.front();
+          g->queue.pop_front();
+        }
+      }
+      for (Job &j : active)
+        if (!j.prepared && rc == DS_OK) rc = prepare_job(g, j);
+      bool room = true;
+      for (Job &j : active) {
+        while (rc == DS_OK && room && j.np < j.groups.size()) rc = try_issue_pack(g, j, &room);
+        if (rc != DS_OK || !room) break;
+      }
+      if (rc == DS_OK) {
+        Job &j = active.front();
+        bool blocked = false;
+        rc = issue_group_copies(g, j, &blocked);
+        if (rc == DS_OK && !blocked && j.nc == j.groups.size() && j.np == j.groups.size()) {
+          rc = finish_job(g, j);
+          if (rc == DS_OK) {
+            {
+              std::lock_guard<std::mutex> lk(g->mu);
+              j.ev->all_issued = true;
+            }
+            g->cv.notify_all();
+            active.pop_front();
+          }
+        }
+      }
+    } catch (const std::bad_alloc &) {
+      rc = DS_ENOMEM;
     }
-    int rc = issue_snapshot(g, ev);
-    {
-      std::lock_guard<std::mutex> lk(g->mu);
-      ev->error = rc;
-      ev->all_issued = true;
+    if (rc != DS_OK) {
+      // Issuing failed: every snapshot in hand reports it.  What was enqueued runs out, then staging is
+      // taken to be empty.
+      (void)hipStreamSynchronize(g->pack_stream);
+      for (int c = 0; c < g->n_copy_streams; ++c) (void)hipStreamSynchronize(g->copy_stream[c]);
+      forget_regions(g);
+      {
+        std::lock_guard<std::mutex> lk(g->mu);
+        for (Job &j : active) {
+          j.ev->error = rc;
+          j.ev->all_issued = true;
+        }
+      }
+      g->cv.notify_all();
+      active.clear();
     }
-    g->cv.notify_all();
   }
 }
 
@@ -278,10 +415,10 @@ void destroy_events(std::vector<hipEvent_t> &v) {
 }
 
 void free_engine(ds_engine *g) {
-  for (int c = 0; c < kMaxCopyStreams; ++c) {
-    destroy_events(g->stage_free[c]);
+  for (int c = 0; c < kMaxCopyStreams; ++c)
     if (g->copy_stream[c]) (void)hipStreamDestroy(g->copy_stream[c]);
-  }
+  forget_regions(g);
+  destroy_events(g->event_pool);
   destroy_events(g->ring_done);
   if (g->pack_stream) (void)hipStreamDestroy(g->pack_stream);
   if (g->stage) (void)hipFree(g->stage);
@@ -313,6 +450,7 @@ int ds_engine_create(const ds_engine_opts *o, ds_engine **out) {
   g->stage_slot_bytes = slot;
   g->first_launch_bytes = first;
   g->stage_slots = slots;
+  g->stage_bytes = slot * slots;
   g->ring_slots = (uint32_t)(ring_bytes / chunk);
   g->n_copy_streams = (int)ncs;
   hipError_t e = hipGetDevice(&g->device);
@@ -331,8 +469,6 @@ int ds_engine_create(const ds_engine_opts *o, ds_engine **out) {
   try {
     g->ring_done.assign(g->ring_slots, nullptr);
     g->ring_busy.assign(g->ring_slots, 0);
-    g->stage_used.assign(slots, false);
-    for (int c = 0; c < g->n_copy_streams; ++c) g->stage_free[c].assign(slots, nullptr);
   } catch (const std::bad_alloc &) {
     free_engine(g);
     return DS_ENOMEM;
@@ -342,8 +478,6 @@ int ds_engine_create(const ds_engine_opts *o, ds_engine **out) {
     // recorded once so that a wait on a never-used slot is a no-op by construction
     if (e == hipSuccess) e = hipEventRecord(g->ring_done[r], g->copy_stream[0]);
   }
-  for (int c = 0; c < g->n_copy_streams; ++c)
-    for (uint32_t s = 0; s < slots && e == hipSuccess; ++s) e = hipEventCreate(&g->stage_free[c][s]);
   if (e != hipSuccess) {
     ds_set_hip_error(e);
     free_engine(g);
@@ -678,6 +812,7 @@ int ds_restore_begin(ds_engine *g, const ds_plan *plan, void *compute_stream, ds
     // the engine is idle by contract; make sure its streams are, so that slots and staging are free
     e = hipStreamSynchronize(g->pack_stream);
     for (int c = 0; c < g->n_copy_streams && e == hipSuccess; ++c) e = hipStreamSynchronize(g->copy_stream[c]);
+    if (e == hipSuccess) forget_regions(g);  // nothing reads staging any more; the restore lays it out in slots
     if (e == hipSuccess) e = hipEventCreate(&ev->requested);
     if (e == hipSuccess) e = hipEventCreate(&ev->final_ev);
     if (e == hipSuccess) e = hipEventCreate(&ev->copy_begin);

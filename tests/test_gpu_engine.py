@@ -152,6 +152,44 @@ def test_back_pressure_slow_consumer_and_queued_snapshots():
         dw.close()
 
 
+def test_gates_of_queued_snapshots_do_not_wait_for_the_host_ring():
+    """Staging holds three images, the host ring two chunks, and nobody consumes:
+    the copies of the first snapshot are stuck behind the full ring, yet the
+    gathers of all three are issued ahead, so every gate opens and the state may
+    be mutated between the requests.  Drained afterwards, each snapshot shows
+    the state at its own request."""
+    ds, orc, gu, torch = _mods()
+    w = W.tiny_gpt()
+    dw = gu.DeviceWorkload(w)
+    assert 3 * dw.total <= 96 * MiB
+    eng = ds.ds_engine_create(2 * MiB, 1 * MiB, 32 * MiB, 3, 0, 0, 2)
+    s = torch.cuda.current_stream().cuda_stream
+    try:
+        mirror = w.arena.copy()
+        events, wants = [], []
+        for it in range(3):
+            print(f"[case] queued gate {it}", flush=True)
+            w.arena[:] = mirror
+            wants.append(gu.oracle_image(w)[0].copy())
+            ev = ds.ds_snapshot_async(eng, dw.plan, s)
+            ds.ds_event_wait_on_stream(ev, s)                  # must not block: no consumer is running
+            dw.arena.add_(1)
+            mirror = mirror + np.uint8(1)
+            events.append(ev)
+        ds.ds_event_wait_captured(events[-1])                  # every source byte of all three is in staging
+        for ev in events:
+            assert ds.ds_event_query(ev) == ds.DS_NOT_READY    # 2 ring slots of ~26 chunks: none can be complete
+        for it, (ev, want) in enumerate(zip(events, wants)):
+            got = _drain(ds, ev, dw.total)
+            ds.ds_event_wait(ev)
+            assert gu.first_mismatch(got, want) is None, (it, gu.first_mismatch(got, want))
+            ds.ds_event_destroy(ev)
+        assert np.array_equal(dw.arena_host(), mirror)
+    finally:
+        ds.ds_engine_destroy(eng)
+        dw.close()
+
+
 def test_auto_release_and_state_errors():
     ds, orc, gu, torch = _mods()
     w = W.tiny_gpt()
@@ -407,6 +445,69 @@ def test_checkpoint_file_from_a_snapshot_with_concurrent_object_log(tmp_path):
     finally:
         ds.ds_engine_destroy(eng)
         dw.close()
+
+
+def test_rank_checkpoint_split_over_several_files(tmp_path):
+    """A rank that writes several files per checkpoint (Sec. VI-D: 20 for the 7B
+    rank) uses one plan and one checkpoint writer per file, all through one
+    engine and in flight together.  Every file must hold the oracle's image of its
+    own shards, and restoring the files one after the other must bring back
+    every tensor."""
+    from oracle import ckpt_format as fmt
+    ds, orc, gu, torch = _mods()
+    w = W.fragmentation(900, max_bytes=1 << 18, seed=41)
+    n = len(w.shards)
+    print("[case] several files", flush=True)
+    arena = torch.from_numpy(w.arena).to("cuda")
+    cuts = [0, n // 7, n // 3, n // 3 + 1, (3 * n) // 4, n]           # five files, one of them a single shard
+    eng = ds.ds_engine_create(4 * MiB, 1 * MiB, 2 * MiB, 2, 0, 0, 0)  # ring smaller than the sum of the images
+    s = torch.cuda.current_stream().cuda_stream
+    files = []
+    try:
+        for k, (a, b) in enumerate(zip(cuts[:-1], cuts[1:])):
+            shards = w.shards[a:b]
+            descs = ds.make_descs(shards, arena.data_ptr())
+            total = ds.ds_layout_assign(descs, b - a, w.align)
+            plan = ds.ds_plan_create(descs, b - a, w.align, ds.DS_PLAN_STRICT)
+            tab = orc.table(shards, w.arena.ctypes.data)
+            assert orc.layout(tab, b - a, w.align) == total
+            files.append({"plan": plan, "tab": tab, "n": b - a, "total": total,
+                          "want": orc.pack(tab, b - a, total, threads=4), "path": str(tmp_path / f"rank0_{k}.ckpt")})
+        for f in files:
+            f["ev"] = ds.ds_snapshot_async(eng, f["plan"], s)
+            f["ck"] = ds.ds_ckpt_create(f["path"], f["plan"], ds.DS_FILE_DIRECT)
+            ds.ds_ckpt_flush_snapshot(f["ck"], f["ev"], 2)
+            ds.ds_ckpt_append(f["ck"], 1, b"file %d" % len(f["path"]))
+        ds.ds_event_wait_on_stream(files[-1]["ev"], s)                 # snapshots run in order: this gate covers all
+        arena.fill_(0xA5)                                              # the update phase may now overwrite everything
+        torch.cuda.synchronize()
+        for f in files:
+            ds.ds_ckpt_finish(f["ck"])
+            ds.ds_event_wait(f["ev"])
+            ds.ds_event_destroy(f["ev"])
+            back = fmt.parse_file(open(f["path"], "rb").read())
+            assert gu.first_mismatch(np.frombuffer(back["image"], dtype=np.uint8), f["want"]) is None, f["path"]
+            assert back["objects"] == {1: b"file %d" % len(f["path"])}
+        mirror = w.arena.copy()
+        w.arena[:] = 0xA5
+        for f in files:
+            r = ds.ds_ckpt_open(f["path"])
+            rev = ds.ds_ckpt_restore(r, eng, f["plan"], 2, ds.DS_FILE_DIRECT, s)
+            ds.ds_event_wait(rev)
+            ds.ds_event_destroy(rev)
+            ds.ds_ckpt_close(r)
+            orc.unpack(f["tab"], f["n"], f["want"])
+        assert gu.first_mismatch(arena.cpu().numpy(), w.arena) is None
+        # every addressed byte is back (the rest of the arena keeps the 0xA5 written above)
+        for f in files:
+            got = orc.pack(f["tab"], f["n"], f["total"], threads=4)
+            assert gu.first_mismatch(got, f["want"]) is None
+        w.arena[:] = mirror
+    finally:
+        ds.ds_engine_destroy(eng)
+        torch.cuda.synchronize()
+        for f in files:
+            ds.ds_plan_destroy(f["plan"])
 
 
 def test_flush_io_error_does_not_stall_the_snapshot():
