@@ -701,6 +701,8 @@ def main() -> int:
                         evs.append(ev)
                         cks.append(ck)
                     ds.ds_event_wait_on_stream(evs[-1], stream)
+                    ds.ds_event_wait_captured(evs[-1])
+                    cap_ms = (time.perf_counter() - t0) * 1e3   # first request -> every tensor may be mutated
                     nbytes = sum(ds.ds_ckpt_finish(ck)[0] for ck in cks)
                     files_s = time.perf_counter() - t0
                     for ev in evs:
@@ -708,6 +710,7 @@ def main() -> int:
                         ds.ds_event_destroy(ev)
                     file_tier["several_files"] = {"dir": dirs[0], "files": len(paths), "file_bytes": nbytes,
                                                   "threads_per_file": max(1, args.file_threads // 2),
+                                                  "first_request_to_all_captured_ms": round(cap_ms, 3),
                                                   "snapshot_to_files_GBps": round(nbytes / files_s / 1e9, 2)}
                 except ds.DsError as e:
                     file_tier["several_files"] = {"error": str(e)}
