@@ -203,8 +203,8 @@ typedef struct ds_engine_opts {
                                 copy.  0 = stage_slot_bytes (no short first launch)                  */
 } ds_engine_opts;
 
-/* Allocates the pinned ring, the device staging slots, two side streams
- * (gather, copy; default priority) and a host thread that issues the work.
+/* Allocates the pinned ring, the device staging, a gather stream and the copy streams
+ * (all at the default priority) and a host thread that issues the work.
  * Uses the current device.  Errors: DS_EINVAL, DS_ENOMEM, DS_EHIP. */
 int ds_engine_create(const ds_engine_opts *opts, ds_engine **out);
 
