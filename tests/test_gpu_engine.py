@@ -190,6 +190,70 @@ def test_gates_of_queued_snapshots_do_not_wait_for_the_host_ring():
         dw.close()
 
 
+@pytest.mark.parametrize("cfg", [
+    dict(ring=3 * MiB, chunk=1 * MiB, slot=2 * MiB, slots=3, copy_streams=2),
+    dict(ring=8 * MiB, chunk=2 * MiB, slot=8 * MiB, slots=2, copy_streams=2, first=2 * MiB),
+    dict(ring=2 * MiB, chunk=1 * MiB, slot=1 * MiB, slots=1, copy_streams=1),
+])
+def test_random_sequence_of_snapshots_of_three_plans(cfg):
+    """Three shard sets of very different sizes share one engine whose staging
+    is smaller than the largest image: ten snapshots in random order, each gated
+    and followed by an update of its own tensors, drained by one consumer
+    thread in request order.  Every image must be the oracle's image of the
+    state at its request (pieces of staging are handed from snapshot to
+    snapshot, wrap around, and wait for the ring)."""
+    import queue
+    ds, orc, gu, torch = _mods()
+    sets = [W.tiny_gpt(), W.fragmentation(400, max_bytes=1 << 16, seed=5), W.fragmentation(12, max_bytes=1 << 12, seed=6)]
+    dws = [gu.DeviceWorkload(w) for w in sets]
+    mirrors = [w.arena.copy() for w in sets]
+    eng = ds.ds_engine_create(cfg["ring"], cfg["chunk"], cfg["slot"], cfg["slots"], 0, 0, cfg["copy_streams"],
+                              cfg.get("first", 0))
+    s = torch.cuda.current_stream().cuda_stream
+    todo, results = queue.Queue(), []
+
+    def consumer():
+        while True:
+            item = todo.get()
+            if item is None:
+                return
+            ev, total = item
+            results.append(_drain(ds, ev, total))
+
+    th = threading.Thread(target=consumer)
+    th.start()
+    rng = np.random.default_rng(2601)
+    wants, events = [], []
+    try:
+        for it in range(10):
+            p = int(rng.integers(0, 3))
+            print(f"[case] random sequence {cfg} step {it} plan {p}", flush=True)
+            sets[p].arena[:] = mirrors[p]
+            wants.append(gu.oracle_image(sets[p])[0].copy())
+            ev = ds.ds_snapshot_async(eng, dws[p].plan, s)
+            todo.put((ev, dws[p].total))
+            ds.ds_event_wait_on_stream(ev, s)                  # the consumer is another thread: this may wait for it
+            dws[p].arena.add_(it + 1)
+            mirrors[p] = mirrors[p] + np.uint8(it + 1)
+            events.append(ev)
+        todo.put(None)
+        th.join()
+        torch.cuda.synchronize()
+        for it, (ev, got, want) in enumerate(zip(events, results, wants)):
+            ds.ds_event_wait(ev)
+            assert gu.first_mismatch(got, want) is None, (it, gu.first_mismatch(got, want))
+            ds.ds_event_destroy(ev)
+        for p in range(3):
+            assert np.array_equal(dws[p].arena_host(), mirrors[p])
+    finally:
+        if th.is_alive():
+            todo.put(None)
+            th.join()
+        ds.ds_engine_destroy(eng)
+        for dw in dws:
+            dw.close()
+
+
 def test_auto_release_and_state_errors():
     ds, orc, gu, torch = _mods()
     w = W.tiny_gpt()
