@@ -23,15 +23,14 @@
 //   of at least 16 bytes each).
 //
 // general path: the remaining chunks (tile boundaries, payload tails, padding,
-//   N-D views); their record names the tiles they hold:
-//   - A chunk that holds a few tiles walks them one after the other with the
-//     whole work-group ("direct" path).
-//   - A chunk that holds many small tiles takes them 64 at a time: every lane
-//     reads one tile's extent, a wavefront inclusive scan over the unit counts
-//     turns the 64 tiles into one dense index space, and the threads of the
-//     work-group share that space evenly; a binary search over the scan (in
-//     LDS) maps a unit back to (tile, offset).  Tiles that are large anyway
-//     are taken out of the scan and go through the direct path.
+//   N-D views); their record names the tiles they hold.  The tiles are taken
+//   64 at a time: the first wavefront reads one tile's extent and descriptor
+//   per lane, a wavefront inclusive scan over the unit counts turns the 64
+//   tiles into one dense index space, and the threads of the work-group share
+//   that space evenly, four units each per pass, in phases (find the tile of
+//   each unit by binary search over the scan in LDS, issue all loads, issue
+//   all stores).  Large pieces of views with several outer dimensions are
+//   taken out of the scan and walked by the whole work-group ("direct" path).
 //
 // Tensor-side addresses are only element-aligned.  gfx950 runs with unaligned
 // global access enabled, so a 16-byte unit that lies inside one contiguous run
@@ -47,8 +46,7 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef u32x4 u32x4_unaligned __attribute__((aligned(1)));
 
 constexpr int kWave = 64;
-constexpr uint32_t kDirectMaxTiles = 4;   // chunks with at most this many tiles skip the scan
-constexpr uint32_t kBigUnits = 512;       // tiles of >= 8 KiB inside a chunk leave the scan
+constexpr uint32_t kBigUnits = 512;       // N-D views: pieces of >= 8 KiB inside a chunk leave the scan
 
 struct MoveArgs {
   const DsTile *tiles;
@@ -297,68 +295,154 @@ __device__ __forceinline__ uint32_t wave_inclusive_scan(uint32_t x, uint32_t lan
   return x;
 }
 
+// What a batch of up to 64 tiles of a general chunk needs, staged in LDS by the first wavefront.
+struct GenLds {
+  uint32_t incl[kWave];     // inclusive scan of the tiles' unit counts inside the chunk
+  uint32_t begin[kWave];    // where a tile's clipped range starts, relative to the chunk's (clipped) start
+  uint32_t meta[kWave];     // n_outer | es_log2 << 8
+  uint64_t b0[kWave];       // byte of the tile's own range at which its clipped range starts
+  uint64_t src[kWave], nbytes[kWave], run[kWave], stride0[kWave];
+  uint64_t big_mask;        // tiles taken out of the scan (large pieces of views with several outer dimensions)
+  uint32_t n_units;         // units of the batch = incl[63]
+};
+
 // One general chunk, whole work-group: chunk number c, which holds (parts of) tiles t0 .. t1.
-// s_incl: inclusive scan of unit counts of the 64 tiles of a batch; s_begin: where each tile's clipped
-// range starts, relative to the chunk (both kWave words of LDS).
+//
+// The tiles are taken 64 at a time.  The first wavefront reads their extents and descriptors (one tile per
+// lane), turns the unit counts into one dense index space with an inclusive scan, and leaves all of it in
+// LDS; then every thread takes the units tid, tid + NT, ... of that space, UNROLL at a time in phases: find
+// the tile of each unit (binary search over the scan) and classify it, issue all loads, issue all stores.
+// So a chunk costs three dependent trips to memory (record -> extents and descriptors -> data) however many
+// tiles it holds.  Units that are one 16-byte access -- inside the payload of a contiguous tile or inside a
+// row of a 2-D view -- and padding are handled in the phases; the rest (cut by the end of a row or of the
+// payload, views with several outer dimensions) go one by one through move_unit afterwards.
 template <bool PACK, int NT, int UNROLL, bool NTL, bool NTS>
-__device__ __forceinline__ void general_chunk(const MoveArgs &a, uint64_t c, uint32_t t0, uint32_t t1, uint32_t *s_incl,
-                                              uint32_t *s_begin) {
+__device__ __forceinline__ void general_chunk(const MoveArgs &a, uint64_t c, uint32_t t0, uint32_t t1, GenLds *g) {
   const uint32_t tid = threadIdx.x;
   const uint32_t lane = tid & (kWave - 1);
-  {
-    const uint64_t c_begin = c << a.chunk_log2;
-    uint64_t c_end = (c + 1) << a.chunk_log2;
-    if (c_end > a.total) c_end = a.total;
-    const uint64_t cb = c_begin > a.img_lo ? c_begin : a.img_lo;
-    const uint64_t ce = c_end < a.img_hi ? c_end : a.img_hi;
-    if (cb >= ce) return;
+  const uint64_t c_begin = c << a.chunk_log2;
+  uint64_t c_end = (c + 1) << a.chunk_log2;
+  if (c_end > a.total) c_end = a.total;
+  const uint64_t cb = c_begin > a.img_lo ? c_begin : a.img_lo;
+  const uint64_t ce = c_end < a.img_hi ? c_end : a.img_hi;
+  if (cb >= ce) return;
 
-    if (t1 - t0 < kDirectMaxTiles) {
-      for (uint32_t t = t0; t <= t1; ++t) {
-        const uint64_t tb = a.tile_off[t], te = a.tile_off[t + 1];
-        const uint64_t lo = tb > cb ? tb : cb, hi = te < ce ? te : ce;
-        if (lo < hi) move_tile_direct<PACK, NT, UNROLL, NTL, NTS>(a.tiles + t, tb, lo, hi, a.img, a.img_lo);
-      }
-      return;
-    }
-
-    for (uint32_t bt = t0; bt <= t1; bt += kWave) {
+  for (uint32_t bt = t0; bt <= t1; bt += kWave) {
+    __syncthreads();  // readers of the previous batch (or of the previous chunk) are done
+    if (tid < kWave) {
       const uint32_t ti = bt + lane;
-      uint64_t lo = cb, hi = cb;
+      uint64_t lo = cb, hi = cb, tb = cb;
+      uint64_t src = 0, nbytes = 0, run = 0, stride0 = 0;
+      uint32_t n_outer = 0, es_log2 = 0;
       if (ti <= t1) {
-        const uint64_t tb = a.tile_off[ti], te = a.tile_off[ti + 1];
+        tb = a.tile_off[ti];
+        const uint64_t te = a.tile_off[ti + 1];
+        const DsTile *t = a.tiles + ti;
+        src = t->src;
+        nbytes = t->nbytes;
+        run = t->run_bytes;
+        n_outer = t->n_outer;
+        es_log2 = t->es_log2;
+        stride0 = t->stride[0];
         lo = tb > cb ? tb : cb;
         hi = te < ce ? te : ce;
         if (hi < lo) hi = lo;
       }
       const uint32_t units = (uint32_t)((hi - lo) >> 4);
-      const bool big = units >= kBigUnits;
-      uint64_t big_mask = __ballot(big);
+      const bool big = units >= kBigUnits && n_outer > 1;
+      const uint64_t big_mask = __ballot(big);
       const uint32_t incl = wave_inclusive_scan(big ? 0u : units, lane);
-      const uint32_t n_small = __shfl(incl, kWave - 1, kWave);
-      __syncthreads();  // readers of the previous batch are done
-      if (tid < kWave) {
-        s_incl[lane] = incl;
-        s_begin[lane] = (uint32_t)(lo - cb);
+      g->incl[lane] = incl;
+      g->begin[lane] = (uint32_t)(lo - cb);
+      g->meta[lane] = n_outer | (es_log2 << 8);
+      g->b0[lane] = lo - tb;
+      g->src[lane] = src;
+      g->nbytes[lane] = nbytes;
+      g->run[lane] = run;
+      g->stride0[lane] = stride0;
+      if (lane == kWave - 1) {
+        g->n_units = incl;
+        g->big_mask = big_mask;
       }
-      __syncthreads();
-      for (uint32_t j = tid; j < n_small; j += NT) {
-        uint32_t p = 0;  // smallest p with s_incl[p] > j
+    }
+    __syncthreads();
+    const uint32_t n_units = g->n_units;
+    // unit j of the batch: its tile p, its image offset x and its byte offset b in the tile's own range
+    auto locate = [&](uint32_t j, uint32_t &p, uint64_t &x, uint64_t &b) {
+      p = 0;  // smallest p with incl[p] > j
 #pragma unroll
-        for (int step = kWave / 2; step > 0; step >>= 1)
-          if (s_incl[p + step - 1] <= j) p += step;
-        const uint32_t before = p ? s_incl[p - 1] : 0u;
-        const uint64_t x = cb + s_begin[p] + 16ull * (j - before);
-        move_unit<PACK, NTL, NTS>(a.tiles + bt + p, a.tile_off[bt + p], x, a.img + (x - a.img_lo));
+      for (int step = kWave / 2; step > 0; step >>= 1)
+        if (g->incl[p + step - 1] <= j) p += step;
+      const uint32_t d = 16u * (j - (p ? g->incl[p - 1] : 0u));
+      x = cb + g->begin[p] + d;
+      b = g->b0[p] + d;
+    };
+    for (uint32_t base = 0; base < n_units; base += NT * UNROLL) {
+      enum : uint32_t { kNone = 0, kFast = 1, kZero = 2, kSlow = 3 };
+      u32x4 v[UNROLL];
+      uint8_t *ip[UNROLL];   // the unit in the image buffer
+      uint8_t *sp[UNROLL];   // kFast: the unit in the tensor
+      uint32_t how[UNROLL];
+#pragma unroll
+      for (int i = 0; i < UNROLL; ++i) {
+        const uint32_t j = base + i * NT + tid;
+        how[i] = kNone;
+        if (j < n_units) {
+          uint32_t p;
+          uint64_t x, b;
+          locate(j, p, x, b);
+          const uint64_t nbytes = g->nbytes[p];
+          ip[i] = a.img + (x - a.img_lo);
+          if (b >= nbytes) {
+            how[i] = kZero;
+          } else {
+            how[i] = kSlow;
+            const uint32_t n_outer = g->meta[p] & 0xFFu;
+            if (nbytes - b >= 16) {
+              if (n_outer == 0) {
+                sp[i] = reinterpret_cast<uint8_t *>(g->src[p] + b);
+                how[i] = kFast;
+              } else if (n_outer == 1) {
+                const uint64_t L = g->run[p];
+                uint64_t row, col;
+                divmod(b, L, row, col);
+                if (col + 16 <= L) {
+                  sp[i] = reinterpret_cast<uint8_t *>(g->src[p] + row * g->stride0[p] + col);
+                  how[i] = kFast;
+                }
+              }
+            }
+          }
+          if (how[i] == kFast) v[i] = PACK ? ld16_any<NTL>(sp[i]) : ld16_aligned<NTL>(ip[i]);
+        }
       }
-      while (big_mask) {
-        const uint32_t p = (uint32_t)__builtin_ctzll(big_mask);
-        big_mask &= big_mask - 1;
-        const uint32_t t = bt + p;
-        const uint64_t tb = a.tile_off[t], te = a.tile_off[t + 1];
-        const uint64_t lo2 = tb > cb ? tb : cb, hi2 = te < ce ? te : ce;
-        move_tile_direct<PACK, NT, UNROLL, NTL, NTS>(a.tiles + t, tb, lo2, hi2, a.img, a.img_lo);
+#pragma unroll
+      for (int i = 0; i < UNROLL; ++i) {
+        if (how[i] == kFast) {
+          if (PACK) st16_aligned<NTS>(ip[i], v[i]);
+          else st16_any<NTS>(sp[i], v[i]);
+        } else if (PACK && how[i] == kZero) {
+          st16_aligned<NTS>(ip[i], u32x4{0, 0, 0, 0});
+        }
       }
+      // the rare rest, one by one (located again: keeping x and b of every unit would cost registers)
+#pragma unroll
+      for (int i = 0; i < UNROLL; ++i)
+        if (how[i] == kSlow) {
+          uint32_t p;
+          uint64_t x, b;
+          locate(base + i * NT + tid, p, x, b);
+          move_unit<PACK, NTL, NTS>(a.tiles + bt + p, x - b, x, ip[i]);
+        }
+    }
+    uint64_t big_mask = g->big_mask;
+    while (big_mask) {
+      const uint32_t p = (uint32_t)__builtin_ctzll(big_mask);
+      big_mask &= big_mask - 1;
+      const uint32_t t = bt + p;
+      const uint64_t tb = a.tile_off[t], te = a.tile_off[t + 1];
+      const uint64_t lo2 = tb > cb ? tb : cb, hi2 = te < ce ? te : ce;
+      move_tile_direct<PACK, NT, UNROLL, NTL, NTS>(a.tiles + t, tb, lo2, hi2, a.img, a.img_lo);
     }
   }
 }
@@ -416,8 +500,7 @@ constexpr int kStorePolicySc0Sc1Nt = 1 | 2 | 16;  // sc0 | nt | sc1 in the intri
 __device__ __forceinline__ uint32_t lean_items(const LeanArgs &a) { return a.xcd_span ? a.xcd_span * 8u : a.n_chunks; }
 
 template <bool PACK, int NT, int UNROLL, bool NTL, bool NTS, bool BUFST>
-__device__ __forceinline__ void lean_chunk(const LeanArgs &a, const MoveArgs &ma, uint32_t ci, uint32_t *s_incl,
-                                           uint32_t *s_begin) {
+__device__ __forceinline__ void lean_chunk(const LeanArgs &a, const MoveArgs &ma, uint32_t ci, GenLds *s_gen) {
   const uint32_t tid = threadIdx.x;
   {
     // Work-groups are dealt to the 8 XCDs round-robin (work-group i runs on XCD i mod 8).  Chunk
@@ -434,7 +517,7 @@ __device__ __forceinline__ void lean_chunk(const LeanArgs &a, const MoveArgs &ma
     const uint32_t kind = r.kind & 0xFF;  // bits 8.. hold log2(itemsize)
     if (kind == DS_CHUNK_GENERAL) {
       // its record names the tiles it holds: one load away from them, and in place among its neighbours
-      general_chunk<PACK, 256, 4, NTL, NTS>(ma, c, r.tile, r.tile + r.col0, s_incl, s_begin);
+      general_chunk<PACK, 256, 4, NTL, NTS>(ma, c, r.tile, r.tile + r.col0, s_gen);
       return;
     }
     uint8_t *imgp = a.img + (((uint64_t)c << a.chunk_log2) - a.img_lo);
@@ -535,13 +618,12 @@ __device__ __forceinline__ void lean_chunk(const LeanArgs &a, const MoveArgs &ma
 template <bool PACK, int UNROLL, bool NTL, bool NTS, bool BUFST>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 4))) void ds_move_kernel(LeanArgs la,
                                                                                                  MoveArgs ma) {
-  __shared__ uint32_t s_incl[kWave];
-  __shared__ uint32_t s_begin[kWave];
+  __shared__ GenLds s_gen;
   const uint32_t n_lean = lean_items(la);
   const uint32_t n_iter = n_lean + ma.n_extra;
   for (uint32_t wi = blockIdx.x; wi < n_iter; wi += gridDim.x) {
     if (wi < n_lean) {
-      lean_chunk<PACK, 256, UNROLL, NTL, NTS, BUFST>(la, ma, wi, s_incl, s_begin);
+      lean_chunk<PACK, 256, UNROLL, NTL, NTS, BUFST>(la, ma, wi, &s_gen);
     } else {
       // a chunk cut by the range: the general path clips to the range, whatever the chunk's kind
       const uint64_t c = ma.extra[wi - n_lean];
@@ -550,7 +632,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 4))) voi
       const uint32_t t0 = ma.first_tile[c];
       uint32_t t1 = ma.first_tile[c + 1];
       if (ma.tile_off[t1] >= c_end) --t1;  // that tile starts where this chunk ends
-      general_chunk<PACK, 256, 4, NTL, NTS>(ma, c, t0, t1, s_incl, s_begin);
+      general_chunk<PACK, 256, 4, NTL, NTS>(ma, c, t0, t1, &s_gen);
     }
   }
 }
