@@ -484,6 +484,66 @@ def test_random_tables_pack_and_unpack():
             dw.close()
 
 
+@pytest.mark.parametrize("chunk_bytes", [8192, 16384, 32768])
+def test_general_path_batches_direct_pieces_and_unit_kinds(chunk_bytes):
+    """A table made for the general path: thousands of 16..60-byte shards at
+    16-byte alignment (hundreds of tiles per chunk: several batches of 64),
+    a large view with two outer dimensions (pieces of >= 8 KiB per chunk: the
+    direct path), a view with three outer dimensions and one-element runs, rows
+    shorter than 16 bytes (every unit cut), and odd-sized payload tails of every
+    dtype -- gathered and scattered whole and in ranges that cut chunks."""
+    from workloads.configs import DTYPES
+    ds, orc, gu = _mods()
+    rng = np.random.default_rng(77)
+    arena_bytes = 1 << 23
+    arena = rng.integers(0, 256, size=arena_bytes, dtype=np.uint8)
+    shards, at = [], 0
+
+    def put(dtype, shape, strides):
+        nonlocal at
+        es = DTYPES[dtype][1]
+        span = 1 + sum((max(e, 1) - 1) * st for e, st in zip(shape, strides))
+        at = -(-at // es) * es + es * int(rng.integers(0, 3))
+        shards.append(Shard(f"g{len(shards)}", dtype, tuple(shape), tuple(strides), at, 5000 + len(shards)))
+        at += span * es
+
+    names = list(DTYPES)
+    for k in range(3000):                                       # tiny shards, any dtype
+        dtype = names[k % 5]
+        es = DTYPES[dtype][1]
+        put(dtype, [max(1, int(rng.integers(16, 61)) // es)], [1])
+    put("f32", [64, 96, 40], [96 * 100 + 7, 100, 1])            # two outer dimensions, 960 KB of payload
+    put("u8", [30, 7, 5, 3], [7 * 5 * 3 * 8, 5 * 3 * 4, 3 * 2, 2])   # one-element runs
+    put("bf16", [4000, 6], [10, 1])                             # 12-byte rows
+    put("i64", [1001, 3], [5, 1])                               # 24-byte rows: most units cut
+    for dtype in names:                                         # odd tails
+        es = DTYPES[dtype][1]
+        put(dtype, [(1 << 15) // es + 1], [1])
+    assert at < arena_bytes
+    w = _adhoc(arena, shards, 16)
+    ds.ds_config_set("chunk_bytes", chunk_bytes)
+    try:
+        print(f"[case] general path table chunk_bytes={chunk_bytes} shards={len(shards)}", flush=True)
+        want, offs, tab = gu.oracle_image(w)
+        dw = gu.DeviceWorkload(w)
+        try:
+            assert dw.info["n_general_chunks"] >= 40
+            got = dw.pack()
+            assert gu.first_mismatch(got, want) is None, gu.first_mismatch(got, want)
+            for lo, hi in ((16, 48), (4096 + 16, 3 * chunk_bytes + 32), (dw.total - chunk_bytes - 16, dw.total)):
+                part = dw.pack(lo, hi)
+                assert gu.first_mismatch(part, want[lo:hi]) is None, (lo, hi, gu.first_mismatch(part, want[lo:hi]))
+            dw.arena.fill_(0x5A)
+            dw.unpack(want)
+            w.arena[:] = 0x5A
+            orc.unpack(tab, len(shards), want)
+            assert gu.first_mismatch(dw.arena_host(), w.arena) is None
+        finally:
+            dw.close()
+    finally:
+        ds.ds_config_set("chunk_bytes", 16384)
+
+
 @pytest.mark.parametrize("block_bytes", [16384, 65536, 1 << 20])
 def test_image_diff_flags_exactly_the_blocks_that_differ(block_bytes):
     """ds_image_diff against its definition (a block is flagged iff some byte of it differs) on image pairs
