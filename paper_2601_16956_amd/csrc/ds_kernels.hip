@@ -35,8 +35,10 @@
 // Tensor-side addresses are only element-aligned.  gfx950 runs with unaligned
 // global access enabled, so a 16-byte unit that lies inside one contiguous run
 // is one (possibly unaligned) dwordx4 access; a unit that is cut by the end of
-// a run or of the payload is moved element by element with exact bounds, so no
-// byte outside the described views is ever read or written.
+// a run or of the payload is assembled from 16-byte loads that lie inside the
+// runs (gather), stored in pieces that cover exactly its bytes (scatter), or,
+// for runs shorter than 16 bytes, moved element by element, so no byte outside
+// the described views is ever read or written.
 
 #include "ds_internal.h"
 
@@ -295,6 +297,56 @@ __device__ __forceinline__ uint32_t wave_inclusive_scan(uint32_t x, uint32_t lan
   return x;
 }
 
+// ---- units cut by the end of a run ------------------------------------------------------
+// bytes [s, s+16) of the 32 bytes a||b, 0 < s < 16
+__device__ __forceinline__ u32x4 splice(u32x4 a, u32x4 b, uint32_t s) {
+  uint64_t x0 = a.x | ((uint64_t)a.y << 32), x1 = a.z | ((uint64_t)a.w << 32);
+  uint64_t x2 = b.x | ((uint64_t)b.y << 32), x3 = b.z | ((uint64_t)b.w << 32);
+  if (s >= 8) {
+    x0 = x1;
+    x1 = x2;
+    x2 = x3;
+    s -= 8;
+  }
+  uint64_t r0 = x0, r1 = x1;
+  if (s) {
+    const uint32_t sh = 8 * s;
+    r0 = (x0 >> sh) | (x1 << (64 - sh));
+    r1 = (x1 >> sh) | (x2 << (64 - sh));
+  }
+  return u32x4{(uint32_t)r0, (uint32_t)(r0 >> 32), (uint32_t)r1, (uint32_t)(r1 >> 32)};
+}
+
+// the low n < 16 bytes of v to p (any alignment), as one store each of 8, 4, 2 and 1 bytes as n has those bits
+typedef uint64_t u64_unaligned __attribute__((aligned(1)));
+typedef uint32_t u32_unaligned __attribute__((aligned(1)));
+typedef uint16_t u16_unaligned __attribute__((aligned(1)));
+__device__ __forceinline__ void store_low_bytes(uint8_t *p, u32x4 v, uint32_t n) {
+  uint64_t lo = v.x | ((uint64_t)v.y << 32);
+  const uint64_t hi = v.z | ((uint64_t)v.w << 32);
+  if (n & 8) {
+    *(DS_GLOBAL u64_unaligned *)p = lo;
+    p += 8;
+    lo = hi;
+  }
+  if (n & 4) {
+    *(DS_GLOBAL u32_unaligned *)p = (uint32_t)lo;
+    p += 4;
+    lo >>= 32;
+  }
+  if (n & 2) {
+    *(DS_GLOBAL u16_unaligned *)p = (uint16_t)lo;
+    p += 2;
+    lo >>= 16;
+  }
+  if (n & 1) *(DS_GLOBAL uint8_t *)p = (uint8_t)lo;
+}
+// bytes [0,k) of v go to p0, bytes [k,valid) to p1 (0 < k < 16, k <= valid <= 16); exactly those bytes are written
+__device__ __forceinline__ void store_cut(uint8_t *p0, uint8_t *p1, uint32_t k, u32x4 v, uint32_t valid = 16) {
+  store_low_bytes(p0, v, k);
+  if (valid > k) store_low_bytes(p1, splice(v, u32x4{0, 0, 0, 0}, k), valid - k);
+}
+
 // What a batch of up to 64 tiles of a general chunk needs, staged in LDS by the first wavefront.
 struct GenLds {
   uint32_t incl[kWave];     // inclusive scan of the tiles' unit counts inside the chunk
@@ -378,7 +430,7 @@ __device__ __forceinline__ void general_chunk(const MoveArgs &a, uint64_t c, uin
       b = g->b0[p] + d;
     };
     for (uint32_t base = 0; base < n_units; base += NT * UNROLL) {
-      enum : uint32_t { kNone = 0, kFast = 1, kZero = 2, kSlow = 3 };
+      enum : uint32_t { kNone = 0, kFast = 1, kZero = 2, kCut = 3, kSlow = 4 };
       u32x4 v[UNROLL];
       uint8_t *ip[UNROLL];   // the unit in the image buffer
       uint8_t *sp[UNROLL];   // kFast: the unit in the tensor
@@ -398,16 +450,17 @@ __device__ __forceinline__ void general_chunk(const MoveArgs &a, uint64_t c, uin
           } else {
             how[i] = kSlow;
             const uint32_t n_outer = g->meta[p] & 0xFFu;
-            if (nbytes - b >= 16) {
-              if (n_outer == 0) {
-                sp[i] = reinterpret_cast<uint8_t *>(g->src[p] + b);
-                how[i] = kFast;
-              } else if (n_outer == 1) {
-                const uint64_t L = g->run[p];
-                uint64_t row, col;
+            if (n_outer <= 1) {
+              // the run the unit starts in: the whole payload, or one row of a 2-D view
+              uint64_t L = nbytes, row = 0, col = b;
+              if (n_outer) {
+                L = g->run[p];
                 divmod(b, L, row, col);
+              }
+              if (L >= 16) {
+                how[i] = kCut;
                 if (col + 16 <= L) {
-                  sp[i] = reinterpret_cast<uint8_t *>(g->src[p] + row * g->stride0[p] + col);
+                  sp[i] = reinterpret_cast<uint8_t *>(g->src[p] + (n_outer ? row * g->stride0[p] : 0) + col);
                   how[i] = kFast;
                 }
               }
@@ -425,7 +478,40 @@ __device__ __forceinline__ void general_chunk(const MoveArgs &a, uint64_t c, uin
           st16_aligned<NTS>(ip[i], u32x4{0, 0, 0, 0});
         }
       }
-      // the rare rest, one by one (located again: keeping x and b of every unit would cost registers)
+      // Units cut by the end of a run of at least 16 bytes: the first k bytes end that run, the rest start the
+      // next one, or are padding when the payload ends there.  As in the lean path the gather takes both
+      // parts with 16-byte loads that lie wholly inside their runs and splices them; the scatter stores each
+      // part as at most four pieces of 8, 4, 2 and 1 bytes.  (Located again: keeping every unit's position
+      // would cost registers.)
+#pragma unroll
+      for (int i = 0; i < UNROLL; ++i)
+        if (how[i] == kCut) {  // at most a few per pass and seldom two in one thread: one after the other
+          uint32_t p;
+          uint64_t x, b;
+          locate(base + i * NT + tid, p, x, b);
+          const uint64_t nbytes = g->nbytes[p];
+          const uint32_t meta = g->meta[p];
+          uint64_t L = nbytes, row = 0, col = b, pitch = 0;
+          if (meta & 0xFFu) {
+            L = g->run[p];
+            pitch = g->stride0[p];
+            divmod(b, L, row, col);
+          }
+          const uint64_t run0 = g->src[p] + row * pitch;
+          const uint32_t k = (uint32_t)(L - col);
+          uint8_t *p0 = reinterpret_cast<uint8_t *>(run0 + col);
+          const bool last = b + k >= nbytes;  // the payload ends with this run
+          uint8_t *p1 = reinterpret_cast<uint8_t *>(run0 + pitch);
+          if (PACK) {
+            const u32x4 va = ld16_any<NTL>(p0 + k - 16);
+            u32x4 vb = u32x4{0, 0, 0, 0};
+            if (!last) vb = ld16_any<NTL>(p1);
+            st16_aligned<NTS>(ip[i], splice(va, vb, 16u - k));
+          } else {
+            store_cut(p0, p1, k, ld16_aligned<NTL>(ip[i]), last ? k : 16u);
+          }
+        }
+      // the rare rest (runs shorter than 16 bytes, views with several outer dimensions), one by one
 #pragma unroll
       for (int i = 0; i < UNROLL; ++i)
         if (how[i] == kSlow) {
@@ -448,47 +534,6 @@ __device__ __forceinline__ void general_chunk(const MoveArgs &a, uint64_t c, uin
 }
 
 // ---- the lean path -----------------------------------------------------------
-// bytes [s, s+16) of the 32 bytes a||b, 0 < s < 16
-__device__ __forceinline__ u32x4 splice(u32x4 a, u32x4 b, uint32_t s) {
-  uint64_t x0 = a.x | ((uint64_t)a.y << 32), x1 = a.z | ((uint64_t)a.w << 32);
-  uint64_t x2 = b.x | ((uint64_t)b.y << 32), x3 = b.z | ((uint64_t)b.w << 32);
-  if (s >= 8) {
-    x0 = x1;
-    x1 = x2;
-    x2 = x3;
-    s -= 8;
-  }
-  uint64_t r0 = x0, r1 = x1;
-  if (s) {
-    const uint32_t sh = 8 * s;
-    r0 = (x0 >> sh) | (x1 << (64 - sh));
-    r1 = (x1 >> sh) | (x2 << (64 - sh));
-  }
-  return u32x4{(uint32_t)r0, (uint32_t)(r0 >> 32), (uint32_t)r1, (uint32_t)(r1 >> 32)};
-}
-
-// bytes [0,k) of v go to p0, bytes [k,16) to p1; element by element (k is a multiple of the itemsize)
-template <int ES>
-__device__ __forceinline__ void store_cut_es(uint8_t *p0, uint8_t *p1, uint32_t k, const Unit &u) {
-  typedef typename ElemType<ES>::type E;
-#pragma unroll
-  for (int e = 0; e < 16 / ES; ++e) {
-    const uint32_t byte = e * ES;
-    uint8_t *dst = byte < k ? p0 + byte : p1 + (byte - k);
-    *reinterpret_cast<E *>(dst) = unit_get<ES>(u, e);
-  }
-}
-__device__ __forceinline__ void store_cut(uint8_t *p0, uint8_t *p1, uint32_t k, uint32_t es_log2, u32x4 v) {
-  Unit u;
-  u.q = v;
-  switch (es_log2) {
-    case 0: store_cut_es<1>(p0, p1, k, u); break;
-    case 1: store_cut_es<2>(p0, p1, k, u); break;
-    case 2: store_cut_es<4>(p0, p1, k, u); break;
-    default: store_cut_es<8>(p0, p1, k, u); break;
-  }
-}
-
 // BUFST: the gather writes the image through buffer stores with the cache policy "sc0 sc1 nt"
 // (write-through, streaming).  Measured on a plain copy of this shape: 6.25 TB/s against 6.07 TB/s with
 // "nt" global stores and 5.88 TB/s with plain ones.  The buffer form is used because the compiler has an
@@ -546,8 +591,8 @@ __device__ __forceinline__ void lean_chunk(const LeanArgs &a, const MoveArgs &ma
       // the end of that run and the other 16-k from the start of the next one; on the
       // gather side both come from 16-byte loads that lie wholly inside their runs
       // (the last 16 bytes of the one, the first 16 of the other), so nothing outside
-      // the view is read; on the scatter side the two parts are stored element by
-      // element.
+      // the view is read; on the scatter side each part is stored as at most four pieces
+      // of 8, 4, 2 and 1 bytes, exactly the bytes of the view.
       uint8_t *p[UNROLL];
       uint32_t cut[UNROLL];  // k, or 0 if the unit is not cut
       u32x4 w[UNROLL];       // gather: the first 16 bytes of the next run, for cut units
@@ -592,7 +637,7 @@ __device__ __forceinline__ void lean_chunk(const LeanArgs &a, const MoveArgs &ma
         } else if (cut[i] == 0) {
           st16_any<NTS>(p[i], v[i]);
         } else {
-          store_cut(p[i], p[i] + cut[i] + (r.pitch - r.run), cut[i], r.kind >> 8, v[i]);
+          store_cut(p[i], p[i] + cut[i] + (r.pitch - r.run), cut[i], v[i]);
         }
       }
     }
