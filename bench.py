@@ -62,6 +62,9 @@ def main() -> int:
     ap.add_argument("--no-file", action="store_true", help="skip the file-tier leg")
     ap.add_argument("--file-dir", default="/tmp", help="where the file-tier leg writes its image")
     ap.add_argument("--file-threads", type=int, default=8)
+    ap.add_argument("--manifest", default=None, metavar="FILE",
+                    help="where the run's input manifest goes (seed, shard table, realised sizes and offsets); "
+                         "default gpurun_out/manifest_<workload>.json, '-' = none")
     ap.add_argument("--files", type=int, default=20, help="--experiments: files the rank's state is split over")
     ap.add_argument("--file-engine", default="threads", choices=["threads", "uring"],
                     help="writers of the file tier: pwrite threads, or one thread with that many writes in flight "
@@ -114,6 +117,23 @@ def main() -> int:
     payload = info["payload_bytes"]
     stream = torch.cuda.current_stream().cuda_stream
     ds.ds_config_set("variant", args.variant)
+
+    # what this run's input was, so that it can be rebuilt: generator, seed, and the shard table as realised
+    manifest_path = args.manifest or os.path.join(ROOT, "gpurun_out", f"manifest_{args.workload}.json")
+    if manifest_path != "-":
+        try:
+            os.makedirs(os.path.dirname(os.path.abspath(manifest_path)), exist_ok=True)
+            with open(manifest_path, "w") as f:
+                json.dump({"workload": args.workload, "generator": f"workloads.by_name({args.workload!r})",
+                           "name": w.name, "seed": w.seed, "align": w.align, "shards": n, "payload_bytes": payload,
+                           "image_bytes": total, "arena_bytes": int(w.arena.size), "notes": w.notes,
+                           "table": [{"name": sh.name, "dtype": sh.dtype, "shape": list(sh.shape),
+                                      "strides": list(sh.strides), "byte_offset": sh.byte_offset,
+                                      "tensor_id": sh.tensor_id, "file_offset": int(descs[i].file_offset),
+                                      "nbytes": sh.nbytes} for i, sh in enumerate(w.shards)]}, f)
+        except OSError as e:
+            log(f"[bench] manifest not written: {e}")
+            manifest_path = "-"
 
     if args.kernels_only:
         image_dev = torch.empty(max(total, 16), dtype=torch.uint8, device=dev)
@@ -737,6 +757,7 @@ def main() -> int:
             "stage_slots": args.stage_slots, "copy_streams": args.copy_streams,
             "first_launch_bytes": args.first_launch_bytes,
             "workgroup_chunk_bytes": info["chunk_bytes"],
+            "manifest": None if manifest_path == "-" else os.path.relpath(manifest_path, ROOT),
         },
         "roofline": roofline,
         "cpu_baseline": cpu_baseline,
