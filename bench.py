@@ -64,7 +64,7 @@ def main() -> int:
     ap.add_argument("--file-threads", type=int, default=8)
     ap.add_argument("--manifest", default=None, metavar="FILE",
                     help="where the run's input manifest goes (seed, shard table, realised sizes and offsets); "
-                         "default gpurun_out/manifest_<workload>.json, '-' = none")
+                         "default bench_out/manifest_<workload>.json, '-' = none")
     ap.add_argument("--files", type=int, default=20, help="--experiments: files the rank's state is split over")
     ap.add_argument("--file-engine", default="threads", choices=["threads", "uring"],
                     help="writers of the file tier: pwrite threads, or one thread with that many writes in flight "
@@ -119,7 +119,7 @@ def main() -> int:
     ds.ds_config_set("variant", args.variant)
 
     # what this run's input was, so that it can be rebuilt: generator, seed, and the shard table as realised
-    manifest_path = args.manifest or os.path.join(ROOT, "gpurun_out", f"manifest_{args.workload}.json")
+    manifest_path = args.manifest or os.path.join(ROOT, "bench_out", f"manifest_{args.workload}.json")
     if manifest_path != "-":
         try:
             os.makedirs(os.path.dirname(os.path.abspath(manifest_path)), exist_ok=True)
