@@ -716,7 +716,8 @@ def main() -> int:
                     evs, cks = [], []
                     for pl, path in zip(file_plans, paths):
                         ev = ds.ds_snapshot_async(eng2, pl, stream)
-                        ck = ds.ds_ckpt_create(path, pl, ds.DS_FILE_DIRECT)
+                        ck = ds.ds_ckpt_create(path, pl, ds.DS_FILE_DIRECT |
+                                               (ds.DS_FILE_URING if args.file_engine == "uring" else 0))
                         ds.ds_ckpt_flush_snapshot(ck, ev, max(1, args.file_threads // 2))
                         evs.append(ev)
                         cks.append(ck)
