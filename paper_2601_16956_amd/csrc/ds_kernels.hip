@@ -431,13 +431,24 @@ __device__ __forceinline__ void general_chunk(const MoveArgs &a, uint64_t c, uin
     };
     for (uint32_t base = 0; base < n_units; base += NT * UNROLL) {
       enum : uint32_t { kNone = 0, kFast = 1, kZero = 2, kCut = 3, kSlow = 4 };
+      // A thread's i-th unit of the pass.  Each block of NT units is rotated by 9 more than the one before:
+      // tensors of one size put their cut units at a fixed period, and periods that divide NT (slots of 512
+      // bytes to 4 KiB) would otherwise give all of them to the same few threads, four each.
+      auto unit_of = [&](int i) { return base + i * NT + ((tid + 9u * i) & (NT - 1)); };
       u32x4 v[UNROLL];
       uint8_t *ip[UNROLL];   // the unit in the image buffer
       uint8_t *sp[UNROLL];   // kFast: the unit in the tensor
       uint32_t how[UNROLL];
+      // Gather: the thread's first cut unit of the pass (see below) travels with the others: its two loads are
+      // issued in the load phase and it is stored in the store phase.  (The scatter has no registers to spare
+      // for that: it would drop to three wavefronts per SIMD.)
+      bool cut_held = false;
+      u32x4 cut_a, cut_b;
+      uint32_t cut_k = 0;
+      uint8_t *cut_ip = nullptr;
 #pragma unroll
       for (int i = 0; i < UNROLL; ++i) {
-        const uint32_t j = base + i * NT + tid;
+        const uint32_t j = unit_of(i);
         how[i] = kNone;
         if (j < n_units) {
           uint32_t p;
@@ -452,16 +463,28 @@ __device__ __forceinline__ void general_chunk(const MoveArgs &a, uint64_t c, uin
             const uint32_t n_outer = g->meta[p] & 0xFFu;
             if (n_outer <= 1) {
               // the run the unit starts in: the whole payload, or one row of a 2-D view
-              uint64_t L = nbytes, row = 0, col = b;
+              uint64_t L = nbytes, row = 0, col = b, pitch = 0;
               if (n_outer) {
                 L = g->run[p];
+                pitch = g->stride0[p];
                 divmod(b, L, row, col);
               }
               if (L >= 16) {
-                how[i] = kCut;
+                const uint64_t run0 = g->src[p] + row * pitch;
                 if (col + 16 <= L) {
-                  sp[i] = reinterpret_cast<uint8_t *>(g->src[p] + (n_outer ? row * g->stride0[p] : 0) + col);
+                  sp[i] = reinterpret_cast<uint8_t *>(run0 + col);
                   how[i] = kFast;
+                } else if (PACK && !cut_held) {
+                  cut_held = true;
+                  how[i] = kNone;
+                  cut_k = (uint32_t)(L - col);
+                  cut_ip = ip[i];
+                  cut_a = ld16_any<NTL>(reinterpret_cast<uint8_t *>(run0 + L - 16));
+                  cut_b = u32x4{0, 0, 0, 0};
+                  // unless the payload ends with this run, the unit goes on in the next one
+                  if (b + cut_k < nbytes) cut_b = ld16_any<NTL>(reinterpret_cast<uint8_t *>(run0 + pitch));
+                } else {
+                  how[i] = kCut;
                 }
               }
             }
@@ -478,17 +501,19 @@ __device__ __forceinline__ void general_chunk(const MoveArgs &a, uint64_t c, uin
           st16_aligned<NTS>(ip[i], u32x4{0, 0, 0, 0});
         }
       }
+      if (PACK && cut_held) st16_aligned<NTS>(cut_ip, splice(cut_a, cut_b, 16u - cut_k));
       // Units cut by the end of a run of at least 16 bytes: the first k bytes end that run, the rest start the
       // next one, or are padding when the payload ends there.  As in the lean path the gather takes both
       // parts with 16-byte loads that lie wholly inside their runs and splices them; the scatter stores each
-      // part as at most four pieces of 8, 4, 2 and 1 bytes.  (Located again: keeping every unit's position
-      // would cost registers.)
+      // part as at most four pieces of 8, 4, 2 and 1 bytes.  A thread's first cut unit went with the phases
+      // above; here follow its further ones, if any, one after the other (located again: keeping every unit's
+      // position would cost registers).
 #pragma unroll
       for (int i = 0; i < UNROLL; ++i)
-        if (how[i] == kCut) {  // at most a few per pass and seldom two in one thread: one after the other
+        if (how[i] == kCut) {
           uint32_t p;
           uint64_t x, b;
-          locate(base + i * NT + tid, p, x, b);
+          locate(unit_of(i), p, x, b);
           const uint64_t nbytes = g->nbytes[p];
           const uint32_t meta = g->meta[p];
           uint64_t L = nbytes, row = 0, col = b, pitch = 0;
@@ -517,7 +542,7 @@ __device__ __forceinline__ void general_chunk(const MoveArgs &a, uint64_t c, uin
         if (how[i] == kSlow) {
           uint32_t p;
           uint64_t x, b;
-          locate(base + i * NT + tid, p, x, b);
+          locate(unit_of(i), p, x, b);
           move_unit<PACK, NTL, NTS>(a.tiles + bt + p, x - b, x, ip[i]);
         }
     }
