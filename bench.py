@@ -45,6 +45,65 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
+def microbench(ds, torch, dev, args) -> int:
+    """Gather / scatter rates (read+write GB/s of payload, median of 15 launches) on tables made to isolate
+    one path of the kernel: (a) contiguous u8 tensors of one size each at 512-byte alignment, so that every
+    16 KiB chunk holds tile boundaries and takes the general path; (b) one 2-D u8 view per (row, pitch)
+    pair, which takes the lean row path.  The plain copy probe over the same number of bytes is the ceiling."""
+    stream = torch.cuda.current_stream().cuda_stream
+    ds.ds_config_set("variant", args.variant)
+    buf = torch.empty(3 << 30, dtype=torch.uint8, device=dev).random_(0, 255)
+
+    def timed(fn):
+        for _ in range(3):
+            fn()
+        torch.cuda.synchronize()
+        ts = []
+        for _ in range(15):
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            fn()
+            b.record()
+            ts.append((a, b))
+        torch.cuda.synchronize()
+        return sorted(x.elapsed_time(y) for x, y in ts)[7]
+
+    def run(tensors, align):
+        descs = ds.make_descs_from_tensors(tensors)
+        n = len(tensors)
+        total = ds.ds_layout_assign(descs, n, align)
+        plan = ds.ds_plan_create(descs, n, align, 0)
+        info = ds.ds_plan_info(plan)
+        img = torch.empty(total, dtype=torch.uint8, device=dev)
+        other = torch.empty(total, dtype=torch.uint8, device=dev)
+        p = timed(lambda: ds.ds_pack(plan, img.data_ptr(), 0, total, stream))
+        u = timed(lambda: ds.ds_unpack(plan, img.data_ptr(), 0, total, stream))
+        c = timed(lambda: ds.ds_copy_probe(other.data_ptr(), img.data_ptr(), total & ~15, stream))
+        ds.ds_plan_destroy(plan)
+        pay = info["payload_bytes"]
+        return {"payload_bytes": pay, "image_bytes": total, "chunks": info["n_chunks"],
+                "general_chunks": info["n_general_chunks"], "gather_GBps": round(2 * pay / p / 1e6),
+                "scatter_GBps": round(2 * pay / u / 1e6), "copy_probe_GBps": round(2 * (total & ~15) / c / 1e6)}
+
+    out = {"microbench": True, "unit": "GB/s read+write of payload", "variant": args.variant, "general_path": [],
+           "row_path": []}
+    out["contiguous_1GiB"] = run([buf[:1 << 30]], 4096)
+    for size in (12288, 12296, 1024, 1032, 208, 200):
+        pitch = (size + 511) // 512 * 512 + 512
+        n = (1 << 30) // pitch
+        r = run([buf[i * pitch + 3: i * pitch + 3 + size] for i in range(n)], 512)
+        out["general_path"].append({"tensor_bytes": size, "tensors": n, **r})
+        log(f"[microbench] general path, tensors of {size} B: {r['gather_GBps']} / {r['scatter_GBps']} GB/s")
+    for row, pitch in ((2048, 2304), (2048, 4096), (2048, 8192), (2048, 8256), (2048, 16384), (2048, 65536), (2048, 131072),
+                       (5504, 22016), (5504, 22528), (5504, 7552), (2752, 11008), (512, 2048)):
+        rows = min((1 << 30) // row, ((3 << 30) - row) // pitch)
+        r = run([torch.as_strided(buf, (rows, row), (pitch, 1))], 4096)
+        out["row_path"].append({"row_bytes": row, "pitch_bytes": pitch, "rows": rows, **r})
+        log(f"[microbench] rows of {row} B at pitch {pitch} B: {r['gather_GBps']} / {r['scatter_GBps']} GB/s")
+    print(json.dumps(out), flush=True)
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -83,6 +142,10 @@ def main() -> int:
                     help="stop after the timed region (so that a kernel trace holds the timed launches only)")
     ap.add_argument("--kernels-only", action="store_true",
                     help="only gather, scatter and the copy probe, 5 launches each (for counter runs)")
+    ap.add_argument("--microbench", action="store_true",
+                    help="instead of the workload: gather and scatter rates on synthetic tables that isolate one path of "
+                         "the kernel each (every chunk general with tensors of one size; one 2-D view per row length "
+                         "and pitch), one JSON object")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         log("bench.py: this build is the one-GPU hot path; it has no multi-GPU leg (run with --gpus 1).")
@@ -98,6 +161,8 @@ def main() -> int:
     assert torch.cuda.is_available(), "needs the MI355X"
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+    if args.microbench:
+        return microbench(ds, torch, dev, args)
     props = torch.cuda.get_device_properties(dev)
     cores = len(os.sched_getaffinity(0))
     cores = min(cores, int(os.environ.get("OMP_NUM_THREADS", cores)))
