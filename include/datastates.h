@@ -66,6 +66,7 @@ typedef enum ds_dtype { DS_F32 = 0, DS_BF16 = 1, DS_F16 = 2, DS_I64 = 3, DS_U8 =
 #define DS_ESTATE (-9)   /* call not valid in this state (e.g. release of a chunk never handed out) */
 #define DS_EIO (-10)     /* a file operation failed; see ds_last_errno()           */
 #define DS_EFORMAT (-11) /* not a checkpoint file of this format, or a damaged one   */
+#define DS_EFAULT (-12)  /* DS_PLAN_CHECK_MEMORY: a shard is not inside one device allocation */
 
 /*
  * One shard: a view into device memory plus its place in the file.
@@ -109,6 +110,11 @@ int ds_layout_assign(ds_shard_desc *desc, size_t n, uint64_t align, uint64_t *to
 #define DS_PLAN_STRICT 1u    /* reject holes larger than alignment padding (DS_EGAP)           */
 #define DS_PLAN_HOST_ONLY 2u /* validate and build tables on the host only; such a plan can be
                                 inspected but not passed to ds_pack/ds_unpack/ds_snapshot_async */
+#define DS_PLAN_CHECK_MEMORY 4u /* ask the runtime, for every non-empty shard, which allocation its
+                                base address lies in, and require every address of the view to be
+                                inside it (DS_EFAULT otherwise): a wrong descriptor is then an error
+                                here, not a memory fault in a kernel later.  Costs one runtime call
+                                per shard; not with DS_PLAN_HOST_ONLY */
 
 /*
  * Validates the table (any order of offsets; shards must be disjoint in the
@@ -119,7 +125,7 @@ int ds_layout_assign(ds_shard_desc *desc, size_t n, uint64_t align, uint64_t *to
  * themselves stay owned by the caller and must stay allocated while the plan
  * is used.  The plan is reused by every snapshot of the same shard set (Sec.
  * V-A1: what is set up once serves all later checkpoint requests).
- * Errors: DS_EINVAL, DS_EALIGN, DS_EOVERLAP, DS_EGAP, DS_ENOMEM, DS_EHIP.
+ * Errors: DS_EINVAL, DS_EALIGN, DS_EOVERLAP, DS_EGAP, DS_EFAULT, DS_ENOMEM, DS_EHIP.
  */
 int ds_plan_create(const ds_shard_desc *desc, size_t n, uint64_t align, uint32_t flags, ds_plan **out);
 

@@ -20,8 +20,9 @@ DS_OK, DS_NOT_READY, DS_EOF = 0, 1, 2
 DS_EINVAL, DS_EALIGN, DS_EOVERLAP, DS_EGAP, DS_ERANGE, DS_ENOMEM, DS_EHIP, DS_EBUSY, DS_ESTATE, DS_EIO = (
     -1, -2, -3, -4, -5, -6, -7, -8, -9, -10)
 DS_EFORMAT = -11
+DS_EFAULT = -12
 DS_FILE_DIRECT, DS_FILE_SYNC, DS_FILE_URING = 1, 2, 4
-DS_PLAN_STRICT, DS_PLAN_HOST_ONLY = 1, 2
+DS_PLAN_STRICT, DS_PLAN_HOST_ONLY, DS_PLAN_CHECK_MEMORY = 1, 2, 4
 DS_ENGINE_AUTO_RELEASE, DS_ENGINE_TRACE = 1, 2
 
 # every symbol include/datastates.h declares

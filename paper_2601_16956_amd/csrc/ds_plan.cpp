@@ -67,6 +67,24 @@ bool view_is_injective(const ds_shard_desc &d) {
   return true;
 }
 
+// DS_PLAN_CHECK_MEMORY: every address of a non-empty view, from its base to its last element's last byte,
+// must lie in the allocation the runtime reports for the base address.
+int view_in_one_allocation(const ds_shard_desc &d) {
+  unsigned __int128 last = 0;  // element index of the view's last element
+  for (uint32_t j = 0; j < d.ndim; ++j) last += (unsigned __int128)(uint64_t)(d.shape[j] - 1) * (uint64_t)d.strides[j];
+  const unsigned __int128 span = (last + 1) * (unsigned)ds_itemsize(d.dtype);
+  hipDeviceptr_t abase = nullptr;
+  size_t asize = 0;
+  if (hipMemGetAddressRange(&abase, &asize, (hipDeviceptr_t)d.base) != hipSuccess) {
+    (void)hipGetLastError();  // not memory the runtime knows: the error is reported through the return code
+    return DS_EFAULT;
+  }
+  const uintptr_t b = (uintptr_t)d.base, a = (uintptr_t)abase;
+  if (b < a || span > (unsigned __int128)asize || (unsigned __int128)(b - a) > (unsigned __int128)asize - span)
+    return DS_EFAULT;
+  return DS_OK;
+}
+
 // Device form of one non-empty shard: drop extents of 1, merge neighbouring
 // dimensions that are contiguous with each other (stride[j] == extent[j+1] *
 // stride[j+1]; this keeps the row-major order of the view), then split off the
@@ -168,6 +186,7 @@ const char *ds_strerror(int code) {
     case DS_ESTATE: return "call not valid in this state";
     case DS_EIO: return "a file operation failed (see ds_last_errno)";
     case DS_EFORMAT: return "not a checkpoint file of this format, or a damaged one";
+    case DS_EFAULT: return "a shard's addresses are not all inside one device allocation";
     default: return "unknown datastates status";
   }
 }
@@ -217,7 +236,8 @@ int ds_layout_assign(ds_shard_desc *desc, size_t n, uint64_t align, uint64_t *to
 
 int ds_plan_create(const ds_shard_desc *desc, size_t n, uint64_t align, uint32_t flags, ds_plan **out) {
   if ((!desc && n) || !out || !is_pow2(align) || align < 16) return DS_EINVAL;
-  if (flags & ~(DS_PLAN_STRICT | DS_PLAN_HOST_ONLY)) return DS_EINVAL;
+  if (flags & ~(DS_PLAN_STRICT | DS_PLAN_HOST_ONLY | DS_PLAN_CHECK_MEMORY)) return DS_EINVAL;
+  if ((flags & DS_PLAN_CHECK_MEMORY) && (flags & DS_PLAN_HOST_ONLY)) return DS_EINVAL;
   ds_plan *p = new (std::nothrow) ds_plan;
   if (!p) return DS_ENOMEM;
   int rc = DS_OK;
@@ -239,6 +259,10 @@ int ds_plan_create(const ds_shard_desc *desc, size_t n, uint64_t align, uint32_t
         for (uint32_t j = 0; j < d.ndim; ++j) bad_stride |= (d.shape[j] > 1 && d.strides[j] <= 0);
         if (bad_stride) { rc = DS_EINVAL; break; }
         if (!view_is_injective(d)) { rc = DS_EOVERLAP; break; }
+        if (flags & DS_PLAN_CHECK_MEMORY) {
+          rc = view_in_one_allocation(d);
+          if (rc != DS_OK) break;
+        }
       }
       DsManifestEntry &me = p->manifest[i];
       me.tensor_id = d.tensor_id;

@@ -256,6 +256,40 @@ def test_range_and_argument_errors_on_device_plan():
         dw.close()
 
 
+def test_plan_memory_check_turns_wrong_descriptors_into_errors():
+    """DS_PLAN_CHECK_MEMORY: a table whose views all lie inside their allocations is accepted and packs as
+    usual; views that run past the end of their allocation and a host address are refused
+    with DS_EFAULT at plan time -- nothing is launched on them."""
+    import torch
+    ds, orc, gu = _mods()
+    w = W.fragmentation(300, max_bytes=1 << 14, seed=8)
+    want, _, _ = gu.oracle_image(w)
+    dw = gu.DeviceWorkload(w, flags=ds.DS_PLAN_CHECK_MEMORY | ds.DS_PLAN_STRICT)
+    try:
+        assert gu.first_mismatch(dw.pack(), want) is None
+    finally:
+        dw.close()
+    small = torch.zeros(4096, dtype=torch.uint8, device="cuda")
+    host = np.zeros(4096, dtype=np.uint8)
+    cases = {
+        "runs past the end": Shard("x", "u8", (1 << 30,), (1,), 0, 0),              # 1 GiB claimed in a 4 KiB tensor
+        "rows run past the end": Shard("x", "f32", (1 << 20, 4), (1 << 12, 1), 0, 0),
+    }
+    for name, sh in cases.items():
+        print(f"[case] memory check: {name}", flush=True)
+        d = ds.make_descs([sh], small.data_ptr())
+        ds.ds_layout_assign(d, 1, 256)
+        with pytest.raises(ds.DsError) as e:
+            ds.ds_plan_create(d, 1, 256, ds.DS_PLAN_CHECK_MEMORY)
+        assert e.value.code == ds.DS_EFAULT, name
+        ds.ds_plan_destroy(ds.ds_plan_create(d, 1, 256, ds.DS_PLAN_HOST_ONLY))   # the table itself is well-formed
+    d = ds.make_descs([Shard("h", "u8", (4096,), (1,), 0, 0)], host.ctypes.data)
+    ds.ds_layout_assign(d, 1, 256)
+    with pytest.raises(ds.DsError) as e:
+        ds.ds_plan_create(d, 1, 256, ds.DS_PLAN_CHECK_MEMORY)
+    assert e.value.code == ds.DS_EFAULT
+
+
 def test_sizes_beyond_32_bits():
     """One contiguous shard of 5 GiB (offsets inside a tile beyond 2^32) and a 2-D
     view whose rows are longer than 2^31 bytes (the 64-bit index path of the

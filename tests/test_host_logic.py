@@ -119,6 +119,16 @@ def test_seven_dims_rejected():
     assert out.value is None                                      # untouched on failure
 
 
+def test_unknown_flags_and_memory_check_on_a_host_only_plan_are_rejected():
+    d = _descs([Shard("a", "u8", (64,), (1,), 0, 0)])
+    ds.ds_layout_assign(d, 1, 64)
+    out = ctypes.c_void_p()
+    for flags in (8, 0x100, ds.DS_PLAN_HOST_ONLY | ds.DS_PLAN_CHECK_MEMORY):
+        assert ds._lib.ds_plan_create(d, 1, 64, flags, ctypes.byref(out)) == ds.DS_EINVAL
+        assert out.value is None
+    assert "allocation" in ds.ds_strerror(ds.DS_EFAULT)
+
+
 def test_host_only_plan_cannot_be_packed():
     d = _descs([Shard("a", "u8", (64,), (1,), 0, 0)])
     ds.ds_layout_assign(d, 1, 64)
