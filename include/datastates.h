@@ -312,9 +312,9 @@ int ds_event_destroy(ds_event *ev);
  * `compute_stream`.  The caller then repeats, in file order:
  *   ds_restore_next_slot  -> a ring slot to fill with image bytes
  *                            [file_off, file_off+len) (e.g. read from the file)
- *   ds_restore_submit     -> the slot is copied to the device; when the chunks of
- *                            a staging slot are complete they are scattered into
- *                            the tensors
+ *   ds_restore_submit     -> the slot is copied to the device; every eight chunks
+ *                            (or stage_slot_bytes, if that is less) are scattered
+ *                            into the tensors while the next ones are copied
  * and finally ds_event_wait (host) or ds_event_wait_on_stream (a stream that is
  * to use the restored tensors), then ds_event_destroy.
  */

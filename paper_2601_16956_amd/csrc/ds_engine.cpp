@@ -56,6 +56,10 @@ struct ds_engine {
   uint64_t stage_slot_bytes = 0;  // image bytes per gather launch
   uint64_t first_launch_bytes = 0; // image bytes of the first gather launch of a snapshot
   uint32_t stage_slots = 0;
+  // a restore scatters staging in pieces of this many image bytes (a few copies' worth: the scatter of one
+  // piece then runs beside the copies of the next, and only the last, short one is left over at the end)
+  uint64_t restore_piece_bytes = 0;
+  uint32_t restore_pieces = 0;    // pieces of that size that staging holds
   uint32_t ring_slots = 0;
   int n_copy_streams = 1;
   hipStream_t pack_stream = nullptr;
@@ -451,6 +455,8 @@ int ds_engine_create(const ds_engine_opts *o, ds_engine **out) {
   g->first_launch_bytes = first;
   g->stage_slots = slots;
   g->stage_bytes = slot * slots;
+  g->restore_piece_bytes = 8 * chunk < slot ? 8 * chunk : slot;
+  g->restore_pieces = (uint32_t)(g->stage_bytes / g->restore_piece_bytes);
   g->ring_slots = (uint32_t)(ring_bytes / chunk);
   g->n_copy_streams = (int)ncs;
   hipError_t e = hipGetDevice(&g->device);
@@ -803,7 +809,7 @@ int ds_restore_begin(ds_engine *g, const ds_plan *plan, void *compute_stream, ds
         c.len = lo + g->chunk_bytes < T ? g->chunk_bytes : T - lo;
         ev->chunks.push_back(c);
       }
-      ev->group_done.assign((size_t)((T + g->stage_slot_bytes - 1) / g->stage_slot_bytes), nullptr);
+      ev->group_done.assign((size_t)((T + g->restore_piece_bytes - 1) / g->restore_piece_bytes), nullptr);
     } catch (const std::bad_alloc &) {
       rc = DS_ENOMEM;
     }
@@ -871,17 +877,17 @@ int ds_restore_submit(ds_event *ev, const void *host_ptr) {
   if (k >= ev->r_handed) return DS_ESTATE;
   DsChunk &c = ev->chunks[k];
   if (host_ptr != g->ring + (uint64_t)c.ring_slot * g->chunk_bytes) return DS_ESTATE;
-  const uint64_t S = g->stage_slot_bytes;
+  const uint64_t S = g->restore_piece_bytes;
   const size_t gi = (size_t)(c.file_off / S);
   const uint64_t glo = (uint64_t)gi * S;
   const uint64_t ghi = glo + S < ev->plan->total_bytes ? glo + S : ev->plan->total_bytes;
-  const uint32_t s = (uint32_t)(gi % g->stage_slots);
+  const uint32_t s = (uint32_t)(gi % g->restore_pieces);
   uint8_t *slot = g->stage + (uint64_t)s * S;
   // chunks alternate over the copy streams, as in a snapshot
   hipStream_t cs = g->copy_stream[k % (uint32_t)g->n_copy_streams];
   // the staging slot must have been scattered out by the group that used it before (a wait per chunk:
   // either stream may carry the group's first chunk; it costs nothing once the event has fired)
-  if (gi >= g->stage_slots) W_TRY(hipStreamWaitEvent(cs, ev->group_done[gi - g->stage_slots], 0));
+  if (gi >= g->restore_pieces) W_TRY(hipStreamWaitEvent(cs, ev->group_done[gi - g->restore_pieces], 0));
   W_TRY(hipMemcpyAsync(slot + (c.file_off - glo), host_ptr, c.len, hipMemcpyHostToDevice, cs));
   W_TRY(hipEventRecord(g->ring_done[c.ring_slot], cs));
   g->ring_busy[c.ring_slot] = 1;
