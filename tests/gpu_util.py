@@ -40,7 +40,9 @@ class DeviceWorkload:
             for i, off in enumerate(offsets):
                 self.descs[i].file_offset = off
             self.total = None
-        self.plan = ds.ds_plan_create(self.descs, self.n, w.align, flags)
+        # every plan of the GPU tests is made with the memory check: a generator or a test that describes memory
+        # it does not own is then an error here, not a fault in a kernel
+        self.plan = ds.ds_plan_create(self.descs, self.n, w.align, flags | ds.DS_PLAN_CHECK_MEMORY)
         self.info = ds.ds_plan_info(self.plan)
         if self.total is None:
             self.total = self.info["total_bytes"]
