@@ -176,7 +176,7 @@ def main() -> int:
     descs = ds.make_descs(w.shards, arena.data_ptr())
     total = ds.ds_layout_assign(descs, n, w.align)
     t0 = time.perf_counter()
-    plan = ds.ds_plan_create(descs, n, w.align, ds.DS_PLAN_STRICT)
+    plan = ds.ds_plan_create(descs, n, w.align, ds.DS_PLAN_STRICT | ds.DS_PLAN_CHECK_MEMORY)
     plan_ms = (time.perf_counter() - t0) * 1e3
     info = ds.ds_plan_info(plan)
     payload = info["payload_bytes"]
