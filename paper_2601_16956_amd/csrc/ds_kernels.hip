@@ -41,6 +41,7 @@
 // the described views is ever read or written.
 
 #include "ds_internal.h"
+#include "ds_splice.h"
 
 namespace {
 
@@ -298,23 +299,10 @@ __device__ __forceinline__ uint32_t wave_inclusive_scan(uint32_t x, uint32_t lan
 }
 
 // ---- units cut by the end of a run ------------------------------------------------------
-// bytes [s, s+16) of the 32 bytes a||b, 0 < s < 16
+// bytes [s, s+16) of the 32 bytes a||b, 0 < s < 16 (word selects and byte-aligns, see ds_splice.h)
 __device__ __forceinline__ u32x4 splice(u32x4 a, u32x4 b, uint32_t s) {
-  uint64_t x0 = a.x | ((uint64_t)a.y << 32), x1 = a.z | ((uint64_t)a.w << 32);
-  uint64_t x2 = b.x | ((uint64_t)b.y << 32), x3 = b.z | ((uint64_t)b.w << 32);
-  if (s >= 8) {
-    x0 = x1;
-    x1 = x2;
-    x2 = x3;
-    s -= 8;
-  }
-  uint64_t r0 = x0, r1 = x1;
-  if (s) {
-    const uint32_t sh = 8 * s;
-    r0 = (x0 >> sh) | (x1 << (64 - sh));
-    r1 = (x1 >> sh) | (x2 << (64 - sh));
-  }
-  return u32x4{(uint32_t)r0, (uint32_t)(r0 >> 32), (uint32_t)r1, (uint32_t)(r1 >> 32)};
+  const DsWords4 r = ds_splice_words(DsWords4{{a.x, a.y, a.z, a.w}}, DsWords4{{b.x, b.y, b.z, b.w}}, s);
+  return u32x4{r.w[0], r.w[1], r.w[2], r.w[3]};
 }
 
 // the low n < 16 bytes of v to p (any alignment), as one store each of 8, 4, 2 and 1 bytes as n has those bits
@@ -820,22 +808,28 @@ extern "C" int ds_copy_probe(void *dst_dev, const void *src_dev, uint64_t nbytes
   return DS_OK;
 }
 
-int ds_launch_move(const ds_plan *plan, bool pack, uint8_t *img, uint64_t img_lo, uint64_t img_hi,
-                   uint32_t grid_limit, hipStream_t stream) {
+namespace {
+
+// The plan's tables in device memory: the plan's own copy, or the one ds_pack_noalloc keeps in static memory.
+struct DeviceTables {
+  const DsTile *tiles;
+  const uint64_t *tile_off;
+  const uint32_t *first_tile;
+  const DsChunkRec *recs;
+};
+
+int launch_move_with(const ds_plan *plan, const DeviceTables &tb, bool pack, uint8_t *img, uint64_t img_lo,
+                     uint64_t img_hi, uint32_t grid_limit, hipStream_t stream) {
   const uint32_t lg = plan->chunk_log2;
   const uint64_t C = (uint64_t)1 << lg;
   const uint64_t n_total = plan->n_chunks();
   if (img_hi > plan->total_bytes || img_lo >= img_hi) return DS_ERANGE;
-  // the tables live on the device the plan was made on: a launch from another one would read them remotely
-  int dev = -1;
-  DS_HIP_TRY(hipGetDevice(&dev));
-  if (dev != plan->device) return DS_ESTATE;
   // whole chunks inside the range: one work item each, lean or general by their record ...
   uint64_t w_lo = (img_lo + C - 1) >> lg;
   uint64_t w_hi = img_hi >> lg;
   if (img_hi == plan->total_bytes) w_hi = n_total;  // the last chunk may be short; its record says 'general' then
   LeanArgs la;
-  la.recs = plan->d_recs;
+  la.recs = tb.recs;
   la.img = img;
   la.img_lo = img_lo;
   la.chunk_log2 = lg;
@@ -844,9 +838,9 @@ int ds_launch_move(const ds_plan *plan, bool pack, uint8_t *img, uint64_t img_lo
   la.xcd_span = ds_cfg_variant() == 3 ? 0 : (la.n_chunks + 7) / 8;
   // ... and the one or two chunks cut by the ends of the range, clipped by the general path
   MoveArgs ma;
-  ma.tiles = plan->d_tiles;
-  ma.tile_off = plan->d_tile_off;
-  ma.first_tile = plan->d_first_tile;
+  ma.tiles = tb.tiles;
+  ma.tile_off = tb.tile_off;
+  ma.first_tile = tb.first_tile;
   ma.img = img;
   ma.img_lo = img_lo;
   ma.img_hi = img_hi;
@@ -875,4 +869,16 @@ int ds_launch_move(const ds_plan *plan, bool pack, uint8_t *img, uint64_t img_lo
   // default: non-temporal accesses, and the lean gather writes the image with "sc0 sc1 nt" buffer stores
   return pack ? launch_move<true, true, true, true>(lg, la, ma, grid_limit, stream)
               : launch_move<false, true, true, false>(lg, la, ma, grid_limit, stream);
+}
+
+}  // namespace
+
+int ds_launch_move(const ds_plan *plan, bool pack, uint8_t *img, uint64_t img_lo, uint64_t img_hi,
+                   uint32_t grid_limit, hipStream_t stream) {
+  // the tables live on the device the plan was made on: a launch from another one would read them remotely
+  int dev = -1;
+  DS_HIP_TRY(hipGetDevice(&dev));
+  if (dev != plan->device) return DS_ESTATE;
+  const DeviceTables tb = {plan->d_tiles, plan->d_tile_off, plan->d_first_tile, plan->d_recs};
+  return launch_move_with(plan, tb, pack, img, img_lo, img_hi, grid_limit, stream);
 }

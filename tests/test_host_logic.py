@@ -208,3 +208,33 @@ def test_plain_c_program_uses_the_header_and_the_library(tmp_path):
     assert floats[128 + 20 * 3: 128 + 20 * 3 + 3].tolist() == [7 + 48 * 3, 8 + 48 * 3, 9 + 48 * 3]
     assert floats[3072 // 4] == 5.0
     assert len(open(ckpt, "rb").read()) == 3328 + 24 + 3 * 80 + 3 * 32 + 64
+
+
+def test_splice_of_the_kernels_on_the_host(tmp_path):
+    """csrc/ds_splice.h, the routine every unit cut by the end of a run goes through in the kernels, compiled
+    unchanged for the host: bytes [s, s+16) of a || b for every s, against plain slicing of the 32 bytes; and
+    the byte-align primitive against its definition on the eight bytes lo || hi."""
+    import shutil
+    import subprocess
+    if shutil.which("g++") is None:
+        pytest.skip("no g++ here")
+    so = str(tmp_path / "splice_host.so")
+    subprocess.run(["g++", "-O2", "-Wall", "-Werror", "-fPIC", "-shared", "-I",
+                    os.path.join(ROOT, "paper_2601_16956_amd", "csrc"),
+                    os.path.join(ROOT, "tests", "c_abi", "splice_host.cpp"), "-o", so], check=True)
+    lib = ctypes.CDLL(so)
+    lib.align_bytes_host.restype = ctypes.c_uint32
+    lib.align_bytes_host.argtypes = [ctypes.c_uint32] * 3
+    rng = np.random.default_rng(7)
+    patterns = [bytes(range(32)), bytes(range(255, 223, -1)), b"\xff" * 32, b"\x00" * 16 + b"\xff" * 16,
+                b"\x80" * 32] + [rng.integers(0, 256, 32, dtype=np.uint8).tobytes() for _ in range(200)]
+    out = (ctypes.c_ubyte * 16)()
+    for both in patterns:
+        a = (ctypes.c_ubyte * 16).from_buffer_copy(both[:16])
+        b = (ctypes.c_ubyte * 16).from_buffer_copy(both[16:])
+        for s in range(16):
+            lib.splice_host(a, b, s, out)
+            assert bytes(out) == both[s:s + 16], (both.hex(), s, bytes(out).hex())
+        lo, hi = int.from_bytes(both[0:4], "little"), int.from_bytes(both[4:8], "little")
+        for r in range(4):
+            assert lib.align_bytes_host(hi, lo, r) == int.from_bytes(both[r:r + 4], "little")
