@@ -67,6 +67,7 @@ typedef enum ds_dtype { DS_F32 = 0, DS_BF16 = 1, DS_F16 = 2, DS_I64 = 3, DS_U8 =
 #define DS_EIO (-10)     /* a file operation failed; see ds_last_errno()           */
 #define DS_EFORMAT (-11) /* not a checkpoint file of this format, or a damaged one   */
 #define DS_EFAULT (-12)  /* DS_PLAN_CHECK_MEMORY: a shard is not inside one device allocation */
+#define DS_ETOOBIG (-13) /* ds_pack_noalloc: the plan's tables do not fit the static table memory */
 
 /*
  * One shard: a view into device memory plus its place in the file.
@@ -179,6 +180,28 @@ int ds_pack(const ds_plan *plan, void *dst_dev, uint64_t img_lo, uint64_t img_hi
  * never cut).  No other byte of the tensors' memory is written.
  */
 int ds_unpack(const ds_plan *plan, const void *src_dev, uint64_t img_lo, uint64_t img_hi, void *stream);
+
+/*
+ * ds_pack for callers that cannot allocate device memory: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same result
+ * as ds_pack, byte for byte; the difference is where the kernel finds the
+ * plan's tables.  ds_pack reads them from the device allocation ds_plan_create
+ * made; this call copies them (on `stream`, ahead of the kernel) into a static
+ * device array of DS_PACK_NOALLOC_TABLE_BYTES that the library holds on every
+ * GPU it runs on until the process ends, and calls neither hipMalloc nor
+ * hipFree nor anything else that allocates.  `plan` may therefore be a
+ * DS_PLAN_HOST_ONLY plan, whose creation touches no device either.
+ * Limit: the tables (128 bytes per non-empty shard, 36 bytes per work-group
+ * chunk of the image, i.e. about 2.3 KiB per MiB of image) must fit the array:
+ * an image of about 1.7 GB with few shards does, DS_ETOOBIG otherwise
+ * (returned before anything is enqueued).  All calls on one GPU share the one
+ * array and it keeps the last call's tables: calls on the same stream are
+ * ordered by it, calls that may overlap on one GPU (different streams, or
+ * different threads) race and are the caller's to serialise.  Arguments and
+ * the other errors as for ds_pack; the current device is the one that runs it.
+ */
+#define DS_PACK_NOALLOC_TABLE_BYTES (4u << 20)
+int ds_pack_noalloc(const ds_plan *plan, void *dst_dev, uint64_t img_lo, uint64_t img_hi, void *stream);
 
 /* ---- the snapshot engine (Sec. V-A1 pre-pinned reused pool, Sec. V-A2 lazy
  *      capture, Sec. V-A4 chunked streaming, Sec. V-C dedicated streams) ----- */

@@ -21,6 +21,8 @@ DS_EINVAL, DS_EALIGN, DS_EOVERLAP, DS_EGAP, DS_ERANGE, DS_ENOMEM, DS_EHIP, DS_EB
     -1, -2, -3, -4, -5, -6, -7, -8, -9, -10)
 DS_EFORMAT = -11
 DS_EFAULT = -12
+DS_ETOOBIG = -13
+DS_PACK_NOALLOC_TABLE_BYTES = 4 << 20
 DS_FILE_DIRECT, DS_FILE_SYNC, DS_FILE_URING = 1, 2, 4
 DS_PLAN_STRICT, DS_PLAN_HOST_ONLY, DS_PLAN_CHECK_MEMORY = 1, 2, 4
 DS_ENGINE_AUTO_RELEASE, DS_ENGINE_TRACE = 1, 2
@@ -37,7 +39,7 @@ EXPORTS = [
     "ds_plan_shard_shape", "ds_ckpt_create", "ds_ckpt_flush_snapshot", "ds_ckpt_write_region", "ds_ckpt_append",
     "ds_ckpt_finish", "ds_ckpt_open", "ds_ckpt_close", "ds_ckpt_layout_info", "ds_ckpt_tensor_info",
     "ds_ckpt_object_at", "ds_ckpt_object_read", "ds_ckpt_matches_plan", "ds_ckpt_restore", "ds_event_trace",
-    "ds_image_diff",
+    "ds_image_diff", "ds_pack_noalloc",
 ]
 
 
@@ -157,6 +159,7 @@ def _load() -> ctypes.CDLL:
         "ds_plan_shard": ([vp, sz, P(u64), P(u32), P(u64), P(u64)], ctypes.c_int),
         "ds_pack": ([vp, vp, u64, u64, vp], ctypes.c_int),
         "ds_unpack": ([vp, vp, u64, u64, vp], ctypes.c_int),
+        "ds_pack_noalloc": ([vp, vp, u64, u64, vp], ctypes.c_int),
         "ds_engine_create": ([P(ds_engine_opts), P(vp)], ctypes.c_int),
         "ds_engine_destroy": ([vp], ctypes.c_int),
         "ds_snapshot_async": ([vp, vp, vp, P(vp)], ctypes.c_int),
@@ -299,6 +302,10 @@ def ds_plan_shard(plan: int, i: int) -> Tuple[int, int, int, int]:
 
 def ds_pack(plan: int, dst_dev: int, img_lo: int, img_hi: int, stream: int = 0) -> None:
     _check(_lib.ds_pack(plan, dst_dev, img_lo, img_hi, stream), "ds_pack")
+
+
+def ds_pack_noalloc(plan: int, dst_dev: int, img_lo: int, img_hi: int, stream: int = 0) -> None:
+    _check(_lib.ds_pack_noalloc(plan, dst_dev, img_lo, img_hi, stream), "ds_pack_noalloc")
 
 
 def ds_unpack(plan: int, src_dev: int, img_lo: int, img_hi: int, stream: int = 0) -> None:

@@ -40,6 +40,8 @@
 // for runs shorter than 16 bytes, moved element by element, so no byte outside
 // the described views is ever read or written.
 
+#include <mutex>
+
 #include "ds_internal.h"
 #include "ds_splice.h"
 
@@ -881,4 +883,71 @@ int ds_launch_move(const ds_plan *plan, bool pack, uint8_t *img, uint64_t img_lo
   if (dev != plan->device) return DS_ESTATE;
   const DeviceTables tb = {plan->d_tiles, plan->d_tile_off, plan->d_first_tile, plan->d_recs};
   return launch_move_with(plan, tb, pack, img, img_lo, img_hi, grid_limit, stream);
+}
+
+// ---- ds_pack for callers that cannot allocate ----------------------------------------------------
+// The gather reads the plan's tables from device memory; ds_plan_create puts them into an allocation of
+// its own.  Here they go into a static device array instead, so that neither the plan (made with
+// DS_PLAN_HOST_ONLY) nor the call allocates device memory.  Every device the library runs on holds its own
+// copy of the array, at its own address, until the process ends.
+namespace {
+
+constexpr size_t kScratchBytes = DS_PACK_NOALLOC_TABLE_BYTES;
+static __device__ __align__(256) uint8_t scratch[kScratchBytes];
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mu;
+uint8_t *g_scratch_ptr[kMaxDevices];  // device address of `scratch` on device d, once asked for
+
+// The array's address on the current device (`dev`).  In host code the array's name is only a handle for
+// this lookup, never an address a kernel or a copy could use.
+int scratch_on_device(int dev, uint8_t **out) {
+  if (dev < 0 || dev >= kMaxDevices) return DS_EINVAL;
+  std::lock_guard<std::mutex> lk(g_scratch_mu);
+  if (!g_scratch_ptr[dev]) {
+    void *p = nullptr;
+    DS_HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+    if (!p) return DS_EINVAL;
+    g_scratch_ptr[dev] = (uint8_t *)p;
+  }
+  *out = g_scratch_ptr[dev];
+  return DS_OK;
+}
+
+inline size_t round_up_128(size_t x) { return (x + 127) & ~(size_t)127; }
+
+}  // namespace
+
+extern "C" int ds_pack_noalloc(const ds_plan *plan, void *dst_dev, uint64_t img_lo, uint64_t img_hi, void *stream) {
+  if (!plan) return DS_EINVAL;
+  if (img_lo > img_hi || img_hi > plan->total_bytes || ((img_lo | img_hi) & 15)) return DS_ERANGE;
+  // the tables, laid out one behind the other as in a plan's own device copy
+  const size_t b_tiles = plan->tiles.size() * sizeof(DsTile);
+  const size_t b_off = round_up_128(plan->tile_off.size() * sizeof(uint64_t));
+  const size_t b_first = round_up_128(plan->first_tile.size() * sizeof(uint32_t));
+  const size_t b_recs = round_up_128(plan->recs.size() * sizeof(DsChunkRec));
+  if (b_tiles + b_off + b_first + b_recs > kScratchBytes) return DS_ETOOBIG;
+  if (img_lo == img_hi) return DS_OK;
+  if (!dst_dev || ((uintptr_t)dst_dev & 15)) return DS_EINVAL;
+  int dev = -1;
+  DS_HIP_TRY(hipGetDevice(&dev));
+  uint8_t *base = nullptr;
+  const int rc = scratch_on_device(dev, &base);
+  if (rc != DS_OK) return rc;
+  // Copies and kernel on the caller's stream: they run behind whatever that stream still has to do with the
+  // array (an earlier call's kernel).  Every entry the kernel reads is written here first, so nothing of an
+  // earlier call's tables, which stay in the array, needs clearing.  The host tables belong to the plan, which
+  // the caller keeps until the work has run.
+  hipStream_t st = (hipStream_t)stream;
+  if (b_tiles) DS_HIP_TRY(hipMemcpyAsync(base, plan->tiles.data(), b_tiles, hipMemcpyHostToDevice, st));
+  DS_HIP_TRY(hipMemcpyAsync(base + b_tiles, plan->tile_off.data(), plan->tile_off.size() * sizeof(uint64_t),
+                            hipMemcpyHostToDevice, st));
+  DS_HIP_TRY(hipMemcpyAsync(base + b_tiles + b_off, plan->first_tile.data(),
+                            plan->first_tile.size() * sizeof(uint32_t), hipMemcpyHostToDevice, st));
+  DS_HIP_TRY(hipMemcpyAsync(base + b_tiles + b_off + b_first, plan->recs.data(),
+                            plan->recs.size() * sizeof(DsChunkRec), hipMemcpyHostToDevice, st));
+  const DeviceTables tb = {(const DsTile *)base, (const uint64_t *)(base + b_tiles),
+                           (const uint32_t *)(base + b_tiles + b_off),
+                           (const DsChunkRec *)(base + b_tiles + b_off + b_first)};
+  return launch_move_with(plan, tb, true, (uint8_t *)dst_dev, img_lo, img_hi, 0, st);
 }

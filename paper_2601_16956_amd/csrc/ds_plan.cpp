@@ -187,6 +187,7 @@ const char *ds_strerror(int code) {
     case DS_EIO: return "a file operation failed (see ds_last_errno)";
     case DS_EFORMAT: return "not a checkpoint file of this format, or a damaged one";
     case DS_EFAULT: return "a shard's addresses are not all inside one device allocation";
+    case DS_ETOOBIG: return "the plan's tables do not fit the static table memory of ds_pack_noalloc";
     default: return "unknown datastates status";
   }
 }
