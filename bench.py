@@ -54,19 +54,21 @@ def microbench(ds, torch, dev, args) -> int:
     ds.ds_config_set("variant", args.variant)
     buf = torch.empty(3 << 30, dtype=torch.uint8, device=dev).random_(0, 255)
 
+    reps = max(1, args.reps)
+
     def timed(fn):
-        for _ in range(3):
+        for _ in range(min(3, reps)):
             fn()
         torch.cuda.synchronize()
         ts = []
-        for _ in range(15):
+        for _ in range(reps):
             a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             a.record()
             fn()
             b.record()
             ts.append((a, b))
         torch.cuda.synchronize()
-        return sorted(x.elapsed_time(y) for x, y in ts)[7]
+        return sorted(x.elapsed_time(y) for x, y in ts)[len(ts) // 2]
 
     def run(tensors, align):
         descs = ds.make_descs_from_tensors(tensors)
@@ -87,8 +89,13 @@ def microbench(ds, torch, dev, args) -> int:
 
     out = {"microbench": True, "unit": "GB/s read+write of payload", "variant": args.variant, "general_path": [],
            "row_path": []}
-    out["contiguous_1GiB"] = run([buf[:1 << 30]], 4096)
+    # --tables general:200,rows:5504x22016 limits the run to those tables (for counter runs, with --reps)
+    want = set(args.tables.split(",")) if args.tables else None
+    if want is None or "contiguous" in want:
+        out["contiguous_1GiB"] = run([buf[:1 << 30]], 4096)
     for size in (12288, 12296, 1024, 1032, 208, 200):
+        if want is not None and f"general:{size}" not in want:
+            continue
         pitch = (size + 511) // 512 * 512 + 512
         n = (1 << 30) // pitch
         r = run([buf[i * pitch + 3: i * pitch + 3 + size] for i in range(n)], 512)
@@ -96,6 +103,8 @@ def microbench(ds, torch, dev, args) -> int:
         log(f"[microbench] general path, tensors of {size} B: {r['gather_GBps']} / {r['scatter_GBps']} GB/s")
     for row, pitch in ((2048, 2304), (2048, 4096), (2048, 8192), (2048, 8256), (2048, 16384), (2048, 65536), (2048, 131072),
                        (5504, 22016), (5504, 22528), (5504, 7552), (2752, 11008), (512, 2048)):
+        if want is not None and f"rows:{row}x{pitch}" not in want:
+            continue
         rows = min((1 << 30) // row, ((3 << 30) - row) // pitch)
         r = run([torch.as_strided(buf, (rows, row), (pitch, 1))], 4096)
         out["row_path"].append({"row_bytes": row, "pitch_bytes": pitch, "rows": rows, **r})
@@ -146,6 +155,9 @@ def main() -> int:
                     help="instead of the workload: gather and scatter rates on synthetic tables that isolate one path of "
                          "the kernel each (every chunk general with tensors of one size; one 2-D view per row length "
                          "and pitch), one JSON object")
+    ap.add_argument("--tables", default=None,
+                    help="--microbench: only these tables, e.g. contiguous,general:200,rows:5504x22016")
+    ap.add_argument("--reps", type=int, default=15, help="--microbench: timed launches per kernel and table")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         log("bench.py: this build is the one-GPU hot path; it has no multi-GPU leg (run with --gpus 1).")

@@ -23,6 +23,20 @@ struct DsTile {
 };
 static_assert(sizeof(DsTile) == 128, "DsTile is one 128-byte line");
 
+// What the kernel's general path needs of a tile, 40 bytes instead of the 128 of a DsTile plus its two
+// tile_off entries: the first wavefront of a general chunk reads one of these per lane.  Entry n_tiles is
+// a sentinel whose img_off is the image length, so that a tile's end is the next entry's img_off.
+struct DsTileHot {
+  uint64_t img_off;  // where the tile's range starts in the image (= tile_off[t])
+  uint64_t src;      // device address of element (0,...,0)
+  uint64_t nbytes;   // payload bytes
+  uint64_t stride0;  // distance between runs in bytes (views with one outer dimension)
+  uint32_t run;      // run length in bytes, views with one outer dimension (0 otherwise)
+  uint32_t meta;     // n_outer | log2(itemsize) << 8.  n_outer is given as 2 for a view with one outer
+                     // dimension whose runs do not fit 32 bits: it then takes the routes of the N-D views
+};
+static_assert(sizeof(DsTileHot) == 40, "five 8-byte words");
+
 // What the kernel's lean path needs to move one whole chunk, in one 32-byte load.
 // Chunks that are not "simple" (a tile boundary, the end of a payload or
 // padding inside the chunk, more than one outer dimension, rows shorter than
@@ -64,7 +78,8 @@ struct ds_plan {
   uint32_t chunk_log2 = 0;
   std::vector<DsManifestEntry> manifest;   // table order as given
   std::vector<DsTile> tiles;               // image order
-  std::vector<uint64_t> tile_off;          // n_tiles + 1 entries, last = total_bytes
+  std::vector<uint64_t> tile_off;          // n_tiles + 1 entries, last = total_bytes (host only)
+  std::vector<DsTileHot> hot;              // n_tiles + 1 entries, image order, last = sentinel
   std::vector<uint32_t> first_tile;        // n_chunks + 1 entries, last = n_tiles
   std::vector<DsChunkRec> recs;            // one per chunk
   uint64_t n_general = 0;                  // chunks of kind DS_CHUNK_GENERAL
@@ -72,7 +87,7 @@ struct ds_plan {
   int device = -1;
   void *dev_blob = nullptr;
   const DsTile *d_tiles = nullptr;
-  const uint64_t *d_tile_off = nullptr;
+  const DsTileHot *d_hot = nullptr;
   const uint32_t *d_first_tile = nullptr;
   const DsChunkRec *d_recs = nullptr;
   uint64_t n_chunks() const { return first_tile.empty() ? 0 : first_tile.size() - 1; }

@@ -24,13 +24,14 @@
 //
 // general path: the remaining chunks (tile boundaries, payload tails, padding,
 //   N-D views); their record names the tiles they hold.  The tiles are taken
-//   64 at a time: the first wavefront reads one tile's extent and descriptor
-//   per lane, a wavefront inclusive scan over the unit counts turns the 64
-//   tiles into one dense index space, and the threads of the work-group share
-//   that space evenly, four units each per pass, in phases (find the tile of
-//   each unit by binary search over the scan in LDS, issue all loads, issue
-//   all stores).  Large pieces of views with several outer dimensions are
-//   taken out of the scan and walked by the whole work-group ("direct" path).
+//   64 at a time: the first wavefront reads one tile's compact descriptor
+//   (DsTileHot, 40 bytes) per lane, a wavefront inclusive scan over the unit
+//   counts turns the 64 tiles into one dense index space, and the threads of
+//   the work-group share that space evenly, four units each per pass, in three
+//   phases: (1) registers and LDS only: find the tile of each unit by binary
+//   search over the scan and classify it; (2) all loads, nothing between
+//   them; (3) all stores.  Large pieces of views with several outer dimensions
+//   are taken out of the scan and walked by the whole work-group ("direct").
 //
 // Tensor-side addresses are only element-aligned.  gfx950 runs with unaligned
 // global access enabled, so a 16-byte unit that lies inside one contiguous run
@@ -55,7 +56,7 @@ constexpr uint32_t kBigUnits = 512;       // N-D views: pieces of >= 8 KiB insid
 
 struct MoveArgs {
   const DsTile *tiles;
-  const uint64_t *tile_off;
+  const DsTileHot *hot;  // n_tiles + 1 entries: the general path's compact copy of the tiles, and a sentinel
   const uint32_t *first_tile;
   uint8_t *img;         // points at image byte img_lo
   uint64_t img_lo, img_hi;
@@ -337,28 +338,38 @@ __device__ __forceinline__ void store_cut(uint8_t *p0, uint8_t *p1, uint32_t k, 
   if (valid > k) store_low_bytes(p1, splice(v, u32x4{0, 0, 0, 0}, k), valid - k);
 }
 
-// What a batch of up to 64 tiles of a general chunk needs, staged in LDS by the first wavefront.
+// What a batch of up to 64 tiles of a general chunk needs, staged in LDS by the first wavefront.  Everything
+// a unit needs is relative to the start of its tile's range inside the (clipped) chunk, so that the per-unit
+// arithmetic is 32-bit: a chunk is at most 32 KiB.
 struct GenLds {
-  uint32_t incl[kWave];     // inclusive scan of the tiles' unit counts inside the chunk
-  uint32_t begin[kWave];    // where a tile's clipped range starts, relative to the chunk's (clipped) start
-  uint32_t meta[kWave];     // n_outer | es_log2 << 8
-  uint64_t b0[kWave];       // byte of the tile's own range at which its clipped range starts
-  uint64_t src[kWave], nbytes[kWave], run[kWave], stride0[kWave];
-  uint64_t big_mask;        // tiles taken out of the scan (large pieces of views with several outer dimensions)
-  uint32_t n_units;         // units of the batch = incl[63]
+  uint32_t incl[kWave];   // inclusive scan of the tiles' unit counts inside the chunk
+  uint32_t begin[kWave];  // where a tile's clipped range starts, relative to the chunk's clipped start
+  uint32_t rem[kWave];    // payload bytes from there on (clamped to 2^31; 0 = padding only)
+  uint32_t run[kWave];    // views with one outer dimension: run length
+  uint32_t col0[kWave];   // ... and the position of the clipped start inside its run
+  uint32_t meta[kWave];   // n_outer | log2(itemsize) << 8 | kRunGe16 if the runs are at least 16 bytes long
+  uint64_t src0[kWave];   // address of the clipped start (one run), or of the start of the run that holds it
+  uint64_t pitch[kWave];  // views with one outer dimension: distance between runs
+  uint64_t big_mask;      // tiles taken out of the scan (large pieces of views with several outer dimensions)
+  uint32_t n_units;       // units of the batch = incl[63]
 };
+constexpr uint32_t kRunGe16 = 1u << 16;
+constexpr int kStorePolicySc0Sc1Nt = 1 | 2 | 16;  // sc0 | nt | sc1 in the buffer-store intrinsic's aux operand
+// s_waitcnt immediate on gfx9: vmcnt = 0 (bits 3:0 and 15:14), expcnt (6:4) and lgkmcnt (11:8) left at their maxima
+constexpr int kWaitVmcnt0 = 0x0F70;
 
 // One general chunk, whole work-group: chunk number c, which holds (parts of) tiles t0 .. t1.
 //
-// The tiles are taken 64 at a time.  The first wavefront reads their extents and descriptors (one tile per
-// lane), turns the unit counts into one dense index space with an inclusive scan, and leaves all of it in
-// LDS; then every thread takes the units tid, tid + NT, ... of that space, UNROLL at a time in phases: find
-// the tile of each unit (binary search over the scan) and classify it, issue all loads, issue all stores.
-// So a chunk costs three dependent trips to memory (record -> extents and descriptors -> data) however many
-// tiles it holds.  Units that are one 16-byte access -- inside the payload of a contiguous tile or inside a
-// row of a 2-D view -- and padding are handled in the phases; the rest (cut by the end of a row or of the
-// payload, views with several outer dimensions) go one by one through move_unit afterwards.
-template <bool PACK, int NT, int UNROLL, bool NTL, bool NTS>
+// The tiles are taken 64 at a time.  The first wavefront reads their compact descriptors (DsTileHot, one tile
+// per lane), turns the unit counts into one dense index space with an inclusive scan, and leaves what the
+// units need in LDS; then every thread takes the units tid, tid + NT, ... of that space, UNROLL at a time in
+// phases: find the tile of each unit (binary search over the scan) and classify it, issue all loads, issue
+// all stores.  So a chunk costs three dependent trips to memory (record -> descriptors -> data) however many
+// tiles it holds.  Units that are one 16-byte access (inside the payload of a contiguous tile or inside a row
+// of a 2-D view), padding, and units cut by the end of a run of at least 16 bytes are handled in the phases;
+// only the rest (runs shorter than 16 bytes, views with several outer dimensions) goes one by one through
+// move_unit afterwards.
+template <bool PACK, int NT, int UNROLL, bool NTL, bool NTS, bool BUFST>
 __device__ __forceinline__ void general_chunk(const MoveArgs &a, uint64_t c, uint32_t t0, uint32_t t1, GenLds *g) {
   const uint32_t tid = threadIdx.x;
   const uint32_t lane = tid & (kWave - 1);
@@ -368,40 +379,60 @@ __device__ __forceinline__ void general_chunk(const MoveArgs &a, uint64_t c, uin
   const uint64_t cb = c_begin > a.img_lo ? c_begin : a.img_lo;
   const uint64_t ce = c_end < a.img_hi ? c_end : a.img_hi;
   if (cb >= ce) return;
+  uint8_t *const cimg = a.img + (cb - a.img_lo);  // the chunk's (clipped) start in the image buffer
+  // Gather with buffer stores: the resource covers exactly the chunk's part of the image, and a lane that has
+  // nothing to store in a phase gives an offset beyond it, which the hardware drops.  The stores of a phase
+  // are then plain instructions one behind the other, with no branch (and no wait) between them.
+  __amdgpu_buffer_rsrc_t image_rsrc;
+  if (PACK && BUFST) image_rsrc = __builtin_amdgcn_make_buffer_rsrc(cimg, 0, (int)(uint32_t)(ce - cb), 0x00020000);
+  constexpr uint32_t kNoStore = 0x80000000u;
 
   for (uint32_t bt = t0; bt <= t1; bt += kWave) {
     __syncthreads();  // readers of the previous batch (or of the previous chunk) are done
     if (tid < kWave) {
       const uint32_t ti = bt + lane;
       uint64_t lo = cb, hi = cb, tb = cb;
-      uint64_t src = 0, nbytes = 0, run = 0, stride0 = 0;
-      uint32_t n_outer = 0, es_log2 = 0;
+      uint64_t src = 0, nbytes = 0, stride0 = 0;
+      uint32_t run = 0, meta = 0;
       if (ti <= t1) {
-        tb = a.tile_off[ti];
-        const uint64_t te = a.tile_off[ti + 1];
-        const DsTile *t = a.tiles + ti;
-        src = t->src;
-        nbytes = t->nbytes;
-        run = t->run_bytes;
-        n_outer = t->n_outer;
-        es_log2 = t->es_log2;
-        stride0 = t->stride[0];
+        const DsTileHot *h = a.hot + ti;
+        tb = h->img_off;
+        src = h->src;
+        nbytes = h->nbytes;
+        stride0 = h->stride0;
+        run = h->run;
+        meta = h->meta;
+        const uint64_t te = h[1].img_off;  // the entry behind the last tile is a sentinel
         lo = tb > cb ? tb : cb;
         hi = te < ce ? te : ce;
         if (hi < lo) hi = lo;
       }
+      const uint32_t n_outer = meta & 0xFFu;
       const uint32_t units = (uint32_t)((hi - lo) >> 4);
       const bool big = units >= kBigUnits && n_outer > 1;
       const uint64_t big_mask = __ballot(big);
       const uint32_t incl = wave_inclusive_scan(big ? 0u : units, lane);
+      const uint64_t b0 = lo - tb;  // byte of the tile's own range at which its clipped range starts
+      uint64_t rem = b0 < nbytes ? nbytes - b0 : 0;
+      if (rem > (1ull << 31)) rem = 1ull << 31;
+      uint64_t src0 = src + b0;
+      uint32_t col0 = 0;
+      uint64_t longest = nbytes;  // length of the tile's runs
+      if (n_outer == 1) {
+        uint64_t row0, c0;
+        divmod(b0, run, row0, c0);
+        src0 = src + row0 * stride0;
+        col0 = (uint32_t)c0;
+        longest = run;
+      }
       g->incl[lane] = incl;
       g->begin[lane] = (uint32_t)(lo - cb);
-      g->meta[lane] = n_outer | (es_log2 << 8);
-      g->b0[lane] = lo - tb;
-      g->src[lane] = src;
-      g->nbytes[lane] = nbytes;
+      g->rem[lane] = (uint32_t)rem;
       g->run[lane] = run;
-      g->stride0[lane] = stride0;
+      g->col0[lane] = col0;
+      g->meta[lane] = meta | (longest >= 16 ? kRunGe16 : 0u);
+      g->src0[lane] = src0;
+      g->pitch[lane] = stride0;
       if (lane == kWave - 1) {
         g->n_units = incl;
         g->big_mask = big_mask;
@@ -409,131 +440,166 @@ __device__ __forceinline__ void general_chunk(const MoveArgs &a, uint64_t c, uin
     }
     __syncthreads();
     const uint32_t n_units = g->n_units;
-    // unit j of the batch: its tile p, its image offset x and its byte offset b in the tile's own range
-    auto locate = [&](uint32_t j, uint32_t &p, uint64_t &x, uint64_t &b) {
-      p = 0;  // smallest p with incl[p] > j
-#pragma unroll
-      for (int step = kWave / 2; step > 0; step >>= 1)
-        if (g->incl[p + step - 1] <= j) p += step;
-      const uint32_t d = 16u * (j - (p ? g->incl[p - 1] : 0u));
-      x = cb + g->begin[p] + d;
-      b = g->b0[p] + d;
-    };
     for (uint32_t base = 0; base < n_units; base += NT * UNROLL) {
-      enum : uint32_t { kNone = 0, kFast = 1, kZero = 2, kCut = 3, kSlow = 4 };
+      // how[i]: kind | k << 8 | last << 16 | tile << 24 (k: bytes of a cut unit that end its run; last: the
+      // payload ends with that run; tile: 0..63 inside the batch)
+      enum : uint32_t { kNone = 0, kFast = 1, kZero = 2, kCut = 3, kSlow = 4, kCutHeld = 5, kKind = 0xFFu, kLast = 1u << 16 };
+      uint32_t j[UNROLL], p[UNROLL], how[UNROLL];
+      uint8_t *ip[UNROLL];   // the unit in the image buffer
+      uint8_t *sp[UNROLL];   // kFast, kCut: where the unit starts in the tensor
+      // ---- phase 1, registers and LDS only: which tile each unit belongs to, and what kind of unit it is ----
       // A thread's i-th unit of the pass.  Each block of NT units is rotated by 9 more than the one before:
       // tensors of one size put their cut units at a fixed period, and periods that divide NT (slots of 512
       // bytes to 4 KiB) would otherwise give all of them to the same few threads, four each.
-      auto unit_of = [&](int i) { return base + i * NT + ((tid + 9u * i) & (NT - 1)); };
-      u32x4 v[UNROLL];
-      uint8_t *ip[UNROLL];   // the unit in the image buffer
-      uint8_t *sp[UNROLL];   // kFast: the unit in the tensor
-      uint32_t how[UNROLL];
-      // Gather: the thread's first cut unit of the pass (see below) travels with the others: its two loads are
-      // issued in the load phase and it is stored in the store phase.  (The scatter has no registers to spare
-      // for that: it would drop to three wavefronts per SIMD.)
-      bool cut_held = false;
-      u32x4 cut_a, cut_b;
-      uint32_t cut_k = 0;
-      uint8_t *cut_ip = nullptr;
 #pragma unroll
       for (int i = 0; i < UNROLL; ++i) {
-        const uint32_t j = unit_of(i);
+        j[i] = base + i * NT + ((tid + 40u * i) & (NT - 1));
+        p[i] = 0;
+      }
+      // smallest p with incl[p] > j, the searches of the thread's units side by side (a unit beyond the end
+      // of the batch ends at tile 63: every index stays inside the table)
+#pragma unroll
+      for (int step = kWave / 2; step > 0; step >>= 1) {
+#pragma unroll
+        for (int i = 0; i < UNROLL; ++i)
+          if (g->incl[p[i] + step - 1] <= j[i]) p[i] += step;
+      }
+#pragma unroll
+      for (int i = 0; i < UNROLL; ++i) {
         how[i] = kNone;
-        if (j < n_units) {
-          uint32_t p;
-          uint64_t x, b;
-          locate(j, p, x, b);
-          const uint64_t nbytes = g->nbytes[p];
-          ip[i] = a.img + (x - a.img_lo);
-          if (b >= nbytes) {
+        ip[i] = cimg;
+        sp[i] = cimg;
+        if (j[i] < n_units) {
+          const uint32_t q = p[i];
+          const uint32_t d = 16u * (j[i] - (q ? g->incl[q - 1] : 0u));  // the unit's offset in the tile's clipped range
+          ip[i] = cimg + (g->begin[q] + d);
+          const uint32_t rem = g->rem[q];
+          const uint32_t meta = g->meta[q];
+          if (d >= rem) {
             how[i] = kZero;
+          } else if ((meta & 0xFFu) > 1 || !(meta & kRunGe16)) {
+            how[i] = kSlow | (q << 24);
           } else {
-            how[i] = kSlow;
-            const uint32_t n_outer = g->meta[p] & 0xFFu;
-            if (n_outer <= 1) {
-              // the run the unit starts in: the whole payload, or one row of a 2-D view
-              uint64_t L = nbytes, row = 0, col = b, pitch = 0;
-              if (n_outer) {
-                L = g->run[p];
-                pitch = g->stride0[p];
-                divmod(b, L, row, col);
-              }
-              if (L >= 16) {
-                const uint64_t run0 = g->src[p] + row * pitch;
-                if (col + 16 <= L) {
-                  sp[i] = reinterpret_cast<uint8_t *>(run0 + col);
-                  how[i] = kFast;
-                } else if (PACK && !cut_held) {
-                  cut_held = true;
-                  how[i] = kNone;
-                  cut_k = (uint32_t)(L - col);
-                  cut_ip = ip[i];
-                  cut_a = ld16_any<NTL>(reinterpret_cast<uint8_t *>(run0 + L - 16));
-                  cut_b = u32x4{0, 0, 0, 0};
-                  // unless the payload ends with this run, the unit goes on in the next one
-                  if (b + cut_k < nbytes) cut_b = ld16_any<NTL>(reinterpret_cast<uint8_t *>(run0 + pitch));
-                } else {
-                  how[i] = kCut;
-                }
-              }
+            // the run the unit starts in: what is left of the payload, or one row of a 2-D view
+            uint64_t run0 = g->src0[q];
+            uint32_t L = rem, col = d;
+            if (meta & 0xFFu) {
+              L = g->run[q];
+              const uint32_t t = g->col0[q] + d;  // < 2^31 + 2^15
+              const uint32_t rows = t / L;
+              col = t - rows * L;
+              run0 += (uint64_t)rows * g->pitch[q];
+            }
+            sp[i] = reinterpret_cast<uint8_t *>(run0 + col);
+            if (col + 16u <= L) {
+              how[i] = kFast;
+            } else {
+              const uint32_t k = L - col;
+              // unless the payload ends with this run, the unit goes on in the next one
+              const bool last = !(meta & 0xFFu) || d + k >= rem;
+              how[i] = kCut | (k << 8) | (last ? kLast : 0u) | (q << 24);
             }
           }
-          if (how[i] == kFast) v[i] = PACK ? ld16_any<NTL>(sp[i]) : ld16_aligned<NTL>(ip[i]);
         }
       }
+      // Gather: the thread's first cut unit of the pass travels with the others: its two loads are issued in
+      // the load phase, it is spliced into v[] and leaves with the same store instruction as its neighbours
+      // (so that a line of the image is written whole).  Further cut units of the same thread wait for a
+      // phase of their own; the rotation above makes them rare.  (Chosen here, after the units have been
+      // classified independently of each other, so that their classifications can run side by side.)
+      bool cut_held = false;
+      uint8_t *cut_pa = nullptr, *cut_pb = nullptr;  // the last 16 bytes of the run; the first 16 of the next (or null)
+      if (PACK) {
+#pragma unroll
+        for (int i = 0; i < UNROLL; ++i)
+          if ((how[i] & kKind) == kCut && !cut_held) {
+            cut_held = true;
+            const uint32_t k = (how[i] >> 8) & 0xFFu, q = how[i] >> 24;
+            cut_pa = sp[i] + k - 16;
+            if (!(how[i] & kLast)) cut_pb = sp[i] + k + (g->pitch[q] - g->run[q]);
+            how[i] = kCutHeld | (k << 8);
+          }
+      }
+      // ---- phase 2: all loads, nothing between them ----
+      u32x4 v[UNROLL];
+#pragma unroll
+      for (int i = 0; i < UNROLL; ++i) v[i] = u32x4{0, 0, 0, 0};  // padding is written as zeros
+      u32x4 cut_a = u32x4{0, 0, 0, 0}, cut_b = u32x4{0, 0, 0, 0};
 #pragma unroll
       for (int i = 0; i < UNROLL; ++i) {
-        if (how[i] == kFast) {
-          if (PACK) st16_aligned<NTS>(ip[i], v[i]);
-          else st16_any<NTS>(sp[i], v[i]);
-        } else if (PACK && how[i] == kZero) {
-          st16_aligned<NTS>(ip[i], u32x4{0, 0, 0, 0});
+        const uint32_t kind = how[i] & kKind;
+        if (PACK) {
+          if (kind == kFast) v[i] = ld16_any<NTL>(sp[i]);
+        } else {
+          if (kind == kFast || kind == kCut) v[i] = ld16_aligned<NTL>(ip[i]);
         }
       }
-      if (PACK && cut_held) st16_aligned<NTS>(cut_ip, splice(cut_a, cut_b, 16u - cut_k));
-      // Units cut by the end of a run of at least 16 bytes: the first k bytes end that run, the rest start the
-      // next one, or are padding when the payload ends there.  As in the lean path the gather takes both
-      // parts with 16-byte loads that lie wholly inside their runs and splices them; the scatter stores each
-      // part as at most four pieces of 8, 4, 2 and 1 bytes.  A thread's first cut unit went with the phases
-      // above; here follow its further ones, if any, one after the other (located again: keeping every unit's
-      // position would cost registers).
+      if (PACK && cut_held) {
+        cut_a = ld16_any<NTL>(cut_pa);
+        if (cut_pb) cut_b = ld16_any<NTL>(cut_pb);
+      }
+      // ---- phase 3: all stores ----
+      // Every load has landed before the first store goes out.  Loads and stores share one counter and
+      // complete out of order with respect to each other, so a wait for a load that is issued behind a store
+      // waits for that store as well; left to itself the compiler, which cannot tell on every path that the
+      // loads are done, puts such a wait in front of each store and the stores leave one round trip apart.
+      __builtin_amdgcn_s_waitcnt(kWaitVmcnt0);
+      if (PACK) {
+        if (cut_held) {
+          uint32_t k = 0;
 #pragma unroll
-      for (int i = 0; i < UNROLL; ++i)
-        if (how[i] == kCut) {
-          uint32_t p;
-          uint64_t x, b;
-          locate(unit_of(i), p, x, b);
-          const uint64_t nbytes = g->nbytes[p];
-          const uint32_t meta = g->meta[p];
-          uint64_t L = nbytes, row = 0, col = b, pitch = 0;
-          if (meta & 0xFFu) {
-            L = g->run[p];
-            pitch = g->stride0[p];
-            divmod(b, L, row, col);
-          }
-          const uint64_t run0 = g->src[p] + row * pitch;
-          const uint32_t k = (uint32_t)(L - col);
-          uint8_t *p0 = reinterpret_cast<uint8_t *>(run0 + col);
-          const bool last = b + k >= nbytes;  // the payload ends with this run
-          uint8_t *p1 = reinterpret_cast<uint8_t *>(run0 + pitch);
-          if (PACK) {
-            const u32x4 va = ld16_any<NTL>(p0 + k - 16);
-            u32x4 vb = u32x4{0, 0, 0, 0};
-            if (!last) vb = ld16_any<NTL>(p1);
-            st16_aligned<NTS>(ip[i], splice(va, vb, 16u - k));
-          } else {
-            store_cut(p0, p1, k, ld16_aligned<NTL>(ip[i]), last ? k : 16u);
+          for (int i = 0; i < UNROLL; ++i)
+            if ((how[i] & kKind) == kCutHeld) k = (how[i] >> 8) & 0xFFu;
+          const u32x4 spliced = splice(cut_a, cut_b, 16u - k);
+#pragma unroll
+          for (int i = 0; i < UNROLL; ++i)
+            if ((how[i] & kKind) == kCutHeld) v[i] = spliced;
+        }
+#pragma unroll
+        for (int i = 0; i < UNROLL; ++i) {
+          const uint32_t kind = how[i] & kKind;
+          const bool stores = kind == kFast || kind == kZero || kind == kCutHeld;
+          if (BUFST)
+            __builtin_amdgcn_raw_buffer_store_b128(v[i], image_rsrc, (int)(stores ? (uint32_t)(ip[i] - cimg) : kNoStore), 0,
+                                                   kStorePolicySc0Sc1Nt);
+          else if (stores)
+            st16_aligned<NTS>(ip[i], v[i]);
+        }
+      } else {
+#pragma unroll
+        for (int i = 0; i < UNROLL; ++i) {
+          const uint32_t kind = how[i] & kKind;
+          if (kind == kFast) {
+            st16_any<NTS>(sp[i], v[i]);
+          } else if (kind == kCut) {
+            // each part as at most four pieces of 8, 4, 2 and 1 bytes: exactly the bytes of the view
+            const uint32_t k = (how[i] >> 8) & 0xFFu, q = how[i] >> 24;
+            const bool last = how[i] & kLast;
+            store_cut(sp[i], sp[i] + k + (g->pitch[q] - g->run[q]), k, v[i], last ? k : 16u);
           }
         }
+      }
+      // Gather: a thread's further cut units, one after the other: the first k bytes end their run, the rest
+      // start the next one or are padding when the payload ends there; both parts come from 16-byte loads
+      // that lie wholly inside their runs.
+      if (PACK) {
+#pragma unroll
+        for (int i = 0; i < UNROLL; ++i)
+          if ((how[i] & kKind) == kCut) {
+            const uint32_t k = (how[i] >> 8) & 0xFFu, q = how[i] >> 24;
+            const u32x4 va = ld16_any<NTL>(sp[i] + k - 16);
+            u32x4 vb = u32x4{0, 0, 0, 0};
+            if (!(how[i] & kLast)) vb = ld16_any<NTL>(sp[i] + k + (g->pitch[q] - g->run[q]));
+            st16_aligned<NTS>(ip[i], splice(va, vb, 16u - k));
+          }
+      }
       // the rare rest (runs shorter than 16 bytes, views with several outer dimensions), one by one
 #pragma unroll
       for (int i = 0; i < UNROLL; ++i)
-        if (how[i] == kSlow) {
-          uint32_t p;
-          uint64_t x, b;
-          locate(unit_of(i), p, x, b);
-          move_unit<PACK, NTL, NTS>(a.tiles + bt + p, x - b, x, ip[i]);
+        if ((how[i] & kKind) == kSlow) {
+          const uint32_t q = how[i] >> 24;
+          const uint64_t tb = a.hot[bt + q].img_off;
+          move_unit<PACK, NTL, NTS>(a.tiles + bt + q, tb, cb + (uint64_t)(ip[i] - cimg), ip[i]);
         }
     }
     uint64_t big_mask = g->big_mask;
@@ -541,7 +607,7 @@ __device__ __forceinline__ void general_chunk(const MoveArgs &a, uint64_t c, uin
       const uint32_t p = (uint32_t)__builtin_ctzll(big_mask);
       big_mask &= big_mask - 1;
       const uint32_t t = bt + p;
-      const uint64_t tb = a.tile_off[t], te = a.tile_off[t + 1];
+      const uint64_t tb = a.hot[t].img_off, te = a.hot[t + 1].img_off;
       const uint64_t lo2 = tb > cb ? tb : cb, hi2 = te < ce ? te : ce;
       move_tile_direct<PACK, NT, UNROLL, NTL, NTS>(a.tiles + t, tb, lo2, hi2, a.img, a.img_lo);
     }
@@ -554,13 +620,15 @@ __device__ __forceinline__ void general_chunk(const MoveArgs &a, uint64_t c, uin
 // "nt" global stores and 5.88 TB/s with plain ones.  The buffer form is used because the compiler has an
 // intrinsic with a cache-policy operand for it (and none for global stores); the resource covers exactly
 // the work-group's chunk, so an out-of-range store would be dropped by the hardware.
-constexpr int kStorePolicySc0Sc1Nt = 1 | 2 | 16;  // sc0 | nt | sc1 in the intrinsic's aux operand
 
 // Number of lean work items of a launch; item ci takes one lean chunk, whole work-group.
 __device__ __forceinline__ uint32_t lean_items(const LeanArgs &a) { return a.xcd_span ? a.xcd_span * 8u : a.n_chunks; }
 
+// Work item ci of a launch: moves its chunk if the chunk is lean and returns false; for a general chunk it
+// moves nothing, says which chunk and tiles (c, t0, t1) and returns true: the caller sends it down the general
+// path (one call site, so that the general path is in the kernel once).
 template <bool PACK, int NT, int UNROLL, bool NTL, bool NTS, bool BUFST>
-__device__ __forceinline__ void lean_chunk(const LeanArgs &a, const MoveArgs &ma, uint32_t ci, GenLds *s_gen) {
+__device__ __forceinline__ bool lean_chunk(const LeanArgs &a, uint32_t ci, uint64_t &c_gen, uint32_t &t0, uint32_t &t1) {
   const uint32_t tid = threadIdx.x;
   {
     // Work-groups are dealt to the 8 XCDs round-robin (work-group i runs on XCD i mod 8).  Chunk
@@ -570,15 +638,17 @@ __device__ __forceinline__ void lean_chunk(const LeanArgs &a, const MoveArgs &ma
     uint32_t cm = ci;
     if (a.xcd_span) {
       cm = (ci & 7u) * a.xcd_span + (ci >> 3);
-      if (cm >= a.n_chunks) return;
+      if (cm >= a.n_chunks) return false;
     }
     const uint32_t c = a.c_lo + cm;
     const DsChunkRec r = a.recs[c];
     const uint32_t kind = r.kind & 0xFF;  // bits 8.. hold log2(itemsize)
     if (kind == DS_CHUNK_GENERAL) {
       // its record names the tiles it holds: one load away from them, and in place among its neighbours
-      general_chunk<PACK, 256, 4, NTL, NTS>(ma, c, r.tile, r.tile + r.col0, s_gen);
-      return;
+      c_gen = c;
+      t0 = r.tile;
+      t1 = r.tile + r.col0;
+      return true;
     }
     uint8_t *imgp = a.img + (((uint64_t)c << a.chunk_log2) - a.img_lo);
     __amdgpu_buffer_rsrc_t image_rsrc;
@@ -657,6 +727,7 @@ __device__ __forceinline__ void lean_chunk(const LeanArgs &a, const MoveArgs &ma
       }
     }
   }
+  return false;
 }
 
 // Both paths in one launch: work item i takes whole chunk number i of the range (in the XCD-contiguous
@@ -682,18 +753,21 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 4))) voi
   const uint32_t n_lean = lean_items(la);
   const uint32_t n_iter = n_lean + ma.n_extra;
   for (uint32_t wi = blockIdx.x; wi < n_iter; wi += gridDim.x) {
+    uint64_t c = 0;
+    uint32_t t0 = 0, t1 = 0;
+    bool general = true;
     if (wi < n_lean) {
-      lean_chunk<PACK, 256, UNROLL, NTL, NTS, BUFST>(la, ma, wi, &s_gen);
+      general = lean_chunk<PACK, 256, UNROLL, NTL, NTS, BUFST>(la, wi, c, t0, t1);
     } else {
       // a chunk cut by the range: the general path clips to the range, whatever the chunk's kind
-      const uint64_t c = ma.extra[wi - n_lean];
+      c = ma.extra[wi - n_lean];
       uint64_t c_end = (c + 1) << ma.chunk_log2;
       if (c_end > ma.total) c_end = ma.total;
-      const uint32_t t0 = ma.first_tile[c];
-      uint32_t t1 = ma.first_tile[c + 1];
-      if (ma.tile_off[t1] >= c_end) --t1;  // that tile starts where this chunk ends
-      general_chunk<PACK, 256, 4, NTL, NTS>(ma, c, t0, t1, &s_gen);
+      t0 = ma.first_tile[c];
+      t1 = ma.first_tile[c + 1];
+      if (ma.hot[t1].img_off >= c_end) --t1;  // that tile starts where this chunk ends
     }
+    if (general) general_chunk<PACK, 256, 4, NTL, NTS, BUFST>(ma, c, t0, t1, &s_gen);
   }
 }
 
@@ -815,7 +889,7 @@ namespace {
 // The plan's tables in device memory: the plan's own copy, or the one ds_pack_noalloc keeps in static memory.
 struct DeviceTables {
   const DsTile *tiles;
-  const uint64_t *tile_off;
+  const DsTileHot *hot;
   const uint32_t *first_tile;
   const DsChunkRec *recs;
 };
@@ -841,7 +915,7 @@ int launch_move_with(const ds_plan *plan, const DeviceTables &tb, bool pack, uin
   // ... and the one or two chunks cut by the ends of the range, clipped by the general path
   MoveArgs ma;
   ma.tiles = tb.tiles;
-  ma.tile_off = tb.tile_off;
+  ma.hot = tb.hot;
   ma.first_tile = tb.first_tile;
   ma.img = img;
   ma.img_lo = img_lo;
@@ -881,7 +955,7 @@ int ds_launch_move(const ds_plan *plan, bool pack, uint8_t *img, uint64_t img_lo
   int dev = -1;
   DS_HIP_TRY(hipGetDevice(&dev));
   if (dev != plan->device) return DS_ESTATE;
-  const DeviceTables tb = {plan->d_tiles, plan->d_tile_off, plan->d_first_tile, plan->d_recs};
+  const DeviceTables tb = {plan->d_tiles, plan->d_hot, plan->d_first_tile, plan->d_recs};
   return launch_move_with(plan, tb, pack, img, img_lo, img_hi, grid_limit, stream);
 }
 
@@ -923,7 +997,7 @@ extern "C" int ds_pack_noalloc(const ds_plan *plan, void *dst_dev, uint64_t img_
   if (img_lo > img_hi || img_hi > plan->total_bytes || ((img_lo | img_hi) & 15)) return DS_ERANGE;
   // the tables, laid out one behind the other as in a plan's own device copy
   const size_t b_tiles = plan->tiles.size() * sizeof(DsTile);
-  const size_t b_off = round_up_128(plan->tile_off.size() * sizeof(uint64_t));
+  const size_t b_off = round_up_128(plan->hot.size() * sizeof(DsTileHot));
   const size_t b_first = round_up_128(plan->first_tile.size() * sizeof(uint32_t));
   const size_t b_recs = round_up_128(plan->recs.size() * sizeof(DsChunkRec));
   if (b_tiles + b_off + b_first + b_recs > kScratchBytes) return DS_ETOOBIG;
@@ -940,13 +1014,13 @@ extern "C" int ds_pack_noalloc(const ds_plan *plan, void *dst_dev, uint64_t img_
   // the caller keeps until the work has run.
   hipStream_t st = (hipStream_t)stream;
   if (b_tiles) DS_HIP_TRY(hipMemcpyAsync(base, plan->tiles.data(), b_tiles, hipMemcpyHostToDevice, st));
-  DS_HIP_TRY(hipMemcpyAsync(base + b_tiles, plan->tile_off.data(), plan->tile_off.size() * sizeof(uint64_t),
+  DS_HIP_TRY(hipMemcpyAsync(base + b_tiles, plan->hot.data(), plan->hot.size() * sizeof(DsTileHot),
                             hipMemcpyHostToDevice, st));
   DS_HIP_TRY(hipMemcpyAsync(base + b_tiles + b_off, plan->first_tile.data(),
                             plan->first_tile.size() * sizeof(uint32_t), hipMemcpyHostToDevice, st));
   DS_HIP_TRY(hipMemcpyAsync(base + b_tiles + b_off + b_first, plan->recs.data(),
                             plan->recs.size() * sizeof(DsChunkRec), hipMemcpyHostToDevice, st));
-  const DeviceTables tb = {(const DsTile *)base, (const uint64_t *)(base + b_tiles),
+  const DeviceTables tb = {(const DsTile *)base, (const DsTileHot *)(base + b_tiles),
                            (const uint32_t *)(base + b_tiles + b_off),
                            (const DsChunkRec *)(base + b_tiles + b_off + b_first)};
   return launch_move_with(plan, tb, true, (uint8_t *)dst_dev, img_lo, img_hi, 0, st);

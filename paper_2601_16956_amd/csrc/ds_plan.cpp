@@ -128,23 +128,22 @@ DsTile make_tile(const ds_shard_desc &d, uint64_t nbytes) {
 int upload(ds_plan *p) {
   DS_HIP_TRY(hipGetDevice(&p->device));
   const size_t b_tiles = p->tiles.size() * sizeof(DsTile);
-  const size_t b_off = round_up(p->tile_off.size() * sizeof(uint64_t), 128);
+  const size_t b_hot = round_up(p->hot.size() * sizeof(DsTileHot), 128);
   const size_t b_first = round_up(p->first_tile.size() * sizeof(uint32_t), 128);
   const size_t b_recs = round_up(p->recs.size() * sizeof(DsChunkRec), 128);
-  const size_t total = std::max<size_t>(b_tiles + b_off + b_first + b_recs, 128);
+  const size_t total = std::max<size_t>(b_tiles + b_hot + b_first + b_recs, 128);
   DS_HIP_TRY(hipMalloc(&p->dev_blob, total));
   uint8_t *base = (uint8_t *)p->dev_blob;
   p->d_tiles = (const DsTile *)base;
-  p->d_tile_off = (const uint64_t *)(base + b_tiles);
-  p->d_first_tile = (const uint32_t *)(base + b_tiles + b_off);
+  p->d_hot = (const DsTileHot *)(base + b_tiles);
+  p->d_first_tile = (const uint32_t *)(base + b_tiles + b_hot);
   if (b_tiles) DS_HIP_TRY(hipMemcpy(base, p->tiles.data(), b_tiles, hipMemcpyHostToDevice));
-  DS_HIP_TRY(hipMemcpy(base + b_tiles, p->tile_off.data(), p->tile_off.size() * sizeof(uint64_t),
+  DS_HIP_TRY(hipMemcpy(base + b_tiles, p->hot.data(), p->hot.size() * sizeof(DsTileHot), hipMemcpyHostToDevice));
+  DS_HIP_TRY(hipMemcpy(base + b_tiles + b_hot, p->first_tile.data(), p->first_tile.size() * sizeof(uint32_t),
                        hipMemcpyHostToDevice));
-  DS_HIP_TRY(hipMemcpy(base + b_tiles + b_off, p->first_tile.data(), p->first_tile.size() * sizeof(uint32_t),
-                       hipMemcpyHostToDevice));
-  p->d_recs = (const DsChunkRec *)(base + b_tiles + b_off + b_first);
+  p->d_recs = (const DsChunkRec *)(base + b_tiles + b_hot + b_first);
   if (!p->recs.empty())
-    DS_HIP_TRY(hipMemcpy(base + b_tiles + b_off + b_first, p->recs.data(), p->recs.size() * sizeof(DsChunkRec),
+    DS_HIP_TRY(hipMemcpy(base + b_tiles + b_hot + b_first, p->recs.data(), p->recs.size() * sizeof(DsChunkRec),
                          hipMemcpyHostToDevice));
   return DS_OK;
 }
@@ -314,6 +313,24 @@ int ds_plan_create(const ds_shard_desc *desc, size_t n, uint64_t align, uint32_t
           p->tile_off.push_back(desc[order[k]].file_offset);
         }
         p->tile_off.push_back(p->total_bytes);
+        // the general path's compact copy of the tiles
+        p->hot.resize(p->tiles.size() + 1);
+        for (size_t t = 0; t <= p->tiles.size(); ++t) {
+          DsTileHot &h = p->hot[t];
+          std::memset(&h, 0, sizeof(h));
+          h.img_off = p->tile_off[t];
+          if (t == p->tiles.size()) break;  // the sentinel
+          const DsTile &tl = p->tiles[t];
+          h.src = tl.src;
+          h.nbytes = tl.nbytes;
+          uint32_t n_outer = tl.n_outer;
+          if (n_outer == 1) {
+            h.stride0 = tl.stride[0];
+            if (tl.run_bytes < ((uint64_t)1 << 31)) h.run = (uint32_t)tl.run_bytes;
+            else n_outer = 2;
+          }
+          h.meta = n_outer | (tl.es_log2 << 8);
+        }
         const uint64_t chunk = ds_cfg_chunk_bytes();
         p->chunk_log2 = (uint32_t)__builtin_ctzll(chunk);
         const uint64_t n_chunks = (p->total_bytes + chunk - 1) >> p->chunk_log2;
