@@ -135,6 +135,17 @@ def hip_runtime_in_use() -> List[str]:
         return []
 
 
+def kernel_source_digest() -> str:
+    """SHA-256 (first 16 hex digits) over the kernel sources; a counter profile names the digest it was taken
+    with, so that a reader of a measurement can tell whether the profile still describes the kernels in use."""
+    import hashlib
+    h = hashlib.sha256()
+    for name in ("ds_kernels.hip", "ds_splice.h", "ds_internal.h"):
+        with open(os.path.join(_HERE, "csrc", name), "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()[:16]
+
+
 def _load() -> ctypes.CDLL:
     # One HIP runtime per process.  The PyTorch wheel bundles its own copy of
     # libamdhip64 (soname libamdhip64.so.7, looked up by torch under the name
