@@ -977,7 +977,7 @@ def main() -> int:
     ap.add_argument("--experiments", action="store_true",
                     help="the capture variants in full (more grid limits, the rank's state as several plans and "
                          "several checkpoint files); the default run measures a compact set of them")
-    ap.add_argument("--variant", type=int, default=0, choices=[0, 1, 2, 3],
+    ap.add_argument("--variant", type=int, default=0, choices=[0, 1, 2, 3, 4],
                     help="kernel variant (ds_config_set): 0 default, 1 plain accesses, 2 non-temporal global accesses, "
                          "3 default accesses with work-group i on chunk i")
     ap.add_argument("--timeline", default=None, metavar="FILE",

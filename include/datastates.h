@@ -530,7 +530,9 @@ int ds_image_diff(const void *image_a_dev, const void *image_b_dev, uint64_t nby
  *   "variant"       0 = default (non-temporal accesses; the lean gather writes the image with
  *                   write-through streaming buffer stores), 1 = plain loads and stores,
  *                   2 = non-temporal global loads and stores everywhere, 3 = default accesses but
- *                   work-group i takes chunk i (no XCD-contiguous order)
+ *                   work-group i takes chunk i (no XCD-contiguous order), 4 = default, but plans made
+ *                   under it do not mark chunks for the gather's aligned-load route (tensors at
+ *                   addresses that are not multiples of 16 are then read with unaligned loads)
  *   "grid_limit"    work-groups per launch of ds_pack / ds_unpack (each then walks several chunks);
  *                   0 = one per chunk (default).  Engines have their own pack_grid_limit
  *   "io_uring_available"  (get only) 1 if this process can set up an io_uring, else 0

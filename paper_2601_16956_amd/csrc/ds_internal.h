@@ -43,12 +43,16 @@ static_assert(sizeof(DsTileHot) == 40, "five 8-byte words");
 // 16 bytes) are of kind DS_CHUNK_GENERAL and take the general path; their
 // record names the tiles they hold (tile, col0).
 enum : uint32_t { DS_CHUNK_CONTIG = 0, DS_CHUNK_ROWS = 1, DS_CHUNK_GENERAL = 2 };
+// CONTIG only, bit 8 of `kind`: the tensor side of the chunk is not 16-byte aligned, and the tensor has at least
+// 16 more bytes on either side of it, so the gather may read the 16-byte aligned units that cover the chunk's
+// bytes (one more than the chunk has) without leaving the tensor.
+enum : uint32_t { DS_CHUNK_REALIGN = 1u << 8 };
 struct DsChunkRec {
   uint64_t addr;   // CONTIG: tensor address of the chunk's first byte; ROWS: address of the run that holds it
   uint64_t pitch;  // ROWS: distance between runs in bytes
   uint32_t col0;   // ROWS: position of the chunk's first byte inside its run.  GENERAL: number of tiles after the first
   uint32_t run;    // ROWS: run length in bytes (>= 16, multiple of the itemsize)
-  uint32_t kind;   // low byte: DS_CHUNK_*; bits 8..: log2(itemsize) (ROWS)
+  uint32_t kind;   // low byte: DS_CHUNK_*; bits 8..: log2(itemsize) (ROWS), DS_CHUNK_REALIGN (CONTIG)
   uint32_t tile;   // GENERAL: first tile of the chunk.  ROWS: (step / run) << 16 | (step % run), step = bytes
                    // between two units of one thread (threads per work-group x 16)
 };

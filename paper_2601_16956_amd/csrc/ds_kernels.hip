@@ -308,6 +308,12 @@ __device__ __forceinline__ u32x4 splice(u32x4 a, u32x4 b, uint32_t s) {
   return u32x4{r.w[0], r.w[1], r.w[2], r.w[3]};
 }
 
+// The value lane + 1 of the wavefront holds (the last lane keeps its own): one data-parallel move, "wavefront
+// shift left by one".
+__device__ __forceinline__ uint32_t lane_above(uint32_t x) {
+  return (uint32_t)__builtin_amdgcn_update_dpp((int)x, (int)x, 0x130, 0xF, 0xF, false);
+}
+
 // the low n < 16 bytes of v to p (any alignment), as one store each of 8, 4, 2 and 1 bytes as n has those bits
 typedef uint64_t u64_unaligned __attribute__((aligned(1)));
 typedef uint32_t u32_unaligned __attribute__((aligned(1)));
@@ -658,10 +664,34 @@ __device__ __forceinline__ bool lean_chunk(const LeanArgs &a, uint32_t ci, uint6
       uint8_t *s = reinterpret_cast<uint8_t *>(r.addr);
       // (the scatter keeps "nt" global stores on the tensor side: the write-through buffer stores that serve
       // the image so well cost it 3 % on the Llama ranks and 10 % on the fragmentation set, measured)
+      if (PACK && (r.kind & DS_CHUNK_REALIGN)) {
+        // The tensor side is at an odd address: a 16-byte load there costs about twice an aligned one.  Every
+        // lane loads the ALIGNED unit that holds the first byte of its image unit and takes the rest from
+        // the unit of the lane above it (of the same wavefront: the last lane loads that unit itself); the
+        // plan sets the flag only where those units lie inside the tensor.
+        const uint32_t m = (uint32_t)r.addr & 15u;
+        uint8_t *base = s - m;
+        const bool last_lane = (tid & (kWave - 1)) == kWave - 1;
+        u32x4 a[UNROLL], e[UNROLL];
 #pragma unroll
-      for (int i = 0; i < UNROLL; ++i) {
-        const uint32_t off = 16u * (i * NT + tid);
-        v[i] = PACK ? ld16_any<NTL>(s + off) : ld16_aligned<NTL>(imgp + off);
+        for (int i = 0; i < UNROLL; ++i) a[i] = ld16_aligned<NTL>(base + 16u * (i * NT + tid));
+#pragma unroll
+        for (int i = 0; i < UNROLL; ++i) {
+          e[i] = u32x4{0, 0, 0, 0};
+          if (last_lane) e[i] = ld16_aligned<NTL>(base + 16u * (i * NT + tid) + 16u);
+        }
+#pragma unroll
+        for (int i = 0; i < UNROLL; ++i) {
+          u32x4 up = u32x4{lane_above(a[i].x), lane_above(a[i].y), lane_above(a[i].z), lane_above(a[i].w)};
+          if (last_lane) up = e[i];
+          v[i] = splice(a[i], up, m);
+        }
+      } else {
+#pragma unroll
+        for (int i = 0; i < UNROLL; ++i) {
+          const uint32_t off = 16u * (i * NT + tid);
+          v[i] = PACK ? ld16_any<NTL>(s + off) : ld16_aligned<NTL>(imgp + off);
+        }
       }
 #pragma unroll
       for (int i = 0; i < UNROLL; ++i) {

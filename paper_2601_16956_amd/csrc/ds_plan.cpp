@@ -199,7 +199,7 @@ int ds_config_set(const char *key, uint64_t value) {
     return DS_OK;
   }
   if (!std::strcmp(key, "variant")) {
-    if (value > 3) return DS_EINVAL;
+    if (value > 4) return DS_EINVAL;
     g_variant.store(value);
     return DS_OK;
   }
@@ -361,6 +361,9 @@ int ds_plan_create(const ds_shard_desc *desc, size_t n, uint64_t align, uint32_t
               if (tl.n_outer == 0) {
                 r.kind = DS_CHUNK_CONTIG;
                 r.addr = tl.src + b0;
+                // an interior chunk of a tensor at an odd address: the gather may load aligned units
+                if (ds_cfg_variant() != 4 && (r.addr & 15) && b0 >= 16 && b0 + chunk + 16 <= tl.nbytes)
+                  r.kind |= DS_CHUNK_REALIGN;
               } else if (tl.n_outer == 1 && tl.run_bytes >= 16 && tl.run_bytes < ((uint64_t)1 << 31)) {
                 const uint64_t row0 = b0 / tl.run_bytes;
                 r.kind = DS_CHUNK_ROWS | (tl.es_log2 << 8);

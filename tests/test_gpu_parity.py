@@ -610,3 +610,43 @@ def test_image_diff_flags_exactly_the_blocks_that_differ(block_bytes):
     with pytest.raises(ds.DsError) as e:
         ds.ds_image_diff(a.data_ptr() + 4, b.data_ptr(), 1024, block_bytes, flags.data_ptr(), 0)
     assert e.value.code == ds.DS_EINVAL
+
+
+def test_contiguous_tensors_at_every_byte_alignment():
+    """Contiguous tensors whose device address is 0..15 bytes past a multiple of 16, each several chunks long:
+    their interior chunks take the gather's aligned-load route (units assembled from two aligned 16-byte loads,
+    the second one another lane's), first and last chunks the plain one.  Gather and scatter against the
+    oracle, whole image and whole arena, at the three chunk sizes."""
+    ds, orc, gu = _mods()
+    rng = np.random.default_rng(1616)
+    arena = rng.integers(0, 256, size=24 << 20, dtype=np.uint8)
+    shards, at = [], 0
+    for m in range(16):
+        for dtype, es in (("u8", 1), ("bf16", 2), ("f32", 4), ("i64", 8)):
+            if m % es:
+                continue
+            nbytes = int(rng.integers(40, 400)) * 1024 + int(rng.integers(0, 64)) * es
+            start = (at + 255) // 256 * 256 + m
+            shards.append(Shard(f"a{m}_{dtype}", dtype, (nbytes // es,), (1,), start, 100 * m + es))
+            at = start + nbytes
+    assert at < arena.size
+    w = _adhoc(arena, shards, 256)
+    want, offs, tab = gu.oracle_image(w)
+    for chunk_bytes in (16384, 8192, 32768):
+        ds.ds_config_set("chunk_bytes", chunk_bytes)
+        print(f"[case] byte alignments, chunk {chunk_bytes}", flush=True)
+        dw = gu.DeviceWorkload(w)
+        try:
+            got = dw.pack()
+            assert gu.first_mismatch(got, want) is None, (chunk_bytes, gu.first_mismatch(got, want))
+            dw.arena.fill_(0x5A)
+            dw.unpack(want)
+            keep = w.arena.copy()
+            w.arena[:] = 0x5A
+            orc.unpack(tab, len(shards), want)
+            bad = gu.first_mismatch(dw.arena_host(), w.arena)
+            w.arena[:] = keep
+            assert bad is None, (chunk_bytes, bad)
+        finally:
+            dw.close()
+            ds.ds_config_set("chunk_bytes", 16384)
