@@ -358,3 +358,47 @@ def test_image_diff_by_brute_force():
             want.append(flag)
         assert orc.image_diff(a, b, block) == want
         assert len(want) == -(-n // block)
+
+
+def test_image_compress_block_elision_by_hand_and_by_brute_force():
+    """The block-elision oracle (oracle/image_compress.py): a hand-made image; flags against a byte loop on
+    random images with planted constant, periodic and almost-constant blocks; decompress(compress(x)) == x;
+    the position table is the running count of kept blocks."""
+    from oracle import image_compress as ic
+    # by hand: 4 blocks of 32 bytes: zeros | 0..31 | a 16-byte pattern twice | the pattern, last byte changed
+    pat = bytes(range(100, 116))
+    img = np.frombuffer(bytes(32) + bytes(range(32)) + pat + pat + pat + pat[:15] + b"\x00", dtype=np.uint8).copy()
+    keep, pos, patterns, packed = ic.compress(img, 32)
+    assert keep.tolist() == [0, 1, 0, 1] and pos.tolist() == [0, 0, 1, 1, 2]
+    assert patterns[0].tolist() == [0] * 16 and bytes(patterns[2]) == pat and patterns[1].tolist() == list(range(16))
+    assert bytes(packed) == bytes(range(32)) + pat + pat[:15] + b"\x00"
+    assert ic.compressed_bytes(keep, 32) == 2 * 32 + 4 * 20
+    assert np.array_equal(ic.decompress(keep, pos, patterns, packed, img.size, 32), img)
+    # a period of 8 divides 16: constant; a period of 32 does not
+    p8 = np.tile(np.arange(8, dtype=np.uint8), 8)
+    p32 = np.tile(np.arange(32, dtype=np.uint8), 2)
+    assert ic.compress(p8, 64)[0].tolist() == [0] and ic.compress(p32, 64)[0].tolist() == [1]
+    rng = np.random.default_rng(11)
+    for trial in range(30):
+        block = int(rng.choice([16, 48, 64, 256, 1024]))
+        n = int(rng.integers(1, 40)) * 16 * int(rng.integers(1, 9))
+        img = rng.integers(0, 256, n, dtype=np.uint8)
+        for k in range(-(-n // block)):
+            kind = rng.integers(0, 4)
+            blk = img[k * block:(k + 1) * block]
+            if kind == 0:
+                blk[:] = int(rng.integers(0, 2)) * 255
+            elif kind == 1:
+                blk[:] = np.tile(rng.integers(0, 256, 16, dtype=np.uint8), -(-blk.size // 16))[:blk.size]
+            elif kind == 2 and blk.size > 16:
+                blk[:] = 7
+                blk[int(rng.integers(16, blk.size))] = 8     # one byte off, not in the first unit
+        keep, pos, patterns, packed = ic.compress(img, block)
+        for k in range(keep.size):                            # the definition, byte by byte
+            blk = img[k * block:(k + 1) * block]
+            const = all(blk[i] == blk[i % 16] for i in range(blk.size))
+            assert keep[k] == (0 if const else 1), (trial, k)
+            assert pos[k + 1] == pos[k] + keep[k]
+            assert bytes(patterns[k]) == bytes(blk[:16])
+        assert packed.size == int(pos[-1]) * block
+        assert np.array_equal(ic.decompress(keep, pos, patterns, packed, n, block), img), trial
