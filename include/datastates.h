@@ -525,6 +525,29 @@ int ds_image_diff(const void *image_a_dev, const void *image_b_dev, uint64_t nby
                   uint32_t *changed_dev, void *stream);
 
 /*
+ * For compressed snapshots (the other data reduction the paper's conclusions name
+ * as future work; an experiment here, the engine does not use it): block elision.
+ * The image (nbytes, a multiple of 16; device memory, 16-byte aligned) is cut into
+ * blocks of block_bytes (a power of two >= 16 KiB; the last block may be short).
+ * A block all of whose 16-byte units equal its first one (zero padding,
+ * zero-initialised optimizer moments, fills whose period divides 16) is CONSTANT
+ * and is replaced by that unit.  Outputs, all device memory of the caller:
+ *   keep_dev[k]      1 if block k is stored whole, 0 if it is constant (n_blocks x u32)
+ *   pos_dev[k]       kept blocks before block k; pos_dev[n_blocks] = their number
+ *                    (n_blocks + 1 x u32)
+ *   patterns_dev     the first 16 bytes of every block (n_blocks x 16 bytes)
+ *   packed_dev       the kept blocks one behind the other, block k in the slot of
+ *                    block_bytes at pos_dev[k] * block_bytes (capacity: n_blocks slots;
+ *                    of a short last block only its own bytes are written)
+ * What has to leave the device is pos_dev[n_blocks] slots of packed_dev, the
+ * patterns and the flags.  Asynchronous on `stream`.  The paper gives no scheme:
+ * this one is the library's, defined by oracle/image_compress.py for the tests.
+ * Errors: DS_EINVAL, DS_ERANGE, DS_EHIP.
+ */
+int ds_image_compress(const void *image_dev, uint64_t nbytes, uint64_t block_bytes, uint32_t *keep_dev,
+                      uint32_t *pos_dev, void *patterns_dev, void *packed_dev, void *stream);
+
+/*
  * Tunables for experiments, read when a plan is created / a kernel launched:
  *   "chunk_bytes"   image bytes per work-group chunk: 8, 16 (default) or 32 KiB
  *   "variant"       0 = default (non-temporal accesses; the lean gather writes the image with

@@ -39,7 +39,7 @@ EXPORTS = [
     "ds_plan_shard_shape", "ds_ckpt_create", "ds_ckpt_flush_snapshot", "ds_ckpt_write_region", "ds_ckpt_append",
     "ds_ckpt_finish", "ds_ckpt_open", "ds_ckpt_close", "ds_ckpt_layout_info", "ds_ckpt_tensor_info",
     "ds_ckpt_object_at", "ds_ckpt_object_read", "ds_ckpt_matches_plan", "ds_ckpt_restore", "ds_event_trace",
-    "ds_image_diff", "ds_pack_noalloc",
+    "ds_image_diff", "ds_pack_noalloc", "ds_image_compress",
 ]
 
 
@@ -210,6 +210,7 @@ def _load() -> ctypes.CDLL:
         "ds_ckpt_restore": ([vp, vp, vp, u32, u32, vp, P(vp)], ctypes.c_int),
         "ds_event_trace": ([vp, P(ds_trace_rec), sz, P(sz)], ctypes.c_int),
         "ds_image_diff": ([vp, vp, u64, u64, vp, vp], ctypes.c_int),
+        "ds_image_compress": ([vp, u64, u64, vp, vp, vp, vp, vp], ctypes.c_int),
     }
     for name, (args, res) in sig.items():
         fn = getattr(L, name)
@@ -547,3 +548,9 @@ def ds_event_trace(ev: int) -> List[dict]:
 def ds_image_diff(image_a_dev: int, image_b_dev: int, nbytes: int, block_bytes: int, changed_dev: int,
                   stream: int = 0) -> None:
     _check(_lib.ds_image_diff(image_a_dev, image_b_dev, nbytes, block_bytes, changed_dev, stream), "ds_image_diff")
+
+
+def ds_image_compress(image_dev: int, nbytes: int, block_bytes: int, keep_dev: int, pos_dev: int, patterns_dev: int,
+                      packed_dev: int, stream: int = 0) -> None:
+    _check(_lib.ds_image_compress(image_dev, nbytes, block_bytes, keep_dev, pos_dev, patterns_dev, packed_dev, stream),
+           "ds_image_compress")

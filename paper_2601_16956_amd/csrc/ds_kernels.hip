@@ -877,7 +877,109 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 4))) voi
   if (__ballot(diff != 0) != 0 && (threadIdx.x & (kWave - 1)) == 0) atomicOr(flags + (first >> units_per_block_log2), 1u);
 }
 
+// ---- block elision of an image (the compressed-snapshot experiment) ------------------------------------
+// keep[k] = 1 if some 16-byte unit of block k differs from the block's first unit.  One work-group looks at
+// 1024 units (16 KiB), which lie in one block (the block size is a power of two of at least 16 KiB).
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 4))) void ds_constant_blocks_kernel(
+    const u32x4 *__restrict__ img, uint64_t n_units, uint32_t units_per_block_log2, uint32_t *__restrict__ keep) {
+  const uint32_t n_groups = (uint32_t)((n_units + 1023) / 1024), span = (n_groups + 7) / 8;
+  const uint32_t g = (blockIdx.x & 7u) * span + (blockIdx.x >> 3);
+  if (g >= n_groups) return;
+  const uint64_t first = (uint64_t)g * 1024;
+  const uint64_t left = n_units - first;
+  const uint32_t mine = left < 1024 ? (uint32_t)left : 1024u;
+  const uint64_t block = first >> units_per_block_log2;
+  const u32x4 ref = img[block << units_per_block_log2];
+  u32x4 x[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+    if (threadIdx.x + 256u * i < mine) x[i] = __builtin_nontemporal_load(img + first + threadIdx.x + 256 * i);
+  uint32_t diff = 0;
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+    if (threadIdx.x + 256u * i < mine) {
+      const u32x4 d = x[i] ^ ref;
+      diff |= d.x | d.y | d.z | d.w;
+    }
+  if (__ballot(diff != 0) != 0 && (threadIdx.x & (kWave - 1)) == 0) atomicOr(keep + block, 1u);
+}
+
+// pos[k] = keep[0] + ... + keep[k-1], pos[n] = the sum.  One work-group walks the array 256 entries at a time.
+__global__ __launch_bounds__(256) void ds_exclusive_scan_kernel(const uint32_t *__restrict__ keep, uint32_t *__restrict__ pos,
+                                                                 uint64_t n) {
+  __shared__ uint32_t wave_sum[4];
+  const uint32_t tid = threadIdx.x, lane = tid & (kWave - 1), wv = tid / kWave;
+  uint32_t carry = 0;
+  for (uint64_t base = 0; base < n; base += 256) {
+    const uint64_t i = base + tid;
+    const uint32_t x = i < n ? keep[i] : 0u;
+    const uint32_t incl = wave_inclusive_scan(x, lane);
+    if (lane == kWave - 1) wave_sum[wv] = incl;
+    __syncthreads();
+    uint32_t before = carry;
+    for (uint32_t w = 0; w < wv; ++w) before += wave_sum[w];
+    if (i < n) pos[i] = before + incl - x;
+    carry += wave_sum[0] + wave_sum[1] + wave_sum[2] + wave_sum[3];
+    __syncthreads();
+  }
+  if (tid == 0) pos[n] = carry;
+}
+
+// Kept blocks go to their slots in `packed`, one behind the other; every block leaves its first unit in
+// `patterns`.  Same work-group shape as above.
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 4))) void ds_pack_kept_blocks_kernel(
+    const u32x4 *__restrict__ img, uint64_t n_units, uint32_t units_per_block_log2, const uint32_t *__restrict__ keep,
+    const uint32_t *__restrict__ pos, u32x4 *__restrict__ patterns, u32x4 *__restrict__ packed) {
+  const uint32_t n_groups = (uint32_t)((n_units + 1023) / 1024), span = (n_groups + 7) / 8;
+  const uint32_t g = (blockIdx.x & 7u) * span + (blockIdx.x >> 3);
+  if (g >= n_groups) return;
+  const uint64_t first = (uint64_t)g * 1024;
+  const uint64_t left = n_units - first;
+  const uint32_t mine = left < 1024 ? (uint32_t)left : 1024u;
+  const uint64_t block = first >> units_per_block_log2;
+  const uint64_t in_block = first - (block << units_per_block_log2);
+  if (in_block == 0 && threadIdx.x == 0) patterns[block] = img[first];
+  if (!keep[block]) return;
+  u32x4 *out = packed + ((uint64_t)pos[block] << units_per_block_log2) + in_block;
+  u32x4 x[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+    if (threadIdx.x + 256u * i < mine) x[i] = __builtin_nontemporal_load(img + first + threadIdx.x + 256 * i);
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+    if (threadIdx.x + 256u * i < mine) __builtin_nontemporal_store(x[i], out + threadIdx.x + 256 * i);
+}
+
 }  // namespace
+
+extern "C" int ds_image_compress(const void *image_dev, uint64_t nbytes, uint64_t block_bytes, uint32_t *keep_dev,
+                                 uint32_t *pos_dev, void *patterns_dev, void *packed_dev, void *stream) {
+  if (nbytes == 0) return DS_OK;
+  if (!image_dev || !keep_dev || !pos_dev || !patterns_dev || !packed_dev ||
+      (((uintptr_t)image_dev | (uintptr_t)patterns_dev | (uintptr_t)packed_dev) & 15) ||
+      (((uintptr_t)keep_dev | (uintptr_t)pos_dev) & 3))
+    return DS_EINVAL;
+  // a power of two of at least 16 KiB, so that a work-group's piece lies in one block
+  if (block_bytes < 16384 || (block_bytes & (block_bytes - 1)) || (nbytes & 15)) return DS_ERANGE;
+  const uint64_t n_units = nbytes >> 4;
+  const uint64_t groups = (n_units + 1023) / 1024;
+  if (groups > 0x7FFFFFF0ull) return DS_ERANGE;
+  const uint64_t n_blocks = (nbytes + block_bytes - 1) / block_bytes;
+  const uint32_t upb_log2 = (uint32_t)__builtin_ctzll(block_bytes >> 4);
+  const uint32_t grid = (uint32_t)(((groups + 7) / 8) * 8);
+  hipStream_t st = (hipStream_t)stream;
+  hipLaunchKernelGGL(ds_clear_flags_kernel, dim3((uint32_t)((n_blocks + 255) / 256)), dim3(256), 0, st, keep_dev, n_blocks);
+  DS_HIP_TRY(hipGetLastError());
+  hipLaunchKernelGGL(ds_constant_blocks_kernel, dim3(grid), dim3(256), 0, st, (const u32x4 *)image_dev, n_units, upb_log2,
+                     keep_dev);
+  DS_HIP_TRY(hipGetLastError());
+  hipLaunchKernelGGL(ds_exclusive_scan_kernel, dim3(1), dim3(256), 0, st, keep_dev, pos_dev, n_blocks);
+  DS_HIP_TRY(hipGetLastError());
+  hipLaunchKernelGGL(ds_pack_kept_blocks_kernel, dim3(grid), dim3(256), 0, st, (const u32x4 *)image_dev, n_units, upb_log2,
+                     keep_dev, pos_dev, (u32x4 *)patterns_dev, (u32x4 *)packed_dev);
+  DS_HIP_TRY(hipGetLastError());
+  return DS_OK;
+}
 
 extern "C" int ds_image_diff(const void *image_a_dev, const void *image_b_dev, uint64_t nbytes, uint64_t block_bytes,
                              uint32_t *changed_dev, void *stream) {

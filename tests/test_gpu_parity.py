@@ -650,3 +650,60 @@ def test_contiguous_tensors_at_every_byte_alignment():
         finally:
             dw.close()
             ds.ds_config_set("chunk_bytes", 16384)
+
+
+@pytest.mark.parametrize("block_bytes", [16384, 65536, 1 << 20])
+def test_image_compress_equals_the_block_elision_oracle(block_bytes):
+    """ds_image_compress against oracle/image_compress.py: flags, positions, patterns and the packed blocks,
+    on images with planted constant blocks (zeros, 0xFF, a 16-byte pattern), blocks that differ from constant in
+    one byte (first / last unit), a ragged last block; then the oracle's decompression of the DEVICE's output
+    must give the image back."""
+    import torch
+    from oracle import image_compress as ic
+    ds, orc, gu = _mods()
+    rng = np.random.default_rng(77)
+    s = torch.cuda.current_stream().cuda_stream
+    for nbytes in (16, block_bytes, block_bytes * 5 + 16 * 37, block_bytes * 40):
+        img = rng.integers(0, 256, size=nbytes, dtype=np.uint8)
+        n_blocks = -(-nbytes // block_bytes)
+        for k in range(n_blocks):
+            blk = img[k * block_bytes:(k + 1) * block_bytes]
+            kind = k % 6
+            if kind == 0:
+                blk[:] = 0
+            elif kind == 1:
+                blk[:] = np.tile(rng.integers(0, 256, 16, dtype=np.uint8), blk.size // 16)
+            elif kind == 2 and blk.size > 16:
+                blk[:] = 0xFF
+                blk[blk.size - 1] = 0xFE                     # the last byte of the block
+            elif kind == 3 and blk.size > 16:
+                blk[:] = 0
+                blk[16] = 1                                  # the first byte behind the first unit
+        print(f"[case] compress nbytes={nbytes} block={block_bytes}", flush=True)
+        keep_w, pos_w, pat_w, packed_w = ic.compress(img, block_bytes)
+        d_img = torch.from_numpy(img).cuda()
+        keep = torch.full((n_blocks,), 9, dtype=torch.int32, device="cuda")          # stale values must be cleared
+        pos = torch.full((n_blocks + 1,), 9, dtype=torch.int32, device="cuda")
+        pats = torch.full((n_blocks * 16,), 0xCC, dtype=torch.uint8, device="cuda")
+        packed = torch.full((n_blocks * block_bytes,), 0xCC, dtype=torch.uint8, device="cuda")
+        ds.ds_image_compress(d_img.data_ptr(), nbytes, block_bytes, keep.data_ptr(), pos.data_ptr(), pats.data_ptr(),
+                             packed.data_ptr(), s)
+        torch.cuda.synchronize()
+        keep_g = keep.cpu().numpy().astype(np.uint32)
+        pos_g = pos.cpu().numpy().astype(np.uint32)
+        assert keep_g.tolist() == keep_w.tolist(), nbytes
+        assert pos_g.tolist() == pos_w.tolist(), nbytes
+        assert np.array_equal(pats.cpu().numpy().reshape(-1, 16), pat_w)
+        packed_g = packed.cpu().numpy()
+        for k in range(n_blocks):
+            if keep_w[k]:
+                length = min(block_bytes, nbytes - k * block_bytes)
+                at = int(pos_w[k]) * block_bytes
+                assert np.array_equal(packed_g[at:at + length], packed_w[at:at + length]), (nbytes, k)
+        assert np.all(packed_g[int(pos_w[-1]) * block_bytes:] == 0xCC)                 # nothing behind the kept blocks
+        back = ic.decompress(keep_g, pos_g, pats.cpu().numpy().reshape(-1, 16), packed_g, nbytes, block_bytes)
+        assert np.array_equal(back, img)
+    with pytest.raises(ds.DsError) as e:
+        ds.ds_image_compress(d_img.data_ptr(), nbytes, 4096, keep.data_ptr(), pos.data_ptr(), pats.data_ptr(),
+                             packed.data_ptr(), 0)
+    assert e.value.code == ds.DS_ERANGE
