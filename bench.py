@@ -218,8 +218,9 @@ def traffic_from_profile(c: Ctx, name: str):
     return int(m.group(1)), src
 
 
-def timed_region(c: Ctx, L: Loaded, cfg, steps, warmup):
-    """K snapshots back to back, each gated and waited for; returns the bench fields of that region."""
+def timed_region(c: Ctx, L: Loaded, cfg, steps, warmup, extras=True):
+    """K snapshots back to back, each gated and waited for; returns the bench fields of that region.  With
+    `extras` also one isolated snapshot and the same steps without the per-step wait."""
     ds, torch = c.ds, c.torch
     eng = c.engine(cfg)
     try:
@@ -240,22 +241,24 @@ def timed_region(c: Ctx, L: Loaded, cfg, steps, warmup):
             submit_ms += st["submit_host_ms"]
             launches += st["n_pack_launches"]
             ds.ds_event_destroy(ev)
-        # one isolated snapshot: request -> whole image resident in the host ring
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        ev = ds.ds_snapshot_async(eng, L.plan, c.stream)
-        ds.ds_event_wait(ev)
-        latency_ms = (time.perf_counter() - t0) * 1e3
-        one = ds.ds_event_stats(ev)
-        ds.ds_event_destroy(ev)
-        # the same steps without the per-step wait
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        pevs = snapshot_steps(c, eng, L.plan, steps, pipelined=True)
-        torch.cuda.synchronize()
-        pipelined = L.payload * steps / (time.perf_counter() - t0) / 1e9
-        for ev in pevs:
+        latency_ms, one, pipelined = 0.0, {"total_ms": 0.0}, 0.0
+        if extras:
+            # one isolated snapshot: request -> whole image resident in the host ring
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            ev = ds.ds_snapshot_async(eng, L.plan, c.stream)
+            ds.ds_event_wait(ev)
+            latency_ms = (time.perf_counter() - t0) * 1e3
+            one = ds.ds_event_stats(ev)
             ds.ds_event_destroy(ev)
+            # the same steps without the per-step wait
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            pevs = snapshot_steps(c, eng, L.plan, steps, pipelined=True)
+            torch.cuda.synchronize()
+            pipelined = L.payload * steps / (time.perf_counter() - t0) / 1e9
+            for ev in pevs:
+                ds.ds_event_destroy(ev)
     finally:
         ds.ds_engine_destroy(eng)
     achieved = L.algo_bytes * steps / (pack_ms * 1e-3) / 1e9 if pack_ms > 0 else 0.0
@@ -1087,7 +1090,7 @@ def main() -> int:
     measure_link(c)
 
     if args.timed_only:
-        tr = timed_region(c, L, cfg, args.steps, args.warmup)
+        tr = timed_region(c, L, cfg, args.steps, args.warmup, extras=False)
         print(json.dumps({"metric": METRIC, "value": tr["value"], "unit": "GB/s", "steps": args.steps,
                           "warmup": args.warmup, "ms_per_step": tr["ms_per_step"], "workload": args.workload,
                           "timed_only": True, "roofline": tr["roofline"]}), flush=True)
