@@ -214,7 +214,8 @@ typedef struct ds_engine_opts {
   uint64_t host_ring_bytes;  /* pinned host ring capacity, allocated and pinned once; the paper's
                                 single tunable (Sec. V-B).  0 = 2 GiB                              */
   uint64_t d2h_chunk_bytes;  /* size of one ring slot = one device-to-host copy; multiple of 4096.
-                                0 = 32 MiB                                                          */
+                                0 = 128 MiB (on one copy stream the gap between two copies costs
+                                4 % of the link at 32 MiB, 1 % at 128 MiB)                          */
   uint64_t stage_slot_bytes; /* image bytes per gather launch (the last launch of an image may be
                                 shorter); multiple of d2h_chunk_bytes.  0 = 1 GiB                   */
   uint32_t stage_slots;      /* device staging is one ring of stage_slots * stage_slot_bytes bytes
@@ -224,8 +225,11 @@ typedef struct ds_engine_opts {
                                 alone, whatever the link, the host ring or the storage are doing    */
   uint32_t pack_grid_limit;  /* max work-groups resident per gather launch; 0 = one per chunk       */
   uint32_t flags;            /* DS_ENGINE_*                                                         */
-  uint32_t copy_streams;     /* copy streams the chunks alternate over: 1 or 2.  0 = 2 (the gap
-                                between two copies on one stream is hidden by the other stream's copy) */
+  uint32_t copy_streams;     /* copy streams the chunks alternate over: 1 or 2.  0 = 1.  With 2 the gap
+                                between two copies on one stream is hidden by the other stream's copy
+                                (+2 % at 32 MiB chunks) -- when the two copies share the link evenly;
+                                measured, they do in the first engine of a process and share it 2:1 in
+                                later ones (-17 %), so one stream with large chunks is the default     */
   uint64_t first_launch_bytes; /* image bytes of the first gather launch of a snapshot; multiple of
                                 d2h_chunk_bytes, <= stage_slot_bytes.  A short first launch lets the
                                 first copy start earlier; the gather of the rest then runs beside that
@@ -234,7 +238,14 @@ typedef struct ds_engine_opts {
 
 /* Allocates the pinned ring, the device staging, a gather stream and the copy streams
  * (all at the default priority) and a host thread that issues the work.
- * Uses the current device.  Errors: DS_EINVAL, DS_ENOMEM, DS_EHIP. */
+ * Uses the current device.  The pinned ring and the device staging of a
+ * destroyed engine are kept (one allocation each per process, the largest seen)
+ * and handed to the next engine that fits into them: pinning is slow, a fresh
+ * allocation is slow on first touch, and the first pinned allocation of a
+ * process was measured to be the one the link writes fastest; the engine's
+ * streams are reused likewise.  ds_config_set("drop_pinned_cache", 1) frees the
+ * memory.
+ * Errors: DS_EINVAL, DS_ENOMEM, DS_EHIP. */
 int ds_engine_create(const ds_engine_opts *opts, ds_engine **out);
 
 /* Waits for all snapshots in flight, then frees everything.  Events created
@@ -558,6 +569,8 @@ int ds_image_compress(const void *image_dev, uint64_t nbytes, uint64_t block_byt
  *                   addresses that are not multiples of 16 are then read with unaligned loads)
  *   "grid_limit"    work-groups per launch of ds_pack / ds_unpack (each then walks several chunks);
  *                   0 = one per chunk (default).  Engines have their own pack_grid_limit
+ *   "drop_pinned_cache"   (set only) a non-zero value frees the pinned ring and the device staging the
+ *                   library keeps from the last destroyed engine for the next one (see ds_engine_create)
  *   "io_uring_available"  (get only) 1 if this process can set up an io_uring, else 0
  * Returns DS_EINVAL for an unknown key or a value out of range.
  */

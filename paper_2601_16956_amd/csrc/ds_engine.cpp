@@ -36,6 +36,142 @@
 
 namespace {
 constexpr int kMaxCopyStreams = 2;
+
+// The pinned ring of a destroyed engine is kept for the next engine of the process (one allocation, the
+// largest seen): pinning 2 GiB takes hundreds of milliseconds, and -- measured -- a ring allocated later in a
+// process's life, when the first one has been freed, can be backed by memory the link writes at 30 GB/s
+// instead of 57 (its later slots; the first allocation of a process does not show it).  The paper's pool is
+// allocated and pinned once and reused by every request (Sec. V-A1); this extends that to engines.
+struct PinnedCache {
+  std::mutex mu;
+  uint8_t *ptr = nullptr;
+  uint64_t bytes = 0;
+} g_pinned;
+
+hipError_t ring_alloc(uint64_t need, uint8_t **out, uint64_t *cap) {
+  {
+    std::lock_guard<std::mutex> lk(g_pinned.mu);
+    if (g_pinned.ptr && g_pinned.bytes >= need) {
+      *out = g_pinned.ptr;
+      *cap = g_pinned.bytes;
+      g_pinned.ptr = nullptr;
+      g_pinned.bytes = 0;
+      return hipSuccess;
+    }
+  }
+  *cap = need;
+  return hipHostMalloc((void **)out, need, hipHostMallocPortable);
+}
+
+// The same for the device staging: device memory that has just been allocated is slow on first touch (the
+// first snapshot or restore of a new engine ran at 30-50 GB/s instead of 56), so an engine hands its staging
+// on to the next one of the process on the same device.
+struct StageCache {
+  std::mutex mu;
+  uint8_t *ptr = nullptr;
+  uint64_t bytes = 0;
+  int device = -1;
+} g_stage;
+
+hipError_t stage_alloc(int dev, uint64_t need, uint8_t **out, uint64_t *cap) {
+  {
+    std::lock_guard<std::mutex> lk(g_stage.mu);
+    if (g_stage.ptr && g_stage.device == dev && g_stage.bytes >= need) {
+      *out = g_stage.ptr;
+      *cap = g_stage.bytes;
+      g_stage.ptr = nullptr;
+      g_stage.bytes = 0;
+      return hipSuccess;
+    }
+  }
+  *cap = need;
+  return hipMalloc((void **)out, need);
+}
+
+void stage_free(int dev, uint8_t *p, uint64_t cap) {
+  {
+    std::lock_guard<std::mutex> lk(g_stage.mu);
+    if (!g_stage.ptr || (g_stage.device == dev && cap > g_stage.bytes)) {
+      std::swap(p, g_stage.ptr);
+      std::swap(cap, g_stage.bytes);
+      g_stage.device = dev;
+    }
+  }
+  if (p) (void)hipFree(p);
+}
+
+void ring_free(uint8_t *p, uint64_t cap) {
+  {
+    std::lock_guard<std::mutex> lk(g_pinned.mu);
+    if (!g_pinned.ptr || cap > g_pinned.bytes) {
+      std::swap(p, g_pinned.ptr);
+      std::swap(cap, g_pinned.bytes);
+    }
+  }
+  if (p) (void)hipHostFree(p);
+}
+
+// The streams of a destroyed engine are kept for the next engine of the process on the same device.  The
+// runtime spreads streams over a few hardware queues in the order they are created; measured, the two copy
+// streams of an engine created later in a process's life (after other engines' streams had been created and
+// destroyed) shared the link 2:1 instead of 1:1 and the snapshot ran at 45 GB/s instead of 56.  Reusing the
+// first engine's streams keeps the mapping the first engine had.
+struct PooledStream {
+  int device;
+  uint64_t id;  // order of creation: an engine takes the oldest idle ones, so the roles (gather, copy 0, copy 1)
+                // fall to the same streams from one engine to the next
+  hipStream_t stream;
+};
+struct StreamPool {
+  std::mutex mu;
+  std::vector<PooledStream> idle;
+  uint64_t next_id = 0;
+} g_streams;
+
+hipError_t stream_take(int dev, PooledStream *out) {
+  {
+    std::lock_guard<std::mutex> lk(g_streams.mu);
+    size_t best = g_streams.idle.size();
+    for (size_t i = 0; i < g_streams.idle.size(); ++i)
+      if (g_streams.idle[i].device == dev && (best == g_streams.idle.size() || g_streams.idle[i].id < g_streams.idle[best].id))
+        best = i;
+    if (best < g_streams.idle.size()) {
+      *out = g_streams.idle[best];
+      g_streams.idle.erase(g_streams.idle.begin() + (long)best);
+      return hipSuccess;
+    }
+    out->id = g_streams.next_id++;
+  }
+  out->device = dev;
+  return hipStreamCreateWithFlags(&out->stream, hipStreamNonBlocking);
+}
+
+void stream_give(const PooledStream &s) {
+  if (!s.stream) return;
+  try {
+    std::lock_guard<std::mutex> lk(g_streams.mu);
+    g_streams.idle.push_back(s);
+  } catch (const std::bad_alloc &) {
+    (void)hipStreamDestroy(s.stream);
+  }
+}
+}  // namespace
+
+// frees the cached ring and staging (ds_config_set("drop_pinned_cache", 1))
+void ds_drop_pinned_cache() {
+  uint8_t *p = nullptr, *d = nullptr;
+  {
+    std::lock_guard<std::mutex> lk(g_pinned.mu);
+    std::swap(p, g_pinned.ptr);
+    g_pinned.bytes = 0;
+  }
+  {
+    std::lock_guard<std::mutex> lk(g_stage.mu);
+    std::swap(d, g_stage.ptr);
+    g_stage.bytes = 0;
+  }
+  if (p) (void)hipHostFree(p);
+  if (d) (void)hipFree(d);
 }
 
 struct ds_event;
@@ -66,6 +202,8 @@ struct ds_engine {
   hipStream_t copy_stream[kMaxCopyStreams] = {nullptr, nullptr};
   uint8_t *stage = nullptr;  // device
   uint8_t *ring = nullptr;   // pinned host
+  uint64_t ring_cap = 0;     // bytes of the allocation behind `ring` (it may come from the process's cache)
+  uint64_t stage_cap = 0;    // the same for `stage`
   // engine-owned events, reused by every snapshot
   std::vector<hipEvent_t> ring_done;                    // copy into ring slot r finished
   std::vector<uint8_t> ring_busy;  // consumer mode: slot holds data not yet released
@@ -76,6 +214,8 @@ struct ds_engine {
   uint64_t stage_bytes = 0, stage_head = 0;
   std::list<StageRegion> regions;      // pieces of staging whose last gather may still be read by copies
   std::vector<hipEvent_t> event_pool;  // spare events of regions that have been taken over
+
+  std::vector<PooledStream> pooled;  // the streams above, as taken from the process's pool
 
   std::mutex mu;
   std::condition_variable cv;
@@ -424,14 +564,15 @@ void destroy_events(std::vector<hipEvent_t> &v) {
 }
 
 void free_engine(ds_engine *g) {
-  for (int c = 0; c < kMaxCopyStreams; ++c)
-    if (g->copy_stream[c]) (void)hipStreamDestroy(g->copy_stream[c]);
+  // the streams are idle here (the callers have synchronised them, or nothing was ever enqueued); they go back
+  // to the process's pool in the order they were taken
+  for (const PooledStream &ps : g->pooled) stream_give(ps);
+  g->pooled.clear();
   forget_regions(g);
   destroy_events(g->event_pool);
   destroy_events(g->ring_done);
-  if (g->pack_stream) (void)hipStreamDestroy(g->pack_stream);
-  if (g->stage) (void)hipFree(g->stage);
-  if (g->ring) (void)hipHostFree(g->ring);
+  if (g->stage) stage_free(g->device, g->stage, g->stage_cap);
+  if (g->ring) ring_free(g->ring, g->ring_cap);
   delete g;
 }
 
@@ -442,11 +583,11 @@ extern "C" {
 int ds_engine_create(const ds_engine_opts *o, ds_engine **out) {
   if (!o || !out) return DS_EINVAL;
   if (o->flags & ~(DS_ENGINE_AUTO_RELEASE | DS_ENGINE_TRACE)) return DS_EINVAL;
-  const uint64_t chunk = o->d2h_chunk_bytes ? o->d2h_chunk_bytes : (32ull << 20);
+  const uint64_t chunk = o->d2h_chunk_bytes ? o->d2h_chunk_bytes : (128ull << 20);
   const uint64_t ring_bytes = o->host_ring_bytes ? o->host_ring_bytes : (2ull << 30);
   const uint64_t slot = o->stage_slot_bytes ? o->stage_slot_bytes : (1ull << 30);
   const uint32_t slots = o->stage_slots ? o->stage_slots : 2;
-  const uint32_t ncs = o->copy_streams ? o->copy_streams : 2;
+  const uint32_t ncs = o->copy_streams ? o->copy_streams : 1;
   const uint64_t first = o->first_launch_bytes ? o->first_launch_bytes : slot;
   if ((chunk & 4095) || slot % chunk || first % chunk || first > slot || ring_bytes < chunk ||
       ncs > (uint32_t)kMaxCopyStreams || slots > 1024)
@@ -465,16 +606,25 @@ int ds_engine_create(const ds_engine_opts *o, ds_engine **out) {
   g->ring_slots = (uint32_t)(ring_bytes / chunk);
   g->n_copy_streams = (int)ncs;
   hipError_t e = hipGetDevice(&g->device);
-  if (e == hipSuccess) e = hipStreamCreateWithFlags(&g->pack_stream, hipStreamNonBlocking);
-  for (int c = 0; c < g->n_copy_streams && e == hipSuccess; ++c)
-    e = hipStreamCreateWithFlags(&g->copy_stream[c], hipStreamNonBlocking);
+  try {
+    for (int k = 0; k < 1 + g->n_copy_streams && e == hipSuccess; ++k) {
+      PooledStream ps = {g->device, 0, nullptr};
+      e = stream_take(g->device, &ps);
+      if (e != hipSuccess) break;
+      g->pooled.push_back(ps);
+      (k == 0 ? g->pack_stream : g->copy_stream[k - 1]) = ps.stream;
+    }
+  } catch (const std::bad_alloc &) {
+    free_engine(g);
+    return DS_ENOMEM;
+  }
   if (e == hipSuccess) {
-    e = hipMalloc((void **)&g->stage, slot * slots);
+    e = stage_alloc(g->device, slot * slots, &g->stage, &g->stage_cap);
     if (e == hipErrorOutOfMemory) { free_engine(g); return DS_ENOMEM; }
   }
   if (e == hipSuccess) {
     // allocated and pinned once, reused by every snapshot (Sec. V-A1)
-    e = hipHostMalloc((void **)&g->ring, (uint64_t)g->ring_slots * chunk, hipHostMallocDefault);
+    e = ring_alloc((uint64_t)g->ring_slots * chunk, &g->ring, &g->ring_cap);
     if (e == hipErrorOutOfMemory) { free_engine(g); return DS_ENOMEM; }
   }
   try {
@@ -486,7 +636,7 @@ int ds_engine_create(const ds_engine_opts *o, ds_engine **out) {
     return DS_ENOMEM;
   }
   for (uint32_t r = 0; r < g->ring_slots && e == hipSuccess; ++r) {
-    e = hipEventCreate(&g->ring_done[r]);
+    e = hipEventCreateWithFlags(&g->ring_done[r], hipEventDisableTiming);  // only ever waited for, never timed
     // recorded once so that a wait on a never-used slot is a no-op by construction
     if (e == hipSuccess) e = hipEventRecord(g->ring_done[r], g->copy_stream[0]);
   }

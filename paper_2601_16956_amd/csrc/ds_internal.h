@@ -72,6 +72,7 @@ struct DsManifestEntry {
 int ds_flush_start_fds(ds_event *ev, int fd_buffered, int fd_direct, uint32_t threads, uint32_t flags, ds_flush **out);
 void ds_set_errno(int e);  // what ds_last_errno() returns on this thread
 bool ds_io_uring_available();  // can this process set up an io_uring?
+void ds_drop_pinned_cache();   // frees the pinned ring kept from a destroyed engine
 
 struct ds_plan {
   uint64_t align = 0;

@@ -208,6 +208,10 @@ int ds_config_set(const char *key, uint64_t value) {
     g_grid_limit.store(value);
     return DS_OK;
   }
+  if (!std::strcmp(key, "drop_pinned_cache")) {
+    if (value) ds_drop_pinned_cache();
+    return DS_OK;
+  }
   return DS_EINVAL;
 }
 

@@ -64,11 +64,11 @@ def test_full_size_pack_and_restore(name):
         orc.unpack(tab, n, want)
         print(f"[step] restored arena back at {time.time() - t0:.1f}s", flush=True)
         assert gu.first_mismatch(back, w.arena) is None, gu.first_mismatch(back, w.arena)
-        # the same image through the engine as the benchmark configures it (2 GiB ring of 32 MiB slots,
-        # 2 x 2 GiB staging, two copy streams), with a consumer that copies every chunk out of the ring
+        # the same image through the engine as the benchmark configures it (2 GiB ring of 128 MiB slots,
+        # 2 x 2 GiB staging, one copy stream), with a consumer that copies every chunk out of the ring
         import ctypes
         del image                                                  # the tensors hold the oracle's image again
-        eng = ds.ds_engine_create(2 << 30, 32 << 20, 2 << 30, 2, 0, 0, 2)
+        eng = ds.ds_engine_create(2 << 30, 128 << 20, 2 << 30, 2, 0, 0, 1)
         try:
             ev = ds.ds_snapshot_async(eng, dw.plan, s)
             got = np.empty(total, dtype=np.uint8)

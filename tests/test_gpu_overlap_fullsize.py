@@ -4,7 +4,7 @@ while the compute stream runs back-to-back 8192^3 bf16 GEMMs and a mutating upda
 Sec. IV-B: the state is immutable during forward/backward).  A consumer thread copies every chunk out of the
 ring; every host image must equal the CPU oracle's image of the mirror state at that snapshot's request, so a
 torn snapshot -- an update that overtook a gather, a ring slot or a piece of staging reused too early -- shows as
-a mismatch.  Three engines: the benchmark's (ring 2 GiB, staging 2 x 2 GiB), a ring smaller than the image, and
+a mismatch.  Three engines: the benchmark's (ring 2 GiB of 128 MiB slots, staging 2 x 2 GiB, one copy stream), a ring smaller than the image, and
 ring and staging both smaller than the image, which forces chunked double-buffering on both sides."""
 import ctypes
 import os
@@ -21,9 +21,10 @@ pytestmark = pytest.mark.gpu
 MiB, GiB = 1 << 20, 1 << 30
 ITERS = 5
 ENGINES = {
-    "ring_2GiB_staging_2x2GiB": dict(ring=2 * GiB, chunk=32 * MiB, slot=2 * GiB, slots=2),
-    "ring_512MiB_staging_2x2GiB": dict(ring=512 * MiB, chunk=32 * MiB, slot=2 * GiB, slots=2),
-    "ring_512MiB_staging_1x512MiB": dict(ring=512 * MiB, chunk=32 * MiB, slot=512 * MiB, slots=1),
+    # the benchmark's engine: one copy stream, 128 MiB ring slots
+    "ring_2GiB_staging_2x2GiB": dict(ring=2 * GiB, chunk=128 * MiB, slot=2 * GiB, slots=2, streams=1),
+    "ring_512MiB_staging_2x2GiB": dict(ring=512 * MiB, chunk=32 * MiB, slot=2 * GiB, slots=2, streams=2),
+    "ring_512MiB_staging_1x512MiB": dict(ring=512 * MiB, chunk=128 * MiB, slot=512 * MiB, slots=1, streams=1),
 }
 
 _cache = {}
@@ -65,7 +66,7 @@ def test_snapshots_under_the_gemm_stream_equal_the_oracle(name):
     descs = ds.make_descs(w.shards, arena.data_ptr())
     assert ds.ds_layout_assign(descs, n, w.align) == total
     plan = ds.ds_plan_create(descs, n, w.align, ds.DS_PLAN_STRICT | ds.DS_PLAN_CHECK_MEMORY)
-    eng = ds.ds_engine_create(cfg["ring"], cfg["chunk"], cfg["slot"], cfg["slots"], 0, 0, 2)
+    eng = ds.ds_engine_create(cfg["ring"], cfg["chunk"], cfg["slot"], cfg["slots"], 0, 0, cfg["streams"])
     M = 8192
     A = torch.randn(M, M, device="cuda", dtype=torch.bfloat16)
     B = torch.randn(M, M, device="cuda", dtype=torch.bfloat16)
