@@ -107,3 +107,43 @@ def parse_file(blob: bytes) -> dict:
         objects.setdefault(oid, bytearray()).extend(blob[off:off + ln])
     return {"align": align, "tensor_bytes": T, "log_end": E, "n_chunks": m, "tensors": tensors,
             "objects": {k: bytes(v) for k, v in objects.items()}, "image": blob[:T]}
+
+
+# ---- one shard table, several files --------------------------------------------------------------
+# A rank writes its checkpoint as several files (DataStates-LLM Sec. VI-D: 20 for a 7B rank); each
+# shard of the rank's table names the file it belongs to.  Every file is a checkpoint file as above,
+# built from the shards that name it; the rank's ONE image is the files' tensor regions one behind
+# the other, in file order.  Parity unpinned against the paper, which states the file count only.
+
+def rank_files(sizes: Sequence[int], file_of: Sequence[int], n_files: int, align: int):
+    """Where every shard goes when one table feeds `n_files` files.
+
+    Inside its file a shard sits at the next multiple of `align` behind the shard of the same file
+    that precedes it in the table (the canonical layout, file by file).  Returns
+    (offset_in_file per shard, tensor-region length per file, where each region starts in the image)."""
+    if len(sizes) != len(file_of):
+        raise FormatError("one file index per shard")
+    at = [0] * n_files
+    offs = []
+    for size, f in zip(sizes, file_of):
+        if not 0 <= f < n_files:
+            raise FormatError("file index out of range")
+        offs.append(at[f])
+        at[f] += size + (-size % align)
+    begins, run = [], 0
+    for f in range(n_files):
+        begins.append(run)
+        run += at[f]
+    return offs, at, begins
+
+
+def build_rank_files(align: int, image: bytes, tensors: Sequence[TensorEntry], file_of: Sequence[int],
+                     n_files: int, appends: Sequence[Sequence[Tuple[int, bytes]]]) -> List[bytes]:
+    """The files of one rank.  `image` is the rank's whole image, `tensors` the table in table order
+    with offsets INSIDE each shard's own file, appends[f] the object chunks of file f."""
+    _, regions, begins = rank_files([t[4] for t in tensors], file_of, n_files, align)
+    if len(image) != sum(regions):
+        raise FormatError("image length is not the sum of the regions")
+    return [build_file(align, image[begins[f]:begins[f] + regions[f]],
+                       [t for t, g in zip(tensors, file_of) if g == f], appends[f])
+            for f in range(n_files)]

@@ -97,6 +97,56 @@ def test_oracle_rules_on_random_files():
             fmt.parse_file(blob[:-1])
 
 
+def test_rank_files_by_hand_and_against_the_single_file_layout():
+    """One table, several files: a table small enough to lay out by hand; with one file the rule is the
+    canonical layout (the C oracle's, an implementation of its own); and every file built from the
+    rank's one image holds exactly the image of its own shards packed alone."""
+    # sizes 20, 5, 0, 16, 33 in files 1, 0, 1, 0, 2 at alignment 16:
+    #   file 0: the 5-byte shard at 0 (16 with padding), the 16-byte shard at 16      -> region 32
+    #   file 1: the 20-byte shard at 0 (32 with padding), the empty shard at 32       -> region 32
+    #   file 2: the 33-byte shard at 0                                                -> region 48
+    offs, regions, begins = fmt.rank_files([20, 5, 0, 16, 33], [1, 0, 1, 0, 2], 3, 16)
+    assert offs == [0, 0, 32, 16, 0] and regions == [32, 32, 48] and begins == [0, 32, 64]
+    # a file nobody names is empty and takes no room in the image
+    offs, regions, begins = fmt.rank_files([20, 5], [2, 0], 4, 16)
+    assert offs == [0, 0] and regions == [16, 0, 32, 0] and begins == [0, 16, 16, 48]
+    for bad in ([0, 3], [-1, 0]):
+        with pytest.raises(fmt.FormatError):
+            fmt.rank_files([1, 1], bad, 3, 16)
+
+    w = W.fragmentation(200, max_bytes=1 << 12, seed=77)
+    n = len(w.shards)
+    sizes = [s.nbytes for s in w.shards]
+    tab = orc.table(w.shards, w.arena.ctypes.data)
+    total = orc.layout(tab, n, w.align)
+    offs, regions, begins = fmt.rank_files(sizes, [0] * n, 1, w.align)
+    assert regions == [total] and begins == [0] and offs == [tab[i].file_offset for i in range(n)]
+
+    # four files, shards dealt out unevenly (file 2 gets none)
+    rng = random.Random(5)
+    file_of = [rng.choice([0, 0, 1, 3]) for _ in range(n)]
+    offs, regions, begins = fmt.rank_files(sizes, file_of, 4, w.align)
+    assert regions[2] == 0
+    alone = []
+    for f in range(4):
+        sub = [s for s, g in zip(w.shards, file_of) if g == f]
+        t = orc.table(sub, w.arena.ctypes.data)
+        assert orc.layout(t, len(sub), w.align) == regions[f]
+        assert [t[k].file_offset for k in range(len(sub))] == [o for o, g in zip(offs, file_of) if g == f]
+        alone.append(orc.pack(t, len(sub), regions[f]).tobytes())
+    image = b"".join(alone)
+    tensors = [(s.tensor_id, W.DTYPES[s.dtype][0], tuple(s.shape), o, s.nbytes) for s, o in zip(w.shards, offs)]
+    appends = [[(1, b"a" * f), (9, b"tail")] for f in range(4)]
+    blobs = fmt.build_rank_files(w.align, image, tensors, file_of, 4, appends)
+    for f, blob in enumerate(blobs):
+        back = fmt.parse_file(blob)
+        assert back["image"] == alone[f] and back["tensor_bytes"] == regions[f]
+        assert back["tensors"] == [t for t, g in zip(tensors, file_of) if g == f]
+        assert back["objects"] == {1: b"a" * f, 9: b"tail"}
+    with pytest.raises(fmt.FormatError):
+        fmt.build_rank_files(w.align, image + b"\0" * w.align, tensors, file_of, 4, appends)
+
+
 # ---- the library against the oracle --------------------------------------------------------
 
 def _host_plan(w):
