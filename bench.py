@@ -723,18 +723,115 @@ def experiments_leg(c: Ctx, L: Loaded, cfg, loop, gemm, head, full: bool):
     return out
 
 
-def several_plans(c: Ctx, L: Loaded, cfg):
-    """One rank's checkpoint split over several files (the paper's 7B rank writes 20, Sec. VI-D): one plan per
-    file over consecutive shards of about equal bytes, all through the one engine, back to back."""
-    ds, torch, args = c.ds, c.torch, c.args
+def file_cuts(c: Ctx, L: Loaded):
+    """The rank's shard table cut into consecutive runs of about equal bytes, one per file."""
     n, payload = L.n, L.payload
-    F = min(args.files, n)
-    cuts, acc, sizes = [0], 0, [ds.ds_plan_shard(L.plan, i)[3] for i in range(n)]
+    F = min(c.args.files, n)
+    cuts, acc, sizes = [0], 0, [c.ds.ds_plan_shard(L.plan, i)[3] for i in range(n)]
     for i in range(n):
         acc += sizes[i]
         if acc >= payload * len(cuts) / F and len(cuts) < F and i + 1 < n:
             cuts.append(i + 1)
     cuts.append(n)
+    return cuts
+
+
+def rank_files_leg(c: Ctx, L: Loaded, cfg, d):
+    """One plan over all files of the rank (Sec. VI-D: a 7B rank writes 20): ONE snapshot, its chunks cut at the
+    files' boundaries by the flush, one checkpoint writer per file; beside it the same state as one file through
+    the same engine.  Files are consecutive runs of the table, so the files' tensor regions one behind the other
+    are the single image, which is what the parity leg's oracle image is compared with."""
+    ds, torch, np, args = c.ds, c.torch, c.np, c.args
+    cuts = file_cuts(c, L)
+    F = len(cuts) - 1
+    file_of = [f for f in range(F) for _ in range(cuts[f + 1] - cuts[f])]
+    descs = ds.make_descs(L.w.shards, L.arena.data_ptr())
+    regions, total = ds.ds_layout_assign_files(descs, file_of, L.n, F, L.w.align)
+    assert total == L.total
+    t0 = time.perf_counter()
+    plan = ds.ds_plan_create_files(descs, file_of, L.n, F, L.w.align, ds.DS_PLAN_STRICT)
+    plan_ms = (time.perf_counter() - t0) * 1e3
+    eng = c.engine(cfg, flags=0)
+    file_flags = ds.DS_FILE_DIRECT | (ds.DS_FILE_URING if args.file_engine == "uring" else 0)
+    paths = [os.path.join(d, f"ds_bench_{os.getpid()}_part{f}.ckpt") for f in range(F)]
+    one = os.path.join(d, f"ds_bench_{os.getpid()}_whole.ckpt")
+    res = {"workload": L.name, "dir": d, "files": F, "smallest_region_bytes": min(regions),
+           "largest_region_bytes": max(regions), "threads": args.file_threads, "engine": engine_json(cfg),
+           "plan_create_ms": round(plan_ms, 3)}
+    try:
+        for attempt in ("warm-up", "timed"):
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            ev = ds.ds_snapshot_async(eng, plan, c.stream)
+            parts = [ds.ds_ckpt_create_part(paths[f], plan, f, file_flags) for f in range(F)]
+            ds.ds_ckpt_flush_snapshot_parts(parts, ev, args.file_threads)
+            ds.ds_event_wait_on_stream(ev, c.stream)
+            ds.ds_event_wait_captured(ev)
+            cap_ms = (time.perf_counter() - t0) * 1e3    # request -> every tensor of every file may be mutated
+            nbytes = sum(ds.ds_ckpt_finish(ck)[0] for ck in parts)
+            files_s = time.perf_counter() - t0
+            ds.ds_event_wait(ev)
+            st = ds.ds_event_stats(ev)
+            ds.ds_event_destroy(ev)
+        res.update({"file_bytes": nbytes, "request_to_all_captured_ms": round(cap_ms, 3),
+                    "capture_ms_device_events": round(st["capture_ms"], 3),
+                    "gather_launches": st["n_pack_launches"],
+                    "snapshot_to_files_GBps": round(nbytes / files_s / 1e9, 2)})
+        if L.want is not None:
+            at, same = 0, True
+            for f in range(F):
+                got = np.fromfile(paths[f], dtype=np.uint8, count=regions[f])
+                same = same and got.size == regions[f] and same_bytes(c, got, L.want[at:at + regions[f]])
+                at += regions[f]
+            res["tensor_regions_byte_exact_vs_oracle"] = bool(same)
+        # all files back into the GPU in one restore
+        t0 = time.perf_counter()
+        readers = [ds.ds_ckpt_open(p) for p in paths]
+        rev = ds.ds_ckpt_restore_parts(readers, eng, plan, args.file_threads, ds.DS_FILE_DIRECT, c.stream)
+        ds.ds_event_wait(rev)
+        load_s = time.perf_counter() - t0
+        ds.ds_event_destroy(rev)
+        for r in readers:
+            ds.ds_ckpt_close(r)
+        res["files_to_gpu_GBps"] = round(L.payload / load_s / 1e9, 2)
+        # the same state as ONE file, same engine
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        ev = ds.ds_snapshot_async(eng, L.plan, c.stream)
+        ck = ds.ds_ckpt_create(one, L.plan, file_flags)
+        ds.ds_ckpt_flush_snapshot(ck, ev, args.file_threads)
+        ds.ds_event_wait_on_stream(ev, c.stream)
+        ds.ds_event_wait_captured(ev)
+        cap1_ms = (time.perf_counter() - t0) * 1e3
+        nbytes1, _ = ds.ds_ckpt_finish(ck)
+        one_s = time.perf_counter() - t0
+        ds.ds_event_wait(ev)
+        st1 = ds.ds_event_stats(ev)
+        ds.ds_event_destroy(ev)
+        res["same_state_as_one_file"] = {"request_to_captured_ms": round(cap1_ms, 3),
+                                         "capture_ms_device_events": round(st1["capture_ms"], 3),
+                                         "snapshot_to_file_GBps": round(nbytes1 / one_s / 1e9, 2)}
+    except ds.DsError as e:
+        res["error"] = str(e)
+    finally:
+        ds.ds_engine_destroy(eng)
+        torch.cuda.synchronize()
+        ds.ds_plan_destroy(plan)
+        for path in paths + [one]:
+            if os.path.exists(path):
+                os.remove(path)
+    log(f"[bench] {L.name} as {F} files through one plan: {res.get('snapshot_to_files_GBps')} GB/s to {d}, "
+        f"request -> all captured {res.get('request_to_all_captured_ms')} ms "
+        f"(one file: {res.get('same_state_as_one_file', {}).get('request_to_captured_ms')} ms)")
+    return res
+
+
+def several_plans(c: Ctx, L: Loaded, cfg):
+    """One rank's checkpoint split over several files (the paper's 7B rank writes 20, Sec. VI-D): one plan per
+    file over consecutive shards of about equal bytes, all through the one engine, back to back."""
+    ds, torch, args = c.ds, c.torch, c.args
+    n, payload = L.n, L.payload
+    cuts = file_cuts(c, L)
     plans = []
     for a, b in zip(cuts[:-1], cuts[1:]):
         dg = ds.make_descs(L.w.shards[a:b], L.arena.data_ptr())
@@ -1129,7 +1226,10 @@ def main() -> int:
     if args.experiments:
         experiments["rank_state_as_several_plans"], file_plans = several_plans(c, L, cfg)
     # the flush consumer gets finer ring slots than the null consumer of the timed region: more writes in flight
-    file_tier = None if args.no_file else file_leg(c, L, engine_cfg(args, chunk=min(args.chunk_bytes, 32 * MiB)), file_plans)
+    file_chunk = min(args.chunk_bytes, 32 * MiB)
+    file_tier = None if args.no_file else file_leg(c, L, engine_cfg(args, chunk=file_chunk), file_plans)
+    if file_tier is not None:
+        file_tier["one_plan_of_files"] = [rank_files_leg(c, L, engine_cfg(args, chunk=file_chunk), args.file_dir)]
     torch.cuda.synchronize()
     for pl in file_plans:
         ds.ds_plan_destroy(pl)
@@ -1154,6 +1254,10 @@ def main() -> int:
                 if Lx.total > cfg["slot"] and name == "llama70b":
                     cap_binding.append(cap_binding_run(c, Lx, cfg, min(k_steps, 5),
                                                        "host ring and device staging smaller than the image"))
+                if name == "llama70b" and file_tier is not None:
+                    # staging as large as the image: every gate opens behind the gathers alone
+                    file_tier["one_plan_of_files"].append(rank_files_leg(
+                        c, Lx, engine_cfg(args, chunk=file_chunk, slot=8 * GiB, slots=1), args.file_dir))
             finally:
                 Lx.close(c)
                 del Lx

@@ -130,6 +130,32 @@ int ds_layout_assign(ds_shard_desc *desc, size_t n, uint64_t align, uint64_t *to
  */
 int ds_plan_create(const ds_shard_desc *desc, size_t n, uint64_t align, uint32_t flags, ds_plan **out);
 
+/*
+ * One plan for a rank that writes its checkpoint as several files (Sec. VI-D:
+ * 20 files for a 7B rank; Sec. V-A3: one composite provider per rank lays out
+ * everything it owns).  file_of[i] < n_files names the file of shard i and
+ * desc[i].file_offset counts from the start of THAT file.  The plan's one image
+ * is the files' tensor regions one behind the other in file order: region f
+ * spans the shards of file f from offset 0 up to the end of the last one,
+ * rounded up to `align`, and starts at the sum of the regions before it (see
+ * ds_plan_file).  One gather launch and one snapshot then cover all files, and
+ * the file tier cuts the image at the region boundaries (ds_flush_start_files,
+ * ds_ckpt_flush_snapshot_parts).  A file that no shard names has an empty
+ * region.  file_of == NULL with n_files == 1 is ds_plan_create.  Everything else
+ * (checks, flags, errors, ownership) as ds_plan_create; DS_PLAN_STRICT also
+ * requires every file's first shard at offset 0.  n_files <= DS_MAX_FILES.
+ */
+#define DS_MAX_FILES 65536u
+int ds_plan_create_files(const ds_shard_desc *desc, const uint32_t *file_of, size_t n, uint32_t n_files,
+                         uint64_t align, uint32_t flags, ds_plan **out);
+
+/* ds_layout_assign file by file: the canonical offset of every shard inside its own
+ * file; region_bytes[n_files] (may be NULL) gets the files' tensor-region lengths,
+ * *total their sum = the length of the image of ds_plan_create_files.
+ * Errors: DS_EINVAL. */
+int ds_layout_assign_files(ds_shard_desc *desc, const uint32_t *file_of, size_t n, uint32_t n_files,
+                           uint64_t align, uint64_t *region_bytes, uint64_t *total);
+
 /* Frees host and device tables.  The caller makes sure no kernel that uses
  * the plan is still running (synchronise the streams it was used on). */
 int ds_plan_destroy(ds_plan *plan);
@@ -144,6 +170,7 @@ typedef struct ds_plan_stats {
   uint64_t n_strided;     /* shards that are not one contiguous run               */
   uint64_t align;
   uint64_t n_general_chunks; /* chunks that take the kernel's general path (the lean path takes the rest) */
+  uint64_t n_files;       /* 1 for a plan of ds_plan_create                       */
 } ds_plan_stats;
 
 int ds_plan_info(const ds_plan *plan, ds_plan_stats *out);
@@ -152,6 +179,14 @@ int ds_plan_info(const ds_plan *plan, ds_plan_stats *out);
  * (Sec. V-A5 rule (3)).  Any out pointer may be NULL. */
 int ds_plan_shard(const ds_plan *plan, size_t i, uint64_t *tensor_id, uint32_t *dtype,
                   uint64_t *file_offset, uint64_t *nbytes);
+
+/* File f of the plan: where its tensor region starts in the image and how long
+ * it is.  Either out pointer may be NULL.  Errors: DS_EINVAL (f >= n_files). */
+int ds_plan_file(const ds_plan *plan, uint32_t f, uint64_t *image_begin, uint64_t *region_bytes);
+
+/* Manifest entry i: the file it belongs to and its offset in the IMAGE
+ * (= the file_offset of ds_plan_shard + the file's image_begin). */
+int ds_plan_shard_file(const ds_plan *plan, size_t i, uint32_t *file, uint64_t *image_offset);
 
 /* Shape of manifest entry i: *ndim and the first *ndim extents of shape[DS_MAX_DIMS]
  * (the rest are set to 0).  Either out pointer may be NULL. */
@@ -388,6 +423,17 @@ int ds_restore_submit(ds_event *ev, const void *host_ptr);
  */
 int ds_flush_start(ds_event *ev, const char *path, uint32_t threads, uint32_t flags, ds_flush **out);
 
+/*
+ * The same for a snapshot of a plan of several files (ds_plan_create_files):
+ * paths[f] gets the bytes of region f at file offsets 0.., so that file f is
+ * exactly what ds_flush_start would write for a plan of file f's shards alone.
+ * One set of `threads` writers serves all files; a ring chunk that spans a
+ * region boundary is written in pieces and its slot is given back when the
+ * last piece is out.  n_files must be the plan's.  Errors: as ds_flush_start.
+ */
+int ds_flush_start_files(ds_event *ev, const char *const *paths, uint32_t n_files, uint32_t threads,
+                         uint32_t flags, ds_flush **out);
+
 /* Waits until the whole image is in the file, closes it and frees the flush.
  * Either out pointer may be NULL.  Errors: DS_EIO (ds_last_errno()), or the
  * error that ended the snapshot. */
@@ -402,6 +448,12 @@ int ds_flush_wait(ds_flush *flush, uint64_t *bytes_written, double *seconds);
  */
 int ds_restore_from_file(ds_engine *engine, const ds_plan *plan, const char *path, uint32_t threads,
                          uint32_t flags, void *compute_stream, ds_event **out);
+
+/* The same out of the n_files files of a plan of several files, paths[f]
+ * holding region f from its offset 0: ONE restore event, one scatter pipeline
+ * for the whole rank.  n_files must be the plan's.  Errors: as above. */
+int ds_restore_from_files(ds_engine *engine, const ds_plan *plan, const char *const *paths, uint32_t n_files,
+                          uint32_t threads, uint32_t flags, void *compute_stream, ds_event **out);
 
 /* errno of the file operation that last produced DS_EIO on this thread. */
 int ds_last_errno(void);
@@ -425,8 +477,12 @@ int ds_last_errno(void);
  *                     u32 crc of the trailer, u32 crc of the 60 footer bytes before
  *                     it (CRC-32 of IEEE 802.3, as in zlib)
  * The paper fixes the three rules, not the bytes: the encoding is this library's.
- * A rank that writes several files per checkpoint uses one plan and one
- * ds_ckpt per file.
+ * A rank that writes several files per checkpoint uses either one plan and one
+ * ds_ckpt per file, or ONE plan of several files (ds_plan_create_files) with one
+ * ds_ckpt per file made by ds_ckpt_create_part: file f then holds region f of
+ * the image as its tensor region, the plan's entries of file f (offsets inside
+ * the file) as its tensor entries and an object log of its own -- byte for byte
+ * the file that a plan of file f's shards alone would give.
  */
 
 /*
@@ -436,6 +492,19 @@ int ds_last_errno(void);
  * the ds_ckpt.  Errors: DS_EINVAL, DS_ENOMEM, DS_EIO.
  */
 int ds_ckpt_create(const char *path, const ds_plan *plan, uint32_t flags, ds_ckpt **out);
+
+/* The writer of file `file` of a plan of several files (for a plan of one file,
+ * ds_ckpt_create_part(path, plan, 0, ...) is ds_ckpt_create, which refuses a plan
+ * of several).  Errors: as ds_ckpt_create. */
+int ds_ckpt_create_part(const char *path, const ds_plan *plan, uint32_t file, uint32_t flags, ds_ckpt **out);
+
+/* Fills the tensor regions of ALL files of a plan of several files from one
+ * snapshot of that plan: parts[f] must be the writer of file f, n_parts the
+ * plan's number of files; one flush with `threads` writers serves them all.
+ * Flags are those of parts[0].  Each part is then finished on its own with
+ * ds_ckpt_finish, in any order; the first of these calls waits for the flush,
+ * and every part must be finished.  Errors: DS_EINVAL, DS_ESTATE, DS_ENOMEM. */
+int ds_ckpt_flush_snapshot_parts(ds_ckpt *const *parts, uint32_t n_parts, ds_event *snapshot, uint32_t threads);
 
 /* Fills the tensor region from a snapshot of the same plan: ds_flush_start on
  * this file (`threads` writers).  Once per ds_ckpt; returns at once.
@@ -504,6 +573,17 @@ int ds_ckpt_matches_plan(const ds_ckpt_reader *reader, const ds_plan *plan);
 /* ds_ckpt_matches_plan, then ds_restore_from_file on the tensor region. */
 int ds_ckpt_restore(const ds_ckpt_reader *reader, ds_engine *engine, const ds_plan *plan, uint32_t threads,
                     uint32_t flags, void *compute_stream, ds_event **out);
+/* The same for file `file` of a plan of several files: T is that file's region,
+ * the entries are the plan's entries of that file.  ds_ckpt_matches_plan is part 0
+ * of a plan of one file (DS_EINVAL for a plan of several). */
+int ds_ckpt_matches_plan_part(const ds_ckpt_reader *reader, const ds_plan *plan, uint32_t file);
+/* Every reader checked against its part (readers[f] = file f, n_parts = the
+ * plan's number of files), then ONE restore of the whole rank out of all files
+ * (ds_restore_from_files on the tensor regions).  Errors: DS_EINVAL, DS_EFORMAT,
+ * and those of ds_restore_from_file. */
+int ds_ckpt_restore_parts(const ds_ckpt_reader *const *readers, uint32_t n_parts, ds_engine *engine,
+                          const ds_plan *plan, uint32_t threads, uint32_t flags, void *compute_stream,
+                          ds_event **out);
 
 /* ---- misc ---------------------------------------------------------------- */
 

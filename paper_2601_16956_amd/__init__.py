@@ -40,6 +40,9 @@ EXPORTS = [
     "ds_ckpt_finish", "ds_ckpt_open", "ds_ckpt_close", "ds_ckpt_layout_info", "ds_ckpt_tensor_info",
     "ds_ckpt_object_at", "ds_ckpt_object_read", "ds_ckpt_matches_plan", "ds_ckpt_restore", "ds_event_trace",
     "ds_image_diff", "ds_pack_noalloc", "ds_image_compress",
+    "ds_plan_create_files", "ds_layout_assign_files", "ds_plan_file", "ds_plan_shard_file", "ds_flush_start_files",
+    "ds_restore_from_files", "ds_ckpt_create_part", "ds_ckpt_flush_snapshot_parts", "ds_ckpt_matches_plan_part",
+    "ds_ckpt_restore_parts",
 ]
 
 
@@ -58,7 +61,7 @@ class ds_shard_desc(ctypes.Structure):
 class ds_plan_stats(ctypes.Structure):
     _fields_ = [(n, ctypes.c_uint64) for n in (
         "total_bytes", "payload_bytes", "n_shards", "n_tiles", "n_chunks", "chunk_bytes", "n_strided", "align",
-        "n_general_chunks")]
+        "n_general_chunks", "n_files")]
 
 
 class ds_engine_opts(ctypes.Structure):
@@ -211,6 +214,16 @@ def _load() -> ctypes.CDLL:
         "ds_event_trace": ([vp, P(ds_trace_rec), sz, P(sz)], ctypes.c_int),
         "ds_image_diff": ([vp, vp, u64, u64, vp, vp], ctypes.c_int),
         "ds_image_compress": ([vp, u64, u64, vp, vp, vp, vp, vp], ctypes.c_int),
+        "ds_plan_create_files": ([P(ds_shard_desc), P(u32), sz, u32, u64, u32, P(vp)], ctypes.c_int),
+        "ds_layout_assign_files": ([P(ds_shard_desc), P(u32), sz, u32, u64, P(u64), P(u64)], ctypes.c_int),
+        "ds_plan_file": ([vp, u32, P(u64), P(u64)], ctypes.c_int),
+        "ds_plan_shard_file": ([vp, sz, P(u32), P(u64)], ctypes.c_int),
+        "ds_flush_start_files": ([vp, P(ctypes.c_char_p), u32, u32, u32, P(vp)], ctypes.c_int),
+        "ds_restore_from_files": ([vp, vp, P(ctypes.c_char_p), u32, u32, u32, vp, P(vp)], ctypes.c_int),
+        "ds_ckpt_create_part": ([ctypes.c_char_p, vp, u32, u32, P(vp)], ctypes.c_int),
+        "ds_ckpt_flush_snapshot_parts": ([P(vp), u32, vp, u32], ctypes.c_int),
+        "ds_ckpt_matches_plan_part": ([vp, vp, u32], ctypes.c_int),
+        "ds_ckpt_restore_parts": ([P(vp), u32, vp, vp, u32, u32, vp, P(vp)], ctypes.c_int),
     }
     for name, (args, res) in sig.items():
         fn = getattr(L, name)
@@ -293,6 +306,48 @@ def ds_plan_create(descs, n: int, align: int, flags: int = 0) -> int:
     out = ctypes.c_void_p(0)
     _check(_lib.ds_plan_create(descs, n, align, flags, ctypes.byref(out)), "ds_plan_create")
     return int(out.value)
+
+
+def _u32_array(values: Sequence[int]):
+    return (ctypes.c_uint32 * max(len(values), 1))(*values)
+
+
+def _path_array(paths: Sequence[str]):
+    return (ctypes.c_char_p * max(len(paths), 1))(*[p.encode() for p in paths])
+
+
+def _handle_array(handles: Sequence[int]):
+    return (ctypes.c_void_p * max(len(handles), 1))(*handles)
+
+
+def ds_layout_assign_files(descs, file_of: Sequence[int], n: int, n_files: int, align: int) -> Tuple[List[int], int]:
+    """(tensor-region length of every file, their sum = the image length)."""
+    regions = (ctypes.c_uint64 * n_files)()
+    total = ctypes.c_uint64(0)
+    _check(_lib.ds_layout_assign_files(descs, _u32_array(file_of), n, n_files, align, regions, ctypes.byref(total)),
+           "ds_layout_assign_files")
+    return [int(r) for r in regions], int(total.value)
+
+
+def ds_plan_create_files(descs, file_of: Sequence[int], n: int, n_files: int, align: int, flags: int = 0) -> int:
+    out = ctypes.c_void_p(0)
+    _check(_lib.ds_plan_create_files(descs, _u32_array(file_of), n, n_files, align, flags, ctypes.byref(out)),
+           "ds_plan_create_files")
+    return int(out.value)
+
+
+def ds_plan_file(plan: int, f: int) -> Tuple[int, int]:
+    """(where file f's tensor region starts in the image, its length)."""
+    begin, nbytes = ctypes.c_uint64(0), ctypes.c_uint64(0)
+    _check(_lib.ds_plan_file(plan, f, ctypes.byref(begin), ctypes.byref(nbytes)), "ds_plan_file")
+    return int(begin.value), int(nbytes.value)
+
+
+def ds_plan_shard_file(plan: int, i: int) -> Tuple[int, int]:
+    """(file of manifest entry i, its offset in the image)."""
+    f, off = ctypes.c_uint32(0), ctypes.c_uint64(0)
+    _check(_lib.ds_plan_shard_file(plan, i, ctypes.byref(f), ctypes.byref(off)), "ds_plan_shard_file")
+    return int(f.value), int(off.value)
 
 
 def ds_plan_destroy(plan: int) -> None:
@@ -432,6 +487,13 @@ def ds_flush_start(ev: int, path: str, threads: int = 0, flags: int = 0) -> int:
     return int(out.value)
 
 
+def ds_flush_start_files(ev: int, paths: Sequence[str], threads: int = 0, flags: int = 0) -> int:
+    out = ctypes.c_void_p(0)
+    _check(_lib.ds_flush_start_files(ev, _path_array(paths), len(paths), threads, flags, ctypes.byref(out)),
+           "ds_flush_start_files")
+    return int(out.value)
+
+
 def ds_flush_wait(flush: int) -> Tuple[int, float]:
     """(bytes written, seconds from ds_flush_start to the last write)."""
     nbytes, secs = ctypes.c_uint64(0), ctypes.c_double(0)
@@ -444,6 +506,14 @@ def ds_restore_from_file(engine: int, plan: int, path: str, threads: int = 0, fl
     out = ctypes.c_void_p(0)
     _check(_lib.ds_restore_from_file(engine, plan, path.encode(), threads, flags, compute_stream,
                                      ctypes.byref(out)), "ds_restore_from_file")
+    return int(out.value)
+
+
+def ds_restore_from_files(engine: int, plan: int, paths: Sequence[str], threads: int = 0, flags: int = 0,
+                          compute_stream: int = 0) -> int:
+    out = ctypes.c_void_p(0)
+    _check(_lib.ds_restore_from_files(engine, plan, _path_array(paths), len(paths), threads, flags, compute_stream,
+                                      ctypes.byref(out)), "ds_restore_from_files")
     return int(out.value)
 
 
@@ -462,6 +532,17 @@ def ds_ckpt_create(path: str, plan: int, flags: int = 0) -> int:
     out = ctypes.c_void_p(0)
     _check(_lib.ds_ckpt_create(path.encode(), plan, flags, ctypes.byref(out)), "ds_ckpt_create")
     return int(out.value)
+
+
+def ds_ckpt_create_part(path: str, plan: int, file: int, flags: int = 0) -> int:
+    out = ctypes.c_void_p(0)
+    _check(_lib.ds_ckpt_create_part(path.encode(), plan, file, flags, ctypes.byref(out)), "ds_ckpt_create_part")
+    return int(out.value)
+
+
+def ds_ckpt_flush_snapshot_parts(parts: Sequence[int], snapshot: int, threads: int = 0) -> None:
+    _check(_lib.ds_ckpt_flush_snapshot_parts(_handle_array(parts), len(parts), snapshot, threads),
+           "ds_ckpt_flush_snapshot_parts")
 
 
 def ds_ckpt_flush_snapshot(ckpt: int, snapshot: int, threads: int = 0) -> None:
@@ -525,6 +606,18 @@ def ds_ckpt_object_read(reader: int, object_id: int) -> bytes:
 
 def ds_ckpt_matches_plan(reader: int, plan: int) -> None:
     _check(_lib.ds_ckpt_matches_plan(reader, plan), "ds_ckpt_matches_plan")
+
+
+def ds_ckpt_matches_plan_part(reader: int, plan: int, file: int) -> None:
+    _check(_lib.ds_ckpt_matches_plan_part(reader, plan, file), "ds_ckpt_matches_plan_part")
+
+
+def ds_ckpt_restore_parts(readers: Sequence[int], engine: int, plan: int, threads: int = 0, flags: int = 0,
+                          compute_stream: int = 0) -> int:
+    out = ctypes.c_void_p(0)
+    _check(_lib.ds_ckpt_restore_parts(_handle_array(readers), len(readers), engine, plan, threads, flags,
+                                      compute_stream, ctypes.byref(out)), "ds_ckpt_restore_parts")
+    return int(out.value)
 
 
 def ds_ckpt_restore(reader: int, engine: int, plan: int, threads: int = 0, flags: int = 0,

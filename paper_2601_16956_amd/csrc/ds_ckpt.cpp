@@ -98,11 +98,24 @@ double now_s() {
 
 }  // namespace
 
+// One flush that feeds the files of several writers: the first of them to finish waits for it, all of them
+// get its status, the last one frees it.
+struct SharedFlush {
+  ds_flush *flush = nullptr;
+  std::mutex mu;
+  bool waited = false;
+  int status = DS_OK, err_no = 0;
+  int refs = 0;
+};
+
 struct ds_ckpt {
   const ds_plan *plan = nullptr;
+  uint32_t file = 0;      // which of the plan's files this is
+  uint64_t region = 0;    // length of its tensor region
   int fd = -1, fd_direct = -1;
   uint32_t flags = 0;
   ds_flush *flush = nullptr;
+  SharedFlush *shared = nullptr;
   std::atomic<uint64_t> tail{0};  // next free byte of the log
   std::mutex mu;                  // chunks, next_seq, status
   std::vector<ChunkEntry> chunks;
@@ -124,7 +137,13 @@ struct ds_ckpt_reader {
 extern "C" {
 
 int ds_ckpt_create(const char *path, const ds_plan *plan, uint32_t flags, ds_ckpt **out) {
+  if (!plan || plan->file_begin.size() != 2) return DS_EINVAL;  // a plan of several files: one writer per part
+  return ds_ckpt_create_part(path, plan, 0, flags, out);
+}
+
+int ds_ckpt_create_part(const char *path, const ds_plan *plan, uint32_t file, uint32_t flags, ds_ckpt **out) {
   if (!path || !plan || !out || (flags & ~(DS_FILE_DIRECT | DS_FILE_SYNC | DS_FILE_URING))) return DS_EINVAL;
+  if ((size_t)file + 1 >= plan->file_begin.size()) return DS_EINVAL;
   ds_ckpt *c = new (std::nothrow) ds_ckpt;
   if (!c) return DS_ENOMEM;
   c->fd = open(path, O_RDWR | O_CREAT | O_TRUNC | O_CLOEXEC, 0644);
@@ -135,8 +154,10 @@ int ds_ckpt_create(const char *path, const ds_plan *plan, uint32_t flags, ds_ckp
   }
   if (flags & DS_FILE_DIRECT) c->fd_direct = open(path, O_WRONLY | O_DIRECT | O_CLOEXEC);
   c->plan = plan;
+  c->file = file;
+  c->region = plan->file_begin[file + 1] - plan->file_begin[file];
   c->flags = flags;
-  c->tail.store(plan->total_bytes);  // a multiple of the alignment (>= 16), so of 8
+  c->tail.store(c->region);  // a multiple of the alignment (>= 16), so of 8
   c->t0 = now_s();
   *out = c;
   return DS_OK;
@@ -144,14 +165,48 @@ int ds_ckpt_create(const char *path, const ds_plan *plan, uint32_t flags, ds_ckp
 
 int ds_ckpt_flush_snapshot(ds_ckpt *c, ds_event *snapshot, uint32_t threads) {
   if (!c || !snapshot) return DS_EINVAL;
-  if (c->flush) return DS_ESTATE;
+  if (c->flush || c->shared) return DS_ESTATE;
+  if (c->plan->file_begin.size() != 2) return DS_EINVAL;  // parts are flushed together
   return ds_flush_start_fds(snapshot, c->fd, c->fd_direct, threads, c->flags & (DS_FILE_DIRECT | DS_FILE_URING),
                             &c->flush);
 }
 
+int ds_ckpt_flush_snapshot_parts(ds_ckpt *const *parts, uint32_t n_parts, ds_event *snapshot, uint32_t threads) {
+  if (!parts || !n_parts || !snapshot) return DS_EINVAL;
+  const ds_plan *plan = ds_event_plan(snapshot);
+  if (!plan || (size_t)n_parts + 1 != plan->file_begin.size()) return DS_EINVAL;
+  for (uint32_t k = 0; k < n_parts; ++k) {
+    if (!parts[k] || parts[k]->plan != plan || parts[k]->file != k) return DS_EINVAL;
+    if (parts[k]->flush || parts[k]->shared) return DS_ESTATE;
+  }
+  SharedFlush *sf = new (std::nothrow) SharedFlush;
+  if (!sf) return DS_ENOMEM;
+  int rc;
+  try {
+    std::vector<DsFileTarget> targets(n_parts);
+    for (uint32_t k = 0; k < n_parts; ++k) {
+      targets[k].begin = plan->file_begin[k];
+      targets[k].end = plan->file_begin[k + 1];
+      targets[k].fd_buffered = parts[k]->fd;
+      targets[k].fd_direct = parts[k]->fd_direct;
+    }
+    rc = ds_flush_start_targets(snapshot, std::move(targets), threads,
+                                parts[0]->flags & (DS_FILE_DIRECT | DS_FILE_URING), &sf->flush);
+  } catch (const std::bad_alloc &) {
+    rc = DS_ENOMEM;
+  }
+  if (rc != DS_OK) {
+    delete sf;
+    return rc;
+  }
+  sf->refs = (int)n_parts;
+  for (uint32_t k = 0; k < n_parts; ++k) parts[k]->shared = sf;
+  return DS_OK;
+}
+
 int ds_ckpt_write_region(ds_ckpt *c, uint64_t file_off, const void *host, uint64_t len) {
   if (!c || (!host && len)) return DS_EINVAL;
-  if (file_off > c->plan->total_bytes || len > c->plan->total_bytes - file_off) return DS_ERANGE;
+  if (file_off > c->region || len > c->region - file_off) return DS_ERANGE;
   const int e = pwrite_all(c->fd, (const uint8_t *)host, len, file_off);
   if (e) {
     ds_set_errno(e);
@@ -192,6 +247,24 @@ int ds_ckpt_finish(ds_ckpt *c, uint64_t *file_bytes, double *seconds) {
     if (status != DS_OK) err_no = ds_last_errno();
     c->flush = nullptr;
   }
+  if (c->shared) {
+    SharedFlush *sf = c->shared;
+    bool last;
+    {
+      std::lock_guard<std::mutex> lk(sf->mu);
+      if (!sf->waited) {
+        sf->status = ds_flush_wait(sf->flush, nullptr, nullptr);
+        sf->err_no = sf->status != DS_OK ? ds_last_errno() : 0;
+        sf->flush = nullptr;
+        sf->waited = true;
+      }
+      status = sf->status;
+      err_no = sf->err_no;
+      last = --sf->refs == 0;
+    }
+    if (last) delete sf;
+    c->shared = nullptr;
+  }
   if (status == DS_OK && c->status != DS_OK) {
     status = c->status;
     err_no = c->err_no;
@@ -204,8 +277,11 @@ int ds_ckpt_finish(ds_ckpt *c, uint64_t *file_bytes, double *seconds) {
     });
     std::vector<uint8_t> t;
     try {
-      t.reserve(p->manifest.size() * kTensorEntry + c->chunks.size() * kChunkEntry + kFooter);
+      uint64_t n_mine = 0;
+      for (const DsManifestEntry &m : p->manifest) n_mine += m.file == c->file;
+      t.reserve(n_mine * kTensorEntry + c->chunks.size() * kChunkEntry + kFooter);
       for (const DsManifestEntry &m : p->manifest) {
+        if (m.file != c->file) continue;
         put64(t, m.tensor_id);
         put32(t, m.dtype);
         put32(t, m.ndim);
@@ -225,9 +301,9 @@ int ds_ckpt_finish(ds_ckpt *c, uint64_t *file_bytes, double *seconds) {
       put32(t, kVersion);
       put32(t, 0);
       put64(t, p->align);
-      put64(t, p->total_bytes);
+      put64(t, c->region);
       put64(t, c->tail.load());
-      put64(t, p->manifest.size());
+      put64(t, n_mine);
       put64(t, c->chunks.size());
       put32(t, trailer_crc);
       put32(t, crc32_ieee(t.data() + f0, 60));
@@ -416,17 +492,24 @@ int ds_ckpt_object_read(const ds_ckpt_reader *r, uint64_t object_id, void *buf, 
 
 int ds_ckpt_matches_plan(const ds_ckpt_reader *r, const ds_plan *plan) {
   if (!r || !plan) return DS_EINVAL;
-  if (r->lay.align != plan->align || r->lay.tensor_bytes != plan->total_bytes ||
-      r->tensors.size() != plan->manifest.size())
+  if (plan->file_begin.size() != 2) return DS_EINVAL;
+  return ds_ckpt_matches_plan_part(r, plan, 0);
+}
+
+int ds_ckpt_matches_plan_part(const ds_ckpt_reader *r, const ds_plan *plan, uint32_t file) {
+  if (!r || !plan || (size_t)file + 1 >= plan->file_begin.size()) return DS_EINVAL;
+  if (r->lay.align != plan->align || r->lay.tensor_bytes != plan->file_begin[file + 1] - plan->file_begin[file])
     return DS_EFORMAT;
-  for (size_t i = 0; i < r->tensors.size(); ++i) {
-    const ds_ckpt_tensor &x = r->tensors[i];
-    const DsManifestEntry &m = plan->manifest[i];
+  size_t k = 0;  // the file's entries are the plan's entries of that file, in table order
+  for (const DsManifestEntry &m : plan->manifest) {
+    if (m.file != file) continue;
+    if (k >= r->tensors.size()) return DS_EFORMAT;
+    const ds_ckpt_tensor &x = r->tensors[k++];
     if (x.tensor_id != m.tensor_id || x.dtype != m.dtype || x.ndim != m.ndim || x.file_offset != m.file_offset ||
         x.nbytes != m.nbytes || std::memcmp(x.shape, m.shape, sizeof(x.shape)) != 0)
       return DS_EFORMAT;
   }
-  return DS_OK;
+  return k == r->tensors.size() ? DS_OK : DS_EFORMAT;
 }
 
 int ds_ckpt_restore(const ds_ckpt_reader *r, ds_engine *engine, const ds_plan *plan, uint32_t threads, uint32_t flags,
@@ -435,6 +518,38 @@ int ds_ckpt_restore(const ds_ckpt_reader *r, ds_engine *engine, const ds_plan *p
   const int rc = ds_ckpt_matches_plan(r, plan);
   if (rc != DS_OK) return rc;
   return ds_restore_from_file(engine, plan, r->path.c_str(), threads, flags, compute_stream, out);
+}
+
+int ds_ckpt_restore_parts(const ds_ckpt_reader *const *readers, uint32_t n_parts, ds_engine *engine,
+                          const ds_plan *plan, uint32_t threads, uint32_t flags, void *compute_stream,
+                          ds_event **out) {
+  if (!readers || !engine || !plan || !out || (flags & ~DS_FILE_DIRECT)) return DS_EINVAL;
+  if ((size_t)n_parts + 1 != plan->file_begin.size()) return DS_EINVAL;
+  for (uint32_t k = 0; k < n_parts; ++k) {
+    if (!readers[k]) return DS_EINVAL;
+    const int rc = ds_ckpt_matches_plan_part(readers[k], plan, k);
+    if (rc != DS_OK) return rc;
+  }
+  int rc;
+  std::vector<DsFileTarget> targets;
+  try {
+    targets.resize(n_parts);
+    for (uint32_t k = 0; k < n_parts; ++k) {
+      targets[k].begin = plan->file_begin[k];
+      targets[k].end = plan->file_begin[k + 1];
+      targets[k].fd_buffered = readers[k]->fd;  // stays the reader's
+      targets[k].fd_direct =
+          (flags & DS_FILE_DIRECT) ? open(readers[k]->path.c_str(), O_RDONLY | O_DIRECT | O_CLOEXEC) : -1;
+    }
+    rc = ds_restore_from_targets(engine, plan, targets, threads, compute_stream, out);
+  } catch (const std::bad_alloc &) {
+    rc = DS_ENOMEM;
+  }
+  const int keep = ds_last_errno();
+  for (const DsFileTarget &t : targets)
+    if (t.fd_direct >= 0) close(t.fd_direct);
+  ds_set_errno(keep);
+  return rc;
 }
 
 }  // extern "C"

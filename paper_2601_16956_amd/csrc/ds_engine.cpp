@@ -251,6 +251,8 @@ struct ds_event {
   std::vector<hipEvent_t> group_done;  // scatter of staging group gi finished
 };
 
+const ds_plan *ds_event_plan(const ds_event *ev) { return ev ? ev->plan : nullptr; }
+
 namespace {
 
 int hip_fail(hipError_t e) {

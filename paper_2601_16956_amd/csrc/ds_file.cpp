@@ -37,11 +37,39 @@ namespace {
 
 thread_local int g_last_errno = 0;
 
-struct IoJob {
+// A ring slot that one or more writes read from: it goes back to the snapshot when the last of them is done
+// with it.  A chunk that spans the boundary between two files is written as two pieces.
+struct Held {
   void *ptr = nullptr;
-  uint64_t off = 0, len = 0;
-  int slot = -1;  // restore: index into the in-flight window
+  std::atomic<int> left{0};
 };
+
+struct IoJob {
+  void *ptr = nullptr;          // memory of this piece
+  uint64_t off = 0, len = 0;    // where it goes in (comes from) its file
+  int slot = -1;                // restore: index into the in-flight window
+  uint32_t target = 0;          // which file
+  Held *held = nullptr;         // flush: the ring slot the piece lies in
+};
+
+// Cuts image range [off, off + len) at the boundaries of the files and calls piece(target, offset in that
+// file, offset in the range, length) for every non-empty part.  The targets are in image order and cover
+// the image without holes; the last one is open-ended for a caller that does not know the image length.
+template <class F>
+void for_each_piece(const std::vector<DsFileTarget> &targets, uint64_t off, uint64_t len, F piece) {
+  size_t t = 0;
+  while (t + 1 < targets.size() && targets[t].end <= off) ++t;
+  uint64_t at = off;
+  const uint64_t stop = off + len;
+  while (at < stop && t < targets.size()) {
+    const uint64_t e = std::min(stop, targets[t].end);
+    if (e > at) {
+      piece((uint32_t)t, at - targets[t].begin, at - off, e - at);
+      at = e;
+    }
+    if (at < stop) ++t;
+  }
+}
 
 bool direct_ok(const void *p, uint64_t off, uint64_t len) {
   return (((uintptr_t)p | off | len) & 4095) == 0;
@@ -84,9 +112,9 @@ double now_s() {
 
 struct ds_flush {
   ds_event *ev = nullptr;
-  int fd_direct = -1, fd_buffered = -1;
+  std::vector<DsFileTarget> targets;  // the files, in image order
   uint32_t flags = 0;
-  bool own_fds = true;  // false: the descriptors belong to a checkpoint writer, which syncs and closes them
+  bool own_fds = true;  // false: the descriptors belong to checkpoint writers, which sync and close them
   std::thread dispatcher;
   std::vector<std::thread> writers;
   std::mutex mu;
@@ -106,6 +134,14 @@ namespace {
 void flush_fail(ds_flush *f, int status, int e) {
   int expect = DS_OK;
   if (f->status.compare_exchange_strong(expect, status)) f->err_no.store(e);
+}
+
+// This piece no longer needs its ring slot; the last piece of a slot hands it back.
+void release_piece(ds_flush *f, const IoJob &j) {
+  if (j.held->left.fetch_sub(1) != 1) return;
+  int rc = ds_snapshot_release_chunk(f->ev, j.held->ptr);
+  if (rc != DS_OK) flush_fail(f, rc, 0);
+  delete j.held;
 }
 
 // A 4 KiB-aligned buffer of ordinary memory, grown on demand: direct I/O cannot take the pinned ring's pages
@@ -142,10 +178,11 @@ void writer_main(ds_flush *f) {
     }
     bool released = false;
     if (f->status.load() == DS_OK) {
-      const bool direct = f->fd_direct >= 0 && direct_ok(j.ptr, j.off, j.len);
+      const int fd_direct = f->targets[j.target].fd_direct, fd_buffered = f->targets[j.target].fd_buffered;
+      const bool direct = fd_direct >= 0 && direct_ok(j.ptr, j.off, j.len);
       int e = -1;  // -1: not written yet, try the next way
       if (direct && f->direct_usable.load()) {           // straight from the ring, where the kernel allows it
-        e = write_all(f->fd_direct, (const uint8_t *)j.ptr, j.len, j.off);
+        e = write_all(fd_direct, (const uint8_t *)j.ptr, j.len, j.off);
         if (e == EFAULT || e == EINVAL) {
           f->direct_usable.store(false);
           e = -1;
@@ -156,25 +193,21 @@ void writer_main(ds_flush *f) {
         if (b) {
           std::memcpy(b, j.ptr, j.len);
           // the copy is what the file gets: the ring slot is free for the next device-to-host copy already
-          int rc = ds_snapshot_release_chunk(f->ev, j.ptr);
-          if (rc != DS_OK) flush_fail(f, rc, 0);
+          release_piece(f, j);
           released = true;
-          e = write_all(f->fd_direct, b, j.len, j.off);
+          e = write_all(fd_direct, b, j.len, j.off);
           if (e == EINVAL) {                             // the file system has no direct I/O after all
             f->bounce_usable.store(false);
-            e = write_all(f->fd_buffered, b, j.len, j.off);
+            e = write_all(fd_buffered, b, j.len, j.off);
           }
         }
       }
-      if (e == -1) e = write_all(f->fd_buffered, (const uint8_t *)j.ptr, j.len, j.off);
+      if (e == -1) e = write_all(fd_buffered, (const uint8_t *)j.ptr, j.len, j.off);
       if (e) flush_fail(f, DS_EIO, e);
       else f->bytes.fetch_add(j.len);
     }
     // the slot goes back whatever happened, so that the snapshot itself can finish
-    if (!released) {
-      int rc = ds_snapshot_release_chunk(f->ev, j.ptr);
-      if (rc != DS_OK) flush_fail(f, rc, 0);
-    }
+    if (!released) release_piece(f, j);
   }
 }
 
@@ -289,8 +322,7 @@ void uring_writer_main(ds_flush *f, Uring *ring, unsigned depth) {
   unsigned inflight = 0;
   auto release = [&](Op &op) {
     if (op.holds_slot) {
-      int rc = ds_snapshot_release_chunk(f->ev, op.j.ptr);
-      if (rc != DS_OK) flush_fail(f, rc, 0);
+      release_piece(f, op.j);
       op.holds_slot = false;
     }
   };
@@ -298,7 +330,8 @@ void uring_writer_main(ds_flush *f, Uring *ring, unsigned depth) {
     Op &op = ops[i];
     const uint64_t n = op.left < kUringMaxWrite ? op.left : kUringMaxWrite;
     // the ring has 2 x depth entries and at most depth requests are ever queued: this cannot fail
-    (void)ring->queue_write(op.direct ? f->fd_direct : f->fd_buffered, op.src, n, op.off, i);
+    const DsFileTarget &t = f->targets[op.j.target];
+    (void)ring->queue_write(op.direct ? t.fd_direct : t.fd_buffered, op.src, n, op.off, i);
   };
   for (;;) {
     // take new jobs while there is room
@@ -320,7 +353,7 @@ void uring_writer_main(ds_flush *f, Uring *ring, unsigned depth) {
         release(op);
         continue;
       }
-      op.direct = f->fd_direct >= 0 && f->bounce_usable.load() && direct_ok(j.ptr, j.off, j.len);
+      op.direct = f->targets[j.target].fd_direct >= 0 && f->bounce_usable.load() && direct_ok(j.ptr, j.off, j.len);
       uint8_t *b = op.direct ? op.bounce.fit(j.len) : nullptr;
       if (op.direct && !b) op.direct = false;
       if (op.direct) {
@@ -355,7 +388,7 @@ void uring_writer_main(ds_flush *f, Uring *ring, unsigned depth) {
           j = f->queue.front();
           f->queue.pop_front();
         }
-        (void)ds_snapshot_release_chunk(f->ev, j.ptr);
+        release_piece(f, j);
       }
       break;
     }
@@ -404,15 +437,41 @@ void dispatcher_main(ds_flush *f) {
       flush_fail(f, rc, 0);
       break;
     }
-    IoJob j;
-    j.ptr = const_cast<void *>(p);
-    j.off = off;
-    j.len = len;
+    int pieces = 0;
+    for_each_piece(f->targets, off, len, [&](uint32_t, uint64_t, uint64_t, uint64_t) { ++pieces; });
+    Held *held = pieces ? new (std::nothrow) Held : nullptr;
+    if (!held) {  // nothing to write (no file covers the range) or no memory: the slot goes straight back
+      if (pieces) flush_fail(f, DS_ENOMEM, 0);
+      rc = ds_snapshot_release_chunk(f->ev, const_cast<void *>(p));
+      if (rc != DS_OK) flush_fail(f, rc, 0);
+      continue;
+    }
+    held->ptr = const_cast<void *>(p);
+    held->left.store(pieces);
     {
       std::lock_guard<std::mutex> lk(f->mu);
-      f->queue.push_back(j);
+      try {
+        for_each_piece(f->targets, off, len, [&](uint32_t t, uint64_t file_off, uint64_t in_chunk, uint64_t n) {
+          IoJob j;
+          j.ptr = (uint8_t *)held->ptr + in_chunk;
+          j.off = file_off;
+          j.len = n;
+          j.target = t;
+          j.held = held;
+          f->queue.push_back(j);
+          --pieces;
+        });
+      } catch (const std::bad_alloc &) {
+        flush_fail(f, DS_ENOMEM, 0);
+      }
     }
-    f->cv.notify_one();
+    // pieces that could not be queued give their share of the slot back here
+    for (; pieces > 0; --pieces) {
+      IoJob j;
+      j.held = held;
+      release_piece(f, j);
+    }
+    f->cv.notify_all();
   }
   {
     std::lock_guard<std::mutex> lk(f->mu);
@@ -425,11 +484,30 @@ void dispatcher_main(ds_flush *f) {
 
 int ds_flush_start_fds(ds_event *ev, int fd_buffered, int fd_direct, uint32_t threads, uint32_t flags,
                        ds_flush **out) {
-  if (!ev || !out || fd_buffered < 0 || (flags & ~(DS_FILE_DIRECT | DS_FILE_SYNC | DS_FILE_URING))) return DS_EINVAL;
+  DsFileTarget t;
+  t.begin = 0;
+  t.end = ~(uint64_t)0;
+  t.fd_buffered = fd_buffered;
+  t.fd_direct = fd_direct;
+  try {
+    return ds_flush_start_targets(ev, std::vector<DsFileTarget>(1, t), threads, flags, out);
+  } catch (const std::bad_alloc &) {
+    return DS_ENOMEM;
+  }
+}
+
+int ds_flush_start_targets(ds_event *ev, std::vector<DsFileTarget> targets, uint32_t threads, uint32_t flags,
+                           ds_flush **out) {
+  if (!ev || !out || targets.empty() || (flags & ~(DS_FILE_DIRECT | DS_FILE_SYNC | DS_FILE_URING))) return DS_EINVAL;
+  for (size_t t = 0; t < targets.size(); ++t)
+    if (targets[t].fd_buffered < 0 || targets[t].end < targets[t].begin ||
+        targets[t].begin != (t ? targets[t - 1].end : 0))
+      return DS_EINVAL;
   if (threads == 0) threads = 4;
   if (threads > 64) return DS_EINVAL;
   ds_flush *f = new (std::nothrow) ds_flush;
   if (!f) return DS_ENOMEM;
+  f->targets.swap(targets);
   // io_uring if asked for and the kernel lets this process have it; else the pwrite threads
   Uring *ring = nullptr;
   if (flags & DS_FILE_URING) {
@@ -443,8 +521,6 @@ int ds_flush_start_fds(ds_event *ev, int fd_buffered, int fd_direct, uint32_t th
   f->ev = ev;
   f->flags = flags;
   f->own_fds = false;
-  f->fd_buffered = fd_buffered;
-  f->fd_direct = fd_direct;
   f->t0 = now_s();
   // writers first: a dispatcher without anyone to release slots would wait for ever
   try {
@@ -482,6 +558,150 @@ int ds_flush_start_fds(ds_event *ev, int fd_buffered, int fd_direct, uint32_t th
   return DS_OK;
 }
 
+// The files' descriptors stay the caller's.  Ring slots are read by `threads` readers at once, a slot that
+// spans two files in two pieces, and submitted in image order.
+int ds_restore_from_targets(ds_engine *engine, const ds_plan *plan, const std::vector<DsFileTarget> &targets,
+                            uint32_t threads, void *compute_stream, ds_event **out) {
+  if (!engine || !plan || !out || targets.empty()) return DS_EINVAL;
+  if (threads == 0) threads = 4;
+  if (threads > 64) return DS_EINVAL;
+  for (size_t t = 0; t < targets.size(); ++t)
+    if (targets[t].fd_buffered < 0 || targets[t].end < targets[t].begin ||
+        targets[t].begin != (t ? targets[t - 1].end : 0))
+      return DS_EINVAL;
+  if (targets.back().end < plan->total_bytes) return DS_EINVAL;
+  ds_event *ev = nullptr;
+  int rc = ds_restore_begin(engine, plan, compute_stream, &ev);
+  if (rc != DS_OK) return rc;
+  struct Shared {
+    std::mutex mu;
+    std::condition_variable cv;
+    std::deque<IoJob> todo;
+    std::vector<int> done;  // per window position: 0 pending, 1 read, <0 = -errno
+    std::vector<int> left;  // pieces of that slot still being read
+    bool stop = false;
+  } sh;
+  std::atomic<bool> direct_usable{true}, bounce_usable{true};
+  const uint32_t window = 2 * threads;  // slots beyond the readers, so that one slow read does not idle the others
+  sh.done.assign(window, 0);
+  sh.left.assign(window, 0);
+  std::vector<void *> win(window);  // the slot at each window position
+  std::vector<std::thread> readers;
+  auto reader = [&]() {
+    Bounce bounce;
+    for (;;) {
+      IoJob j;
+      {
+        std::unique_lock<std::mutex> lk(sh.mu);
+        sh.cv.wait(lk, [&] { return sh.stop || !sh.todo.empty(); });
+        if (sh.todo.empty()) return;
+        j = sh.todo.front();
+        sh.todo.pop_front();
+      }
+      // the same three ways as in writer_main: direct into the ring, direct into an aligned buffer of
+      // ordinary memory and a copy, buffered
+      const int fd_direct = targets[j.target].fd_direct, fd_buffered = targets[j.target].fd_buffered;
+      const bool direct = fd_direct >= 0 && direct_ok(j.ptr, j.off, j.len);
+      int e = -1;
+      if (direct && direct_usable.load()) {
+        e = read_all(fd_direct, (uint8_t *)j.ptr, j.len, j.off);
+        if (e == EFAULT || e == EINVAL) {
+          direct_usable.store(false);
+          e = -1;
+        }
+      }
+      if (e == -1 && direct && bounce_usable.load()) {
+        uint8_t *b = bounce.fit(j.len);
+        if (b) {
+          e = read_all(fd_direct, b, j.len, j.off);
+          if (e == 0) std::memcpy(j.ptr, b, j.len);
+          if (e == EINVAL) {
+            bounce_usable.store(false);
+            e = -1;
+          }
+        }
+      }
+      if (e == -1) e = read_all(fd_buffered, (uint8_t *)j.ptr, j.len, j.off);
+      {
+        std::lock_guard<std::mutex> lk(sh.mu);
+        if (e) sh.done[j.slot] = -e;  // the first failed piece decides; the slot is never submitted then
+        if (--sh.left[j.slot] == 0 && sh.done[j.slot] == 0) sh.done[j.slot] = 1;
+      }
+      sh.cv.notify_all();
+    }
+  };
+  int err_no = 0;
+  try {
+    for (uint32_t i = 0; i < threads; ++i) readers.emplace_back(reader);
+  } catch (...) {
+    rc = DS_ENOMEM;
+  }
+  uint64_t handed = 0, submitted = 0;
+  bool eof = false;
+  while (rc == DS_OK && (!eof || submitted < handed)) {
+    // fill the window
+    while (!eof && handed - submitted < window) {
+      void *p = nullptr;
+      uint64_t off = 0, len = 0;
+      int r = ds_restore_next_slot(ev, &p, &off, &len);
+      if (r == DS_EOF) { eof = true; break; }
+      if (r == DS_EBUSY) break;  // the ring is smaller than the window: submit first
+      if (r != DS_OK) { rc = r; break; }
+      const int slot = (int)(handed % window);
+      win[slot] = p;
+      int pieces = 0;
+      for_each_piece(targets, off, len, [&](uint32_t, uint64_t, uint64_t, uint64_t) { ++pieces; });
+      {
+        std::lock_guard<std::mutex> lk(sh.mu);
+        sh.done[slot] = pieces ? 0 : 1;
+        sh.left[slot] = pieces;
+        for_each_piece(targets, off, len, [&](uint32_t t, uint64_t file_off, uint64_t in_slot, uint64_t n) {
+          IoJob j;
+          j.ptr = (uint8_t *)p + in_slot;
+          j.off = file_off;
+          j.len = n;
+          j.slot = slot;
+          j.target = t;
+          sh.todo.push_back(j);
+        });
+      }
+      sh.cv.notify_all();
+      ++handed;
+    }
+    if (rc != DS_OK || submitted == handed) continue;
+    // submit the oldest one once it has been read
+    const int pos = (int)(submitted % window);
+    int state;
+    {
+      std::unique_lock<std::mutex> lk(sh.mu);
+      sh.cv.wait(lk, [&] { return sh.left[pos] == 0 && sh.done[pos] != 0; });
+      state = sh.done[pos];
+    }
+    if (state < 0) {
+      rc = DS_EIO;
+      err_no = -state;
+      break;
+    }
+    rc = ds_restore_submit(ev, win[pos]);
+    ++submitted;
+  }
+  {
+    std::lock_guard<std::mutex> lk(sh.mu);
+    sh.stop = true;
+    if (rc != DS_OK) sh.todo.clear();
+  }
+  sh.cv.notify_all();
+  for (std::thread &t : readers)
+    if (t.joinable()) t.join();
+  if (rc != DS_OK) {
+    g_last_errno = err_no;
+    (void)ds_event_destroy(ev);
+    return rc;
+  }
+  *out = ev;
+  return DS_OK;
+}
+
 void ds_set_errno(int e) { g_last_errno = e; }
 
 bool ds_io_uring_available() {
@@ -515,6 +735,51 @@ int ds_flush_start(ds_event *ev, const char *path, uint32_t threads, uint32_t fl
   return DS_OK;
 }
 
+int ds_flush_start_files(ds_event *ev, const char *const *paths, uint32_t n_files, uint32_t threads, uint32_t flags,
+                         ds_flush **out) {
+  if (!ev || !paths || !out || (flags & ~(DS_FILE_DIRECT | DS_FILE_SYNC | DS_FILE_URING))) return DS_EINVAL;
+  if (threads > 64) return DS_EINVAL;
+  const ds_plan *plan = ds_event_plan(ev);
+  if (!plan || (size_t)n_files + 1 != plan->file_begin.size()) return DS_EINVAL;
+  for (uint32_t k = 0; k < n_files; ++k)
+    if (!paths[k]) return DS_EINVAL;
+  std::vector<DsFileTarget> targets;
+  int rc = DS_OK;
+  try {
+    targets.resize(n_files);
+  } catch (const std::bad_alloc &) {
+    return DS_ENOMEM;
+  }
+  for (uint32_t k = 0; k < n_files && rc == DS_OK; ++k) {
+    DsFileTarget &t = targets[k];
+    t.begin = plan->file_begin[k];
+    t.end = plan->file_begin[k + 1];
+    t.fd_buffered = open(paths[k], O_WRONLY | O_CREAT | O_TRUNC | O_CLOEXEC, 0644);
+    if (t.fd_buffered < 0) {
+      g_last_errno = errno;
+      rc = DS_EIO;
+      break;
+    }
+    t.fd_direct = (flags & DS_FILE_DIRECT) ? open(paths[k], O_WRONLY | O_DIRECT | O_CLOEXEC) : -1;
+  }
+  if (rc == DS_OK) {
+    try {
+      rc = ds_flush_start_targets(ev, targets, threads, flags, out);
+    } catch (const std::bad_alloc &) {
+      rc = DS_ENOMEM;
+    }
+  }
+  if (rc != DS_OK) {
+    for (const DsFileTarget &t : targets) {
+      if (t.fd_direct >= 0) close(t.fd_direct);
+      if (t.fd_buffered >= 0) close(t.fd_buffered);
+    }
+    return rc;
+  }
+  (*out)->own_fds = true;
+  return DS_OK;
+}
+
 int ds_flush_wait(ds_flush *f, uint64_t *bytes_written, double *seconds) {
   if (!f) return DS_EINVAL;
   if (f->dispatcher.joinable()) f->dispatcher.join();
@@ -523,14 +788,16 @@ int ds_flush_wait(ds_flush *f, uint64_t *bytes_written, double *seconds) {
     if (t.joinable()) t.join();
   int status = f->status.load();
   if (f->own_fds) {
-    if (status == DS_OK && (f->flags & DS_FILE_SYNC) && fsync(f->fd_buffered) != 0) {
-      status = DS_EIO;
-      f->err_no.store(errno);
-    }
-    if (f->fd_direct >= 0) close(f->fd_direct);
-    if (close(f->fd_buffered) != 0 && status == DS_OK) {
-      status = DS_EIO;
-      f->err_no.store(errno);
+    for (const DsFileTarget &t : f->targets) {
+      if (status == DS_OK && (f->flags & DS_FILE_SYNC) && fsync(t.fd_buffered) != 0) {
+        status = DS_EIO;
+        f->err_no.store(errno);
+      }
+      if (t.fd_direct >= 0) close(t.fd_direct);
+      if (close(t.fd_buffered) != 0 && status == DS_OK) {
+        status = DS_EIO;
+        f->err_no.store(errno);
+      }
     }
   }
   f->t1 = now_s();
@@ -544,140 +811,66 @@ int ds_flush_wait(ds_flush *f, uint64_t *bytes_written, double *seconds) {
 int ds_restore_from_file(ds_engine *engine, const ds_plan *plan, const char *path, uint32_t threads, uint32_t flags,
                          void *compute_stream, ds_event **out) {
   if (!engine || !plan || !path || !out || (flags & ~DS_FILE_DIRECT)) return DS_EINVAL;
-  if (threads == 0) threads = 4;
   if (threads > 64) return DS_EINVAL;
-  const int fd_buffered = open(path, O_RDONLY | O_CLOEXEC);
-  if (fd_buffered < 0) {
+  DsFileTarget t;
+  t.begin = 0;
+  t.end = ~(uint64_t)0;
+  t.fd_buffered = open(path, O_RDONLY | O_CLOEXEC);
+  if (t.fd_buffered < 0) {
     g_last_errno = errno;
     return DS_EIO;
   }
-  const int fd_direct = (flags & DS_FILE_DIRECT) ? open(path, O_RDONLY | O_DIRECT | O_CLOEXEC) : -1;
-  ds_event *ev = nullptr;
-  int rc = ds_restore_begin(engine, plan, compute_stream, &ev);
-  if (rc != DS_OK) {
-    if (fd_direct >= 0) close(fd_direct);
-    close(fd_buffered);
-    return rc;
-  }
-  // A window of slots is read by `threads` readers at once and submitted in file order.
-  struct Shared {
-    std::mutex mu;
-    std::condition_variable cv;
-    std::deque<IoJob> todo;
-    std::vector<int> done;  // per window position: 0 pending, 1 read, <0 = -errno
-    bool stop = false;
-  } sh;
-  std::atomic<bool> direct_usable{true}, bounce_usable{true};
-  const uint32_t window = 2 * threads;  // slots beyond the readers, so that one slow read does not idle the others
-  sh.done.assign(window, 0);
-  std::vector<IoJob> win(window);
-  std::vector<std::thread> readers;
-  auto reader = [&]() {
-    Bounce bounce;
-    for (;;) {
-      IoJob j;
-      {
-        std::unique_lock<std::mutex> lk(sh.mu);
-        sh.cv.wait(lk, [&] { return sh.stop || !sh.todo.empty(); });
-        if (sh.todo.empty()) return;
-        j = sh.todo.front();
-        sh.todo.pop_front();
-      }
-      // the same three ways as in writer_main: direct into the ring, direct into an aligned buffer of
-      // ordinary memory and a copy, buffered
-      const bool direct = fd_direct >= 0 && direct_ok(j.ptr, j.off, j.len);
-      int e = -1;
-      if (direct && direct_usable.load()) {
-        e = read_all(fd_direct, (uint8_t *)j.ptr, j.len, j.off);
-        if (e == EFAULT || e == EINVAL) {
-          direct_usable.store(false);
-          e = -1;
-        }
-      }
-      if (e == -1 && direct && bounce_usable.load()) {
-        uint8_t *b = bounce.fit(j.len);
-        if (b) {
-          e = read_all(fd_direct, b, j.len, j.off);
-          if (e == 0) std::memcpy(j.ptr, b, j.len);
-          if (e == EINVAL) {
-            bounce_usable.store(false);
-            e = -1;
-          }
-        }
-      }
-      if (e == -1) e = read_all(fd_buffered, (uint8_t *)j.ptr, j.len, j.off);
-      {
-        std::lock_guard<std::mutex> lk(sh.mu);
-        sh.done[j.slot] = e ? -e : 1;
-      }
-      sh.cv.notify_all();
-    }
-  };
-  int err_no = 0;
+  t.fd_direct = (flags & DS_FILE_DIRECT) ? open(path, O_RDONLY | O_DIRECT | O_CLOEXEC) : -1;
+  int rc;
   try {
-    for (uint32_t i = 0; i < threads; ++i) readers.emplace_back(reader);
-  } catch (...) {
+    rc = ds_restore_from_targets(engine, plan, std::vector<DsFileTarget>(1, t), threads, compute_stream, out);
+  } catch (const std::bad_alloc &) {
     rc = DS_ENOMEM;
   }
-  uint64_t handed = 0, submitted = 0;
-  bool eof = false;
-  while (rc == DS_OK && (!eof || submitted < handed)) {
-    // fill the window
-    while (!eof && handed - submitted < window) {
-      void *p = nullptr;
-      uint64_t off = 0, len = 0;
-      int r = ds_restore_next_slot(ev, &p, &off, &len);
-      if (r == DS_EOF) { eof = true; break; }
-      if (r == DS_EBUSY) break;  // the ring is smaller than the window: submit first
-      if (r != DS_OK) { rc = r; break; }
-      IoJob j;
-      j.ptr = p;
-      j.off = off;
-      j.len = len;
-      j.slot = (int)(handed % window);
-      win[j.slot] = j;
-      {
-        std::lock_guard<std::mutex> lk(sh.mu);
-        sh.done[j.slot] = 0;
-        sh.todo.push_back(j);
-      }
-      sh.cv.notify_one();
-      ++handed;
-    }
-    if (rc != DS_OK || submitted == handed) continue;
-    // submit the oldest one once it has been read
-    const int pos = (int)(submitted % window);
-    int state;
-    {
-      std::unique_lock<std::mutex> lk(sh.mu);
-      sh.cv.wait(lk, [&] { return sh.done[pos] != 0; });
-      state = sh.done[pos];
-    }
-    if (state < 0) {
+  if (t.fd_direct >= 0) close(t.fd_direct);
+  close(t.fd_buffered);
+  return rc;
+}
+
+int ds_restore_from_files(ds_engine *engine, const ds_plan *plan, const char *const *paths, uint32_t n_files,
+                          uint32_t threads, uint32_t flags, void *compute_stream, ds_event **out) {
+  if (!engine || !plan || !paths || !out || (flags & ~DS_FILE_DIRECT)) return DS_EINVAL;
+  if (threads > 64 || (size_t)n_files + 1 != plan->file_begin.size()) return DS_EINVAL;
+  for (uint32_t k = 0; k < n_files; ++k)
+    if (!paths[k]) return DS_EINVAL;
+  std::vector<DsFileTarget> targets;
+  int rc = DS_OK;
+  try {
+    targets.resize(n_files);
+  } catch (const std::bad_alloc &) {
+    return DS_ENOMEM;
+  }
+  for (uint32_t k = 0; k < n_files; ++k) {
+    DsFileTarget &t = targets[k];
+    t.begin = plan->file_begin[k];
+    t.end = plan->file_begin[k + 1];
+    t.fd_buffered = open(paths[k], O_RDONLY | O_CLOEXEC);
+    if (t.fd_buffered < 0) {
+      g_last_errno = errno;
       rc = DS_EIO;
-      err_no = -state;
       break;
     }
-    rc = ds_restore_submit(ev, win[pos].ptr);
-    ++submitted;
+    t.fd_direct = (flags & DS_FILE_DIRECT) ? open(paths[k], O_RDONLY | O_DIRECT | O_CLOEXEC) : -1;
   }
-  {
-    std::lock_guard<std::mutex> lk(sh.mu);
-    sh.stop = true;
-    if (rc != DS_OK) sh.todo.clear();
+  if (rc == DS_OK) {
+    try {
+      rc = ds_restore_from_targets(engine, plan, targets, threads, compute_stream, out);
+    } catch (const std::bad_alloc &) {
+      rc = DS_ENOMEM;
+    }
   }
-  sh.cv.notify_all();
-  for (std::thread &t : readers)
-    if (t.joinable()) t.join();
-  if (fd_direct >= 0) close(fd_direct);
-  close(fd_buffered);
-  if (rc != DS_OK) {
-    g_last_errno = err_no;
-    (void)ds_event_destroy(ev);
-    return rc;
+  const int keep = g_last_errno;
+  for (const DsFileTarget &t : targets) {
+    if (t.fd_direct >= 0) close(t.fd_direct);
+    if (t.fd_buffered >= 0) close(t.fd_buffered);
   }
-  *out = ev;
-  return DS_OK;
+  g_last_errno = keep;
+  return rc;
 }
 
 }  // extern "C"

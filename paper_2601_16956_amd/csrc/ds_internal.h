@@ -63,13 +63,30 @@ struct DsManifestEntry {
   uint32_t dtype;
   uint32_t ndim;
   int64_t shape[DS_MAX_DIMS];  // unused extents 0
-  uint64_t file_offset;
+  uint64_t file_offset;   // inside the shard's own file
   uint64_t nbytes;
+  uint64_t image_offset;  // in the plan's image (= file_offset + where the file's region starts)
+  uint32_t file;
+};
+
+// One file of a flush or of a restore: image bytes [begin, end) are the file's bytes [0, end - begin).
+// fd_direct may be -1.
+struct DsFileTarget {
+  uint64_t begin = 0, end = 0;
+  int fd_buffered = -1, fd_direct = -1;
 };
 
 // The flush of a snapshot into a file that somebody else opened and will close (the checkpoint writer).
 // fd_direct may be -1.
 int ds_flush_start_fds(ds_event *ev, int fd_buffered, int fd_direct, uint32_t threads, uint32_t flags, ds_flush **out);
+// The same into several files: the targets are in image order, the first begins at 0 and each begins where
+// the one before ends.  May throw std::bad_alloc (the vector is taken by value).
+int ds_flush_start_targets(ds_event *ev, std::vector<DsFileTarget> targets, uint32_t threads, uint32_t flags,
+                           ds_flush **out);
+// Image -> tensors out of files that the caller opened and will close; the targets must cover the image.
+int ds_restore_from_targets(ds_engine *engine, const ds_plan *plan, const std::vector<DsFileTarget> &targets,
+                            uint32_t threads, void *compute_stream, ds_event **out);
+const ds_plan *ds_event_plan(const ds_event *ev);  // the plan a snapshot or restore was started with
 void ds_set_errno(int e);  // what ds_last_errno() returns on this thread
 bool ds_io_uring_available();  // can this process set up an io_uring?
 void ds_drop_pinned_cache();   // frees the pinned ring kept from a destroyed engine
@@ -82,6 +99,7 @@ struct ds_plan {
   uint64_t n_strided = 0;
   uint32_t chunk_log2 = 0;
   std::vector<DsManifestEntry> manifest;   // table order as given
+  std::vector<uint64_t> file_begin;        // n_files + 1 entries: where each file's tensor region starts in the image
   std::vector<DsTile> tiles;               // image order
   std::vector<uint64_t> tile_off;          // n_tiles + 1 entries, last = total_bytes (host only)
   std::vector<DsTileHot> hot;              // n_tiles + 1 entries, image order, last = sentinel

@@ -238,8 +238,35 @@ int ds_layout_assign(ds_shard_desc *desc, size_t n, uint64_t align, uint64_t *to
   return DS_OK;
 }
 
+int ds_layout_assign_files(ds_shard_desc *desc, const uint32_t *file_of, size_t n, uint32_t n_files, uint64_t align,
+                           uint64_t *region_bytes, uint64_t *total) {
+  if ((!desc && n) || (!file_of && n) || !total || !is_pow2(align) || align < 16) return DS_EINVAL;
+  if (n_files == 0 || n_files > DS_MAX_FILES) return DS_EINVAL;
+  std::vector<uint64_t> sizes(n), at(n_files, 0);
+  for (size_t i = 0; i < n; ++i)
+    if (!shard_bytes(desc[i], &sizes[i]) || file_of[i] >= n_files) return DS_EINVAL;
+  for (size_t i = 0; i < n; ++i) {
+    uint64_t &a = at[file_of[i]];
+    desc[i].file_offset = a;
+    a = round_up(a + sizes[i], align);
+  }
+  uint64_t sum = 0;
+  for (uint32_t f = 0; f < n_files; ++f) {
+    if (region_bytes) region_bytes[f] = at[f];
+    sum += at[f];
+  }
+  *total = sum;
+  return DS_OK;
+}
+
 int ds_plan_create(const ds_shard_desc *desc, size_t n, uint64_t align, uint32_t flags, ds_plan **out) {
-  if ((!desc && n) || !out || !is_pow2(align) || align < 16) return DS_EINVAL;
+  return ds_plan_create_files(desc, nullptr, n, 1, align, flags, out);
+}
+
+int ds_plan_create_files(const ds_shard_desc *given, const uint32_t *file_of, size_t n, uint32_t n_files,
+                         uint64_t align, uint32_t flags, ds_plan **out) {
+  if ((!given && n) || !out || !is_pow2(align) || align < 16) return DS_EINVAL;
+  if (n_files == 0 || n_files > DS_MAX_FILES || (!file_of && n_files > 1 && n)) return DS_EINVAL;
   if (flags & ~(DS_PLAN_STRICT | DS_PLAN_HOST_ONLY | DS_PLAN_CHECK_MEMORY)) return DS_EINVAL;
   if ((flags & DS_PLAN_CHECK_MEMORY) && (flags & DS_PLAN_HOST_ONLY)) return DS_EINVAL;
   ds_plan *p = new (std::nothrow) ds_plan;
@@ -250,11 +277,34 @@ int ds_plan_create(const ds_shard_desc *desc, size_t n, uint64_t align, uint32_t
     p->n_shards = n;
     p->manifest.resize(n);
     std::vector<uint64_t> sizes(n);
+    // Several files: every file's tensor region (its shards at the offsets given, which count from the
+    // start of THAT file) goes into the one image behind the regions of the files before it.  From here
+    // on `desc` holds offsets in the image; the manifest keeps both.
+    std::vector<ds_shard_desc> in_image;
+    const ds_shard_desc *desc = given;
+    p->file_begin.assign((size_t)n_files + 1, 0);
+    if (file_of) {
+      std::vector<uint64_t> region(n_files, 0);
+      for (size_t i = 0; i < n && rc == DS_OK; ++i) {
+        if (!shard_bytes(given[i], &sizes[i]) || file_of[i] >= n_files) { rc = DS_EINVAL; break; }
+        if (given[i].file_offset > ((uint64_t)1 << 62)) { rc = DS_EINVAL; break; }
+        region[file_of[i]] = std::max(region[file_of[i]], round_up(given[i].file_offset + sizes[i], align));
+      }
+      for (uint32_t f = 0; f < n_files && rc == DS_OK; ++f) {
+        p->file_begin[f + 1] = p->file_begin[f] + region[f];
+        if (p->file_begin[f + 1] > ((uint64_t)1 << 62)) rc = DS_EINVAL;
+      }
+      if (rc == DS_OK) {
+        in_image.assign(given, given + n);
+        for (size_t i = 0; i < n; ++i) in_image[i].file_offset += p->file_begin[file_of[i]];
+        desc = in_image.data();
+      }
+    }
     uint64_t end_max = 0;
     for (size_t i = 0; i < n && rc == DS_OK; ++i) {
       const ds_shard_desc &d = desc[i];
       if (!shard_bytes(d, &sizes[i])) { rc = DS_EINVAL; break; }
-      if (d.file_offset & (align - 1)) { rc = DS_EALIGN; break; }
+      if (given[i].file_offset & (align - 1)) { rc = DS_EALIGN; break; }
       if (d.file_offset > ((uint64_t)1 << 62)) { rc = DS_EINVAL; break; }
       if (sizes[i]) {
         const uint64_t es = (uint64_t)ds_itemsize(d.dtype);
@@ -273,13 +323,17 @@ int ds_plan_create(const ds_shard_desc *desc, size_t n, uint64_t align, uint32_t
       me.dtype = d.dtype;
       me.ndim = d.ndim;
       for (uint32_t j = 0; j < DS_MAX_DIMS; ++j) me.shape[j] = j < d.ndim ? d.shape[j] : 0;
-      me.file_offset = d.file_offset;
+      me.file_offset = given[i].file_offset;
+      me.image_offset = d.file_offset;
+      me.file = file_of ? file_of[i] : 0;
       me.nbytes = sizes[i];
       p->payload_bytes += sizes[i];
       end_max = std::max(end_max, d.file_offset + sizes[i]);
     }
     if (rc == DS_OK) {
-      p->total_bytes = round_up(end_max, align);
+      // one file: up to the end of the last shard; several: the regions, which cover that
+      if (file_of) p->total_bytes = p->file_begin[n_files];
+      else p->total_bytes = p->file_begin[1] = round_up(end_max, align);
       // image order of the non-empty shards
       std::vector<size_t> order;
       order.reserve(n);
@@ -428,6 +482,21 @@ int ds_plan_info(const ds_plan *plan, ds_plan_stats *out) {
   out->n_strided = plan->n_strided;
   out->n_general_chunks = plan->n_general;
   out->align = plan->align;
+  out->n_files = plan->file_begin.size() - 1;
+  return DS_OK;
+}
+
+int ds_plan_file(const ds_plan *plan, uint32_t f, uint64_t *image_begin, uint64_t *region_bytes) {
+  if (!plan || (size_t)f + 1 >= plan->file_begin.size()) return DS_EINVAL;
+  if (image_begin) *image_begin = plan->file_begin[f];
+  if (region_bytes) *region_bytes = plan->file_begin[f + 1] - plan->file_begin[f];
+  return DS_OK;
+}
+
+int ds_plan_shard_file(const ds_plan *plan, size_t i, uint32_t *file, uint64_t *image_offset) {
+  if (!plan || i >= plan->manifest.size()) return DS_EINVAL;
+  if (file) *file = plan->manifest[i].file;
+  if (image_offset) *image_offset = plan->manifest[i].image_offset;
   return DS_OK;
 }
 

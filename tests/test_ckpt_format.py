@@ -248,6 +248,121 @@ def test_library_file_equals_oracle_file_and_reads_back(tmp_path, maker):
     ds.ds_plan_destroy(plan)
 
 
+def _rank_of_files(w, file_of, n_files):
+    """Host-only plan of several files over workload `w`, and the oracle's side of it: per-file images
+    (each file's shards packed alone), offsets, regions."""
+    n = len(w.shards)
+    d = ds.make_descs(w.shards, w.arena.ctypes.data)
+    regions, total = ds.ds_layout_assign_files(d, file_of, n, n_files, w.align)
+    offs, want_regions, begins = fmt.rank_files([s.nbytes for s in w.shards], file_of, n_files, w.align)
+    assert regions == want_regions and total == sum(want_regions)
+    assert [d[i].file_offset for i in range(n)] == offs
+    plan = ds.ds_plan_create_files(d, file_of, n, n_files, w.align, ds.DS_PLAN_HOST_ONLY | ds.DS_PLAN_STRICT)
+    alone = []
+    for f in range(n_files):
+        sub = [s for s, g in zip(w.shards, file_of) if g == f]
+        t = orc.table(sub, w.arena.ctypes.data)
+        assert orc.layout(t, len(sub), w.align) == regions[f]
+        alone.append(orc.pack(t, len(sub), regions[f]).tobytes())
+    return plan, d, offs, regions, begins, alone
+
+
+def test_plan_of_several_files_is_the_oracles_layout():
+    w = W.fragmentation(300, max_bytes=1 << 13, seed=31)
+    n = len(w.shards)
+    rng = random.Random(11)
+    file_of = [rng.choice([0, 1, 1, 2, 4]) for _ in range(n)]          # file 3 gets nothing
+    plan, d, offs, regions, begins, alone = _rank_of_files(w, file_of, 5)
+    info = ds.ds_plan_info(plan)
+    assert info["n_files"] == 5 and info["total_bytes"] == sum(regions) and info["n_shards"] == n
+    for f in range(5):
+        assert ds.ds_plan_file(plan, f) == (begins[f], regions[f])
+    with pytest.raises(ds.DsError) as e:
+        ds.ds_plan_file(plan, 5)
+    assert e.value.code == ds.DS_EINVAL
+    for i in (0, 1, n // 2, n - 1):
+        assert ds.ds_plan_shard(plan, i)[2] == offs[i]                 # inside its file
+        assert ds.ds_plan_shard_file(plan, i) == (file_of[i], begins[file_of[i]] + offs[i])
+    ds.ds_plan_destroy(plan)
+    # a plan of one file says so, and is the plan of ds_plan_create
+    d1 = ds.make_descs(w.shards, w.arena.ctypes.data)
+    total = ds.ds_layout_assign(d1, n, w.align)
+    p1 = ds.ds_plan_create_files(d1, [0] * n, n, 1, w.align, ds.DS_PLAN_HOST_ONLY)
+    assert ds.ds_plan_info(p1)["n_files"] == 1 and ds.ds_plan_file(p1, 0) == (0, total)
+    assert ds.ds_plan_shard_file(p1, n - 1) == (0, d1[n - 1].file_offset)
+    ds.ds_plan_destroy(p1)
+
+    # what is refused
+    def create(file_of, n_files, flags=ds.DS_PLAN_HOST_ONLY, table=d):
+        return ds.ds_plan_create_files(table, file_of, n, n_files, w.align, flags)
+    for bad_of, bad_n in (([5] + file_of[1:], 5), (file_of, 0), (file_of, 65537)):
+        with pytest.raises(ds.DsError) as e:
+            create(bad_of, bad_n)
+        assert e.value.code == ds.DS_EINVAL
+    first_of_1 = file_of.index(1)
+    second_of_1 = file_of.index(1, first_of_1 + 1)
+    keep = d[second_of_1].file_offset
+    d[second_of_1].file_offset = d[first_of_1].file_offset             # two shards of one file on top of each other
+    with pytest.raises(ds.DsError) as e:
+        create(file_of, 5)
+    assert e.value.code == ds.DS_EOVERLAP
+    d[second_of_1].file_offset = keep
+    moved = list(file_of)
+    moved[second_of_1] = 3                                             # now alone in file 3, but not at its offset 0
+    with pytest.raises(ds.DsError) as e:
+        create(moved, 5, ds.DS_PLAN_HOST_ONLY | ds.DS_PLAN_STRICT)
+    assert e.value.code == ds.DS_EGAP
+    ds.ds_plan_destroy(create(moved, 5))                               # without STRICT the hole is allowed
+
+
+def test_library_part_files_equal_the_oracle_files(tmp_path):
+    """One plan, several checkpoint files: every part written by the library (tensor region from host
+    memory) is byte for byte the oracle's file of that part, and each reader matches its own part only."""
+    w = W.fragmentation(240, max_bytes=1 << 13, seed=32)
+    n = len(w.shards)
+    rng = random.Random(12)
+    file_of = [rng.choice([0, 1, 3]) for _ in range(n)]                # file 2 is empty
+    plan, d, offs, regions, begins, alone = _rank_of_files(w, file_of, 4)
+    image = b"".join(alone)
+    tensors = [m[:3] + (offs[i],) + m[4:] for i, m in enumerate(_manifest(plan, n))]
+    assert tensors == _manifest(plan, n)                               # the manifest holds offsets inside the files
+    appends = [[(7, bytes([f]) * (5 + f)), (2 ** 64 - 1, b""), (7, b"more")] for f in range(4)]
+    want = fmt.build_rank_files(w.align, image, tensors, file_of, 4, appends)
+    paths = [str(tmp_path / f"part{f}.ckpt") for f in range(4)]
+    for f in range(4):
+        ck = ds.ds_ckpt_create_part(paths[f], plan, f)
+        buf = np.frombuffer(alone[f], dtype=np.uint8)
+        if regions[f]:
+            ds.ds_ckpt_write_region(ck, 0, buf.ctypes.data, regions[f])
+        with pytest.raises(ds.DsError) as e:                           # a part ends where its region ends
+            ds.ds_ckpt_write_region(ck, regions[f], buf.ctypes.data, 16)
+        assert e.value.code == ds.DS_ERANGE
+        for oid, data in appends[f]:
+            ds.ds_ckpt_append(ck, oid, data)
+        nbytes, _ = ds.ds_ckpt_finish(ck)
+        assert nbytes == len(want[f]) and open(paths[f], "rb").read() == want[f], f
+    readers = [ds.ds_ckpt_open(p) for p in paths]
+    for f, r in enumerate(readers):
+        ds.ds_ckpt_matches_plan_part(r, plan, f)
+        lay = ds.ds_ckpt_layout_info(r)
+        assert lay["tensor_bytes"] == regions[f] and lay["n_tensors"] == file_of.count(f)
+        with pytest.raises(ds.DsError) as e:
+            ds.ds_ckpt_matches_plan_part(r, plan, (f + 1) % 4)
+        assert e.value.code == ds.DS_EFORMAT
+        with pytest.raises(ds.DsError) as e:
+            ds.ds_ckpt_matches_plan(r, plan)                           # a plan of several files has no "the" file
+        assert e.value.code == ds.DS_EINVAL
+        assert ds.ds_ckpt_object_read(r, 7) == bytes([f]) * (5 + f) + b"more"
+    for bad in (lambda: ds.ds_ckpt_create(paths[0], plan), lambda: ds.ds_ckpt_create_part(paths[0], plan, 4),
+                lambda: ds.ds_ckpt_matches_plan_part(readers[0], plan, 4)):
+        with pytest.raises(ds.DsError) as e:
+            bad()
+        assert e.value.code == ds.DS_EINVAL
+    for r in readers:
+        ds.ds_ckpt_close(r)
+    ds.ds_plan_destroy(plan)
+
+
 def test_concurrent_appends_form_a_valid_log(tmp_path):
     w = W.tiny_gpt()
     plan, d, n, total, image = _host_plan(w)

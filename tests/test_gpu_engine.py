@@ -574,6 +574,141 @@ def test_rank_checkpoint_split_over_several_files(tmp_path):
             ds.ds_plan_destroy(f["plan"])
 
 
+@pytest.mark.parametrize("fflags", ["direct", "uring", "buffered"])
+def test_rank_checkpoint_of_several_files_through_one_plan(tmp_path, fflags):
+    """The same rank with ONE plan over all its files (Sec. VI-D; Sec. V-A3: one composite provider lays
+    out everything the rank owns): one gather launch sequence and one snapshot cover all files, the
+    flush cuts the ring's chunks at the files' boundaries.  The plan's image must be the oracle's
+    per-file images one behind the other, every file must be the oracle's file of its own shards, and
+    ONE restore out of all files must bring back every tensor.  The ring is smaller than the image
+    and its chunks are not aligned with the files, so chunks span two and more files."""
+    from oracle import ckpt_format as fmt
+    ds, orc, gu, torch = _mods()
+    file_flags = {"direct": ds.DS_FILE_DIRECT, "uring": ds.DS_FILE_URING | ds.DS_FILE_DIRECT, "buffered": 0}[fflags]
+    w = W.fragmentation(900, max_bytes=1 << 18, seed=41)
+    n = len(w.shards)
+    print(f"[case] several files through one plan, {fflags}", flush=True)
+    arena = torch.from_numpy(w.arena).to("cuda")
+    # seven files: one of a single shard, one empty, and a run of small shards dealt out in turn over two files
+    # (so that neighbours in the table land in different files)
+    cuts = [0, n // 7, n // 3, n // 3 + 1, (3 * n) // 4, n]
+    file_of = []
+    for i in range(n):
+        f = next(k for k in range(5) if cuts[k] <= i < cuts[k + 1])
+        file_of.append(f if f < 4 else 5 + (i & 1))                   # files 0..3, 5, 6; file 4 stays empty
+    n_files = 7
+    sizes = [sh.nbytes for sh in w.shards]
+    offs, regions, begins = fmt.rank_files(sizes, file_of, n_files, w.align)
+    alone, tabs = [], []
+    for f in range(n_files):
+        sub = [sh for sh, g in zip(w.shards, file_of) if g == f]
+        t = orc.table(sub, w.arena.ctypes.data)
+        assert orc.layout(t, len(sub), w.align) == regions[f]
+        alone.append(orc.pack(t, len(sub), regions[f], threads=4))
+        tabs.append((t, len(sub)))
+    want_image = np.concatenate(alone)
+    descs = ds.make_descs(w.shards, arena.data_ptr())
+    got_regions, total = ds.ds_layout_assign_files(descs, file_of, n, n_files, w.align)
+    assert got_regions == regions and total == want_image.size
+    plan = ds.ds_plan_create_files(descs, file_of, n, n_files, w.align, ds.DS_PLAN_STRICT | ds.DS_PLAN_CHECK_MEMORY)
+    eng = ds.ds_engine_create(4 * MiB, 1 * MiB, 2 * MiB, 2, 0, 0, 0)   # ring smaller than the image
+    s = torch.cuda.current_stream().cuda_stream
+    ck_paths = [str(tmp_path / f"rank0_{f}.ckpt") for f in range(n_files)]
+    raw_paths = [str(tmp_path / f"rank0_{f}.img") for f in range(n_files)]
+    try:
+        # the image itself, straight from the kernel
+        out = torch.full((total,), 0xFF, dtype=torch.uint8, device="cuda")
+        ds.ds_pack(plan, out.data_ptr(), 0, total, s)
+        torch.cuda.synchronize()
+        assert gu.first_mismatch(out.cpu().numpy(), want_image) is None
+        print("[step] image of the plan == the files' images one behind the other", flush=True)
+
+        # one snapshot into seven checkpoint files, objects appended meanwhile
+        ev = ds.ds_snapshot_async(eng, plan, s)
+        parts = [ds.ds_ckpt_create_part(ck_paths[f], plan, f, file_flags) for f in range(n_files)]
+        ds.ds_ckpt_flush_snapshot_parts(parts, ev, 3)
+        appends = [[(1, b"file %d" % f), (2, bytes(range(f + 1)))] for f in range(n_files)]
+        for f, ck in enumerate(parts):
+            for oid, data in appends[f]:
+                ds.ds_ckpt_append(ck, oid, data)
+        with pytest.raises(ds.DsError) as e:                           # once per snapshot
+            ds.ds_ckpt_flush_snapshot_parts(parts, ev, 3)
+        assert e.value.code == ds.DS_ESTATE
+        ds.ds_event_wait_on_stream(ev, s)
+        arena.fill_(0xA5)                                              # the update phase may overwrite everything
+        torch.cuda.synchronize()
+        for ck in reversed(parts):                                     # any order
+            ds.ds_ckpt_finish(ck)
+        ds.ds_event_wait(ev)
+        st = ds.ds_event_stats(ev)
+        ds.ds_event_destroy(ev)
+        assert st["n_pack_launches"] == -(-total // (2 * MiB))
+        tensors = [(sh.tensor_id, W.DTYPES[sh.dtype][0], tuple(sh.shape), o, sh.nbytes)
+                   for sh, o in zip(w.shards, offs)]
+        want_files = fmt.build_rank_files(w.align, want_image.tobytes(), tensors, file_of, n_files, appends)
+        for f in range(n_files):
+            assert open(ck_paths[f], "rb").read() == want_files[f], f
+        print("[step] every checkpoint file == the oracle's file of its shards", flush=True)
+
+        # ONE restore of the rank out of all files
+        readers = [ds.ds_ckpt_open(p) for p in ck_paths]
+        rev = ds.ds_ckpt_restore_parts(readers, eng, plan, 3, file_flags & ds.DS_FILE_DIRECT, s)
+        ds.ds_event_wait(rev)
+        ds.ds_event_destroy(rev)
+        with pytest.raises(ds.DsError) as e:                           # files in the wrong order are refused
+            ds.ds_ckpt_restore_parts(readers[1:] + readers[:1], eng, plan, 3, 0, s)
+        assert e.value.code == ds.DS_EFORMAT
+        for r in readers:
+            ds.ds_ckpt_close(r)
+        mirror = w.arena.copy()
+        try:
+            w.arena[:] = 0xA5
+            for f, (t, k) in enumerate(tabs):
+                orc.unpack(t, k, alone[f])
+            assert gu.first_mismatch(arena.cpu().numpy(), w.arena) is None
+        finally:
+            w.arena[:] = mirror
+        print("[step] restore out of all files == the oracle's", flush=True)
+
+        # the plain flush into several files, and the restore out of them
+        ev = ds.ds_snapshot_async(eng, plan, s)
+        fl = ds.ds_flush_start_files(ev, raw_paths, 2, file_flags)
+        ds.ds_event_wait_on_stream(ev, s)
+        arena.fill_(0x5A)
+        nbytes, _ = ds.ds_flush_wait(fl)
+        ds.ds_event_wait(ev)
+        ds.ds_event_destroy(ev)
+        assert nbytes == total
+        for f in range(n_files):
+            assert open(raw_paths[f], "rb").read() == alone[f].tobytes(), f
+        with pytest.raises(ds.DsError) as e:                           # one path per file of the plan
+            ds.ds_restore_from_files(eng, plan, raw_paths[:-1], 2, 0, s)
+        assert e.value.code == ds.DS_EINVAL
+        rev = ds.ds_restore_from_files(eng, plan, raw_paths, 2, file_flags & ds.DS_FILE_DIRECT, s)
+        ds.ds_event_wait(rev)
+        ds.ds_event_destroy(rev)
+        try:
+            w.arena[:] = 0x5A
+            for f, (t, k) in enumerate(tabs):
+                orc.unpack(t, k, alone[f])
+            assert gu.first_mismatch(arena.cpu().numpy(), w.arena) is None
+        finally:
+            w.arena[:] = mirror
+        # a whole-image flush of the same plan into ONE file is still the image
+        ev = ds.ds_snapshot_async(eng, plan, s)
+        one = str(tmp_path / "rank0_all.img")
+        fl = ds.ds_flush_start(ev, one, 2, file_flags)
+        ds.ds_event_wait_on_stream(ev, s)
+        ds.ds_flush_wait(fl)
+        ds.ds_event_wait(ev)
+        ds.ds_event_destroy(ev)
+        assert open(one, "rb").read() == want_image.tobytes()
+    finally:
+        ds.ds_engine_destroy(eng)
+        torch.cuda.synchronize()
+        ds.ds_plan_destroy(plan)
+
+
 def test_flush_io_error_does_not_stall_the_snapshot():
     """Writers that fail (/dev/full: ENOSPC) still hand every ring slot back, so the
     snapshot runs to its end; the flush reports DS_EIO with the errno."""

@@ -29,7 +29,7 @@ def test_library_exports_every_declared_symbol():
 def test_struct_sizes_match_the_header():
     assert ctypes.sizeof(ds.ds_shard_desc) == 8 + 4 + 4 + 48 + 48 + 8 + 8
     assert ctypes.sizeof(ds.ds_engine_opts) == 48
-    assert ctypes.sizeof(ds.ds_plan_stats) == 72
+    assert ctypes.sizeof(ds.ds_plan_stats) == 80
 
 
 def test_strerror_covers_all_codes():
