@@ -756,10 +756,13 @@ def rank_files_leg(c: Ctx, L: Loaded, cfg, d):
     paths = [os.path.join(d, f"ds_bench_{os.getpid()}_part{f}.ckpt") for f in range(F)]
     one = os.path.join(d, f"ds_bench_{os.getpid()}_whole.ckpt")
     res = {"workload": L.name, "dir": d, "files": F, "smallest_region_bytes": min(regions),
-           "largest_region_bytes": max(regions), "threads": args.file_threads, "engine": engine_json(cfg),
-           "plan_create_ms": round(plan_ms, 3)}
+           "largest_region_bytes": max(regions), "threads": args.file_threads, "d2h_chunk_bytes": cfg["chunk"],
+           "stage_slot_bytes": cfg["slot"], "stage_slots": cfg["slots"], "plan_create_ms": round(plan_ms, 3)}
     try:
         for attempt in ("warm-up", "timed"):
+            for path in paths:                           # new files every time: truncating the warm-up's would
+                if os.path.exists(path):                 # be charged to the request
+                    os.remove(path)
             torch.cuda.synchronize()
             t0 = time.perf_counter()
             ev = ds.ds_snapshot_async(eng, plan, c.stream)
