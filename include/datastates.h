@@ -524,6 +524,21 @@ int ds_ckpt_write_region(ds_ckpt *ckpt, uint64_t file_off, const void *host, uin
 int ds_ckpt_append(ds_ckpt *ckpt, uint64_t object_id, const void *data, uint64_t len);
 
 /*
+ * An object state provider (Sec. V-A3): an iterator that presents the next chunk
+ * of an object's serialized stream -- how many bytes, from where.  Returns 1 with
+ * *data / *len set (the bytes stay valid until the next call), 0 at the end of
+ * the stream, or a negative value to stop with that value as the error.
+ */
+typedef int (*ds_chunk_provider)(void *ctx, const void **data, uint64_t *len);
+
+/* Drains `next` into the log: one ds_ckpt_append per chunk, in the order
+ * presented, so the serializer never has to hold the whole object.  Several
+ * threads may drain providers of different objects into one ds_ckpt at once.
+ * *n_chunks (may be NULL) = chunks appended.  Errors: DS_EINVAL, DS_EIO, or the
+ * provider's own negative value. */
+int ds_ckpt_append_from(ds_ckpt *ckpt, uint64_t object_id, ds_chunk_provider next, void *ctx, uint64_t *n_chunks);
+
+/*
  * Waits for the flush (if one was started), writes trailer and footer, syncs
  * under DS_FILE_SYNC, closes the file and frees the ds_ckpt (also on error).
  * No ds_ckpt_append may be running.  Out pointers may be NULL: the file's

@@ -42,7 +42,7 @@ EXPORTS = [
     "ds_image_diff", "ds_pack_noalloc", "ds_image_compress",
     "ds_plan_create_files", "ds_layout_assign_files", "ds_plan_file", "ds_plan_shard_file", "ds_flush_start_files",
     "ds_restore_from_files", "ds_ckpt_create_part", "ds_ckpt_flush_snapshot_parts", "ds_ckpt_matches_plan_part",
-    "ds_ckpt_restore_parts",
+    "ds_ckpt_restore_parts", "ds_ckpt_append_from",
 ]
 
 
@@ -62,6 +62,10 @@ class ds_plan_stats(ctypes.Structure):
     _fields_ = [(n, ctypes.c_uint64) for n in (
         "total_bytes", "payload_bytes", "n_shards", "n_tiles", "n_chunks", "chunk_bytes", "n_strided", "align",
         "n_general_chunks", "n_files")]
+
+
+ds_chunk_provider = ctypes.CFUNCTYPE(ctypes.c_int, ctypes.c_void_p, ctypes.POINTER(ctypes.c_void_p),
+                                     ctypes.POINTER(ctypes.c_uint64))
 
 
 class ds_engine_opts(ctypes.Structure):
@@ -214,6 +218,7 @@ def _load() -> ctypes.CDLL:
         "ds_event_trace": ([vp, P(ds_trace_rec), sz, P(sz)], ctypes.c_int),
         "ds_image_diff": ([vp, vp, u64, u64, vp, vp], ctypes.c_int),
         "ds_image_compress": ([vp, u64, u64, vp, vp, vp, vp, vp], ctypes.c_int),
+        "ds_ckpt_append_from": ([vp, u64, ds_chunk_provider, vp, P(u64)], ctypes.c_int),
         "ds_plan_create_files": ([P(ds_shard_desc), P(u32), sz, u32, u64, u32, P(vp)], ctypes.c_int),
         "ds_layout_assign_files": ([P(ds_shard_desc), P(u32), sz, u32, u64, P(u64), P(u64)], ctypes.c_int),
         "ds_plan_file": ([vp, u32, P(u64), P(u64)], ctypes.c_int),
@@ -556,6 +561,29 @@ def ds_ckpt_write_region(ckpt: int, file_off: int, host_ptr: int, nbytes: int) -
 def ds_ckpt_append(ckpt: int, object_id: int, data: bytes) -> None:
     _check(_lib.ds_ckpt_append(ckpt, object_id, ctypes.c_char_p(data) if data else None, len(data)),
            "ds_ckpt_append")
+
+
+def ds_ckpt_append_from(ckpt: int, object_id: int, chunks) -> int:
+    """Drains an iterable of bytes-like chunks (an object state provider) into the log; returns the number of
+    chunks appended.  The iterable is pulled from inside the library, one chunk at a time."""
+    it = iter(chunks)
+    keep = []                                            # the chunk handed out last stays alive until the next call
+
+    def next_chunk(_ctx, data, length):
+        try:
+            b = bytes(next(it))
+        except StopIteration:
+            return 0
+        except Exception:                                # noqa: BLE001 -- reported as the provider's error
+            return DS_EINVAL
+        keep[:] = [ctypes.create_string_buffer(b, len(b)) if b else None]
+        data[0] = ctypes.cast(keep[0], ctypes.c_void_p).value if b else None
+        length[0] = len(b)
+        return 1
+    n = ctypes.c_uint64(0)
+    _check(_lib.ds_ckpt_append_from(ckpt, object_id, ds_chunk_provider(next_chunk), None, ctypes.byref(n)),
+           "ds_ckpt_append_from")
+    return int(n.value)
 
 
 def ds_ckpt_finish(ckpt: int) -> Tuple[int, float]:

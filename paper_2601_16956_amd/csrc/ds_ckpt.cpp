@@ -239,6 +239,24 @@ int ds_ckpt_append(ds_ckpt *c, uint64_t object_id, const void *data, uint64_t le
   return DS_OK;
 }
 
+int ds_ckpt_append_from(ds_ckpt *c, uint64_t object_id, ds_chunk_provider next, void *ctx, uint64_t *n_chunks) {
+  if (!c || !next) return DS_EINVAL;
+  uint64_t count = 0;
+  int rc = DS_OK;
+  for (;;) {
+    const void *data = nullptr;
+    uint64_t len = 0;
+    const int more = next(ctx, &data, &len);
+    if (more < 0) { rc = more; break; }   // the provider's own error, handed through
+    if (more == 0) break;
+    rc = ds_ckpt_append(c, object_id, data, len);
+    if (rc != DS_OK) break;
+    ++count;
+  }
+  if (n_chunks) *n_chunks = count;
+  return rc;
+}
+
 int ds_ckpt_finish(ds_ckpt *c, uint64_t *file_bytes, double *seconds) {
   if (!c) return DS_EINVAL;
   int status = DS_OK, err_no = 0;

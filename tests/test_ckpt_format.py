@@ -363,6 +363,46 @@ def test_library_part_files_equal_the_oracle_files(tmp_path):
     ds.ds_plan_destroy(plan)
 
 
+def test_object_state_providers_stream_chunks_into_the_log(tmp_path):
+    """An object handed over as an iterator of chunks (Sec. V-A3) gives the file that the same chunks appended
+    one by one give (the oracle's), two providers on two threads interleave without mixing their objects, and
+    a provider that fails stops its stream with its own error."""
+    w = W.tiny_gpt()
+    plan, d, n, total, image = _host_plan(w)
+    chunks = [b"abc", b"", bytes(range(256)) * 17, b"x" * 4097]
+    path = str(tmp_path / "p.ckpt")
+    ck = ds.ds_ckpt_create(path, plan, 0)
+    ds.ds_ckpt_write_region(ck, 0, image.ctypes.data, total)
+    assert ds.ds_ckpt_append_from(ck, 5, iter(chunks)) == len(chunks)
+    assert ds.ds_ckpt_append_from(ck, 6, []) == 0
+    ds.ds_ckpt_finish(ck)
+    want = fmt.build_file(w.align, image.tobytes(), _manifest(plan, n), [(5, c) for c in chunks])
+    assert open(path, "rb").read() == want
+
+    def gen(tag, k):
+        for i in range(k):
+            yield bytes([tag]) * (1 + (i * 37) % 300)
+    ck = ds.ds_ckpt_create(path, plan, 0)
+    ds.ds_ckpt_write_region(ck, 0, image.ctypes.data, total)
+    ts = [threading.Thread(target=ds.ds_ckpt_append_from, args=(ck, oid, gen(oid, 200))) for oid in (1, 2)]
+    for t in ts:
+        t.start()
+    for t in ts:
+        t.join()
+
+    def failing():
+        yield b"first"
+        raise RuntimeError("serializer failed")
+    with pytest.raises(ds.DsError) as e:
+        ds.ds_ckpt_append_from(ck, 3, failing())
+    assert e.value.code == ds.DS_EINVAL
+    ds.ds_ckpt_finish(ck)
+    back = fmt.parse_file(open(path, "rb").read())
+    assert back["objects"] == {1: b"".join(gen(1, 200)), 2: b"".join(gen(2, 200)), 3: b"first"}
+    assert back["image"] == image.tobytes()
+    ds.ds_plan_destroy(plan)
+
+
 def test_concurrent_appends_form_a_valid_log(tmp_path):
     w = W.tiny_gpt()
     plan, d, n, total, image = _host_plan(w)
