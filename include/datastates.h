@@ -81,7 +81,12 @@ typedef struct ds_shard_desc {
   uint32_t ndim;                  /* 0..DS_MAX_DIMS; 0 = exactly one element                      */
   int64_t shape[DS_MAX_DIMS];     /* extents >= 0 (a zero extent = empty shard, 0 bytes)          */
   int64_t strides[DS_MAX_DIMS];   /* in ELEMENTS, > 0 for every extent > 1; the view must not
-                                     address any element twice                                    */
+                                     address any element twice (DS_EOVERLAP).  Checked exactly:
+                                     by the nesting of the strides where they nest (any slice,
+                                     transpose or permutation of a dense parent does), else by
+                                     writing out the addresses, which is done for views of up
+                                     to 2^20 elements; a larger view with strides that do not
+                                     nest is refused                                              */
   uint64_t tensor_id;             /* logical tensor this shard is a slice of; kept in the plan's
                                      manifest, never touches the bytes                            */
   uint64_t file_offset;           /* byte offset of the shard in the image; multiple of `align`   */

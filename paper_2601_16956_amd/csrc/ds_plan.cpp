@@ -45,8 +45,13 @@ bool shard_bytes(const ds_shard_desc &d, uint64_t *bytes) {
 }
 
 // A view must not address an element twice, else the scatter is ill-defined.
-// Sufficient test: order the dimensions with extent > 1 by stride; every stride
-// must exceed the largest displacement reachable with all smaller ones.
+// Quick test, sufficient but not necessary: order the dimensions with extent > 1 by stride; every
+// stride exceeds the largest displacement reachable with all smaller ones (true of every slice,
+// transpose and permutation of a dense parent).  A view that fails it can still be injective --
+// shape (3,2) with strides (2,3) addresses 0,3,2,5,4,7 -- so up to kEnumerateLimit elements the
+// displacements are then written out and compared; larger views of that kind are refused.
+constexpr uint64_t kEnumerateLimit = (uint64_t)1 << 20;
+
 bool view_is_injective(const ds_shard_desc &d) {
   struct Dim { uint64_t extent, stride; };
   Dim dims[DS_MAX_DIMS];
@@ -59,12 +64,27 @@ bool view_is_injective(const ds_shard_desc &d) {
   }
   std::sort(dims, dims + m, [](const Dim &a, const Dim &b) { return a.stride < b.stride; });
   unsigned __int128 reach = 0;  // largest displacement of the dimensions seen so far
+  bool nested = true;
   for (int k = 0; k < m; ++k) {
-    if ((unsigned __int128)dims[k].stride <= reach) return false;
+    if ((unsigned __int128)dims[k].stride <= reach) nested = false;
     reach += (unsigned __int128)(dims[k].extent - 1) * dims[k].stride;
     if (reach > ((unsigned __int128)1 << 62)) return false;
   }
-  return true;
+  if (nested) return true;
+  uint64_t count = 1;
+  for (int k = 0; k < m; ++k) {
+    if (dims[k].extent > kEnumerateLimit / count) return false;  // too large to write out
+    count *= dims[k].extent;
+  }
+  std::vector<uint64_t> at(1, 0);
+  at.reserve(count);
+  for (int k = 0; k < m; ++k) {
+    const size_t have = at.size();
+    for (uint64_t i = 1; i < dims[k].extent; ++i)
+      for (size_t j = 0; j < have; ++j) at.push_back(at[j] + i * dims[k].stride);
+  }
+  std::sort(at.begin(), at.end());
+  return std::adjacent_find(at.begin(), at.end()) == at.end();
 }
 
 // DS_PLAN_CHECK_MEMORY: every address of a non-empty view, from its base to its last element's last byte,

@@ -652,6 +652,43 @@ def test_contiguous_tensors_at_every_byte_alignment():
             ds.ds_config_set("chunk_bytes", 16384)
 
 
+def test_views_whose_strides_do_not_nest():
+    """Views that address no element twice although a larger stride lies inside the reach of a smaller one
+    (shape (3,2) with strides (2,3) addresses 0,3,2,5,4,7): the plan accepts them after writing the addresses
+    out; gather and scatter against the oracle, whole image and whole arena."""
+    ds, orc, gu = _mods()
+    rng = np.random.default_rng(2323)
+    arena = rng.integers(0, 256, size=4 << 20, dtype=np.uint8)
+    shards, at = [], 0
+    views = [((3, 2), (2, 3)), ((500, 2), (2, 3)), ((2, 700), (3, 2)), ((3, 4, 2), (5, 7, 1)), ((64, 3, 2), (16, 2, 3)),
+             ((1 << 15, 2), (2, 3))]
+    for k, (shape, strides) in enumerate(views):
+        addr = [sum(i * st for i, st in zip(idx, strides)) for idx in np.ndindex(*shape)]
+        assert len(set(addr)) == len(addr)                              # it is a view
+        for dtype, es in (("u8", 1), ("bf16", 2), ("f32", 4), ("i64", 8)):
+            start = (at + 511) // 512 * 512
+            shards.append(Shard(f"v{k}_{dtype}", dtype, shape, strides, start, 10 * k + es))
+            at = start + (max(addr) + 1) * es
+    assert at < arena.size
+    w = _adhoc(arena, shards, 64)
+    want, offs, tab = gu.oracle_image(w)
+    print("[case] strides that do not nest", flush=True)
+    dw = gu.DeviceWorkload(w)
+    try:
+        got = dw.pack()
+        assert gu.first_mismatch(got, want) is None, gu.first_mismatch(got, want)
+        dw.arena.fill_(0x5A)
+        dw.unpack(want)
+        keep = w.arena.copy()
+        w.arena[:] = 0x5A
+        orc.unpack(tab, len(shards), want)
+        bad = gu.first_mismatch(dw.arena_host(), w.arena)
+        w.arena[:] = keep
+        assert bad is None, bad
+    finally:
+        dw.close()
+
+
 @pytest.mark.parametrize("block_bytes", [16384, 65536, 1 << 20])
 def test_image_compress_equals_the_block_elision_oracle(block_bytes):
     """ds_image_compress against oracle/image_compress.py: flags, positions, patterns and the packed blocks,

@@ -102,6 +102,20 @@ def test_plan_validation_codes():
     assert _plan_rc([Shard("x", "f32", (4, 4), (3, 1), 0, 0)], 64) == ds.DS_EOVERLAP    # rows overlap
     assert _plan_rc([Shard("x", "f32", (4, 4), (1, 1), 0, 0)], 64) == ds.DS_EOVERLAP
     assert _plan_rc([Shard("x", "f32", (4, 4), (1, 4), 0, 0)], 64) == 0                 # transposed is fine
+    # strides that do not nest are decided by writing the addresses out: (3,2)/(2,3) -> 0,3,2,5,4,7 is a view,
+    # (3,2)/(2,2) -> 0,2,2,4,4,6 is not; against a brute-force set for every small stride pair
+    assert _plan_rc([Shard("x", "f32", (3, 2), (2, 3), 0, 0)], 64) == 0
+    assert _plan_rc([Shard("x", "f32", (3, 2), (2, 2), 0, 0)], 64) == ds.DS_EOVERLAP
+    for s0 in range(1, 9):
+        for s1 in range(1, 9):
+            for s2 in (1, 5):
+                at = [i * s0 + j * s1 + k * s2 for i in range(3) for j in range(4) for k in range(2)]
+                want = 0 if len(set(at)) == len(at) else ds.DS_EOVERLAP
+                assert _plan_rc([Shard("x", "bf16", (3, 4, 2), (s0, s1, s2), 0, 0)], 64) == want, (s0, s1, s2)
+    # beyond 2^20 elements a view whose strides do not nest is refused
+    # (even addresses, then odd ones from 3 on: no address twice, yet 3 lies inside the reach of the stride 2)
+    assert _plan_rc([Shard("x", "u8", (1 << 19, 2), (2, 3), 0, 0)], 64) == 0
+    assert _plan_rc([Shard("x", "u8", (1 << 20, 2), (2, 3), 0, 0)], 64) == ds.DS_EOVERLAP
     assert _plan_rc([Shard("x", "f32", (1, 4), (0, 1), 0, 0)], 64) == 0                 # stride of an extent 1 is free
     assert _plan_rc([Shard("x", "f32", (4,), (1,), 2, 0)], 64) == ds.DS_EINVAL          # base not element-aligned
     assert _plan_rc([Shard("x", "f32", (4,), (1,), 0, 0)], 64, base=0) == ds.DS_EINVAL  # null base
