@@ -231,7 +231,7 @@ int ds_unpack(const ds_plan *plan, const void *src_dev, uint64_t img_lo, uint64_
  * GPU it runs on until the process ends, and calls neither hipMalloc nor
  * hipFree nor anything else that allocates.  `plan` may therefore be a
  * DS_PLAN_HOST_ONLY plan, whose creation touches no device either.
- * Limit: the tables (128 bytes per non-empty shard, 36 bytes per work-group
+ * Limit: the tables (168 bytes per non-empty shard, 36 bytes per work-group
  * chunk of the image, i.e. about 2.3 KiB per MiB of image) must fit the array:
  * an image of about 1.7 GB with few shards does, DS_ETOOBIG otherwise
  * (returned before anything is enqueued).  All calls on one GPU share the one
