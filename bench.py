@@ -1089,7 +1089,16 @@ def microbench(c: Ctx) -> int:
     want = set(args.tables.split(",")) if args.tables else None
     if want is None or "contiguous" in want:
         out["contiguous_1GiB"] = run([buf[:1 << 30]], 4096)
-    for size in (12288, 12296, 1024, 1032, 208, 200):
+    sizes = [12288, 12296, 1024, 1032, 208, 200]
+    shapes = [(2048, 2304), (2048, 4096), (2048, 8192), (2048, 8256), (2048, 16384), (2048, 65536), (2048, 131072),
+              (5504, 22016), (5504, 22528), (5504, 7552), (2752, 11008), (2752, 11264), (512, 2048)]
+    for item in sorted(want or ()):                      # tables beyond the standard ones may be named too
+        kind, _, spec = item.partition(":")
+        if kind == "general" and int(spec) not in sizes:
+            sizes.append(int(spec))
+        if kind == "rows" and tuple(map(int, spec.split("x"))) not in shapes:
+            shapes.append(tuple(map(int, spec.split("x"))))
+    for size in sizes:
         if want is not None and f"general:{size}" not in want:
             continue
         pitch = (size + 511) // 512 * 512 + 512
@@ -1097,8 +1106,7 @@ def microbench(c: Ctx) -> int:
         r = run([buf[i * pitch + 3: i * pitch + 3 + size] for i in range(n)], 512)
         out["general_path"].append({"tensor_bytes": size, "tensors": n, **r})
         log(f"[microbench] general path, tensors of {size} B: {r['gather_GBps']} / {r['scatter_GBps']} GB/s")
-    for row, pitch in ((2048, 2304), (2048, 4096), (2048, 8192), (2048, 8256), (2048, 16384), (2048, 65536), (2048, 131072),
-                       (5504, 22016), (5504, 22528), (5504, 7552), (2752, 11008), (2752, 11264), (512, 2048)):
+    for row, pitch in shapes:
         if want is not None and f"rows:{row}x{pitch}" not in want:
             continue
         rows = min((768 << 20) // row, (BUF - row) // pitch)

@@ -652,6 +652,53 @@ def test_contiguous_tensors_at_every_byte_alignment():
             ds.ds_config_set("chunk_bytes", 16384)
 
 
+def test_row_views_at_every_byte_alignment():
+    """2-D views whose rows start at every byte position relative to a multiple of 16 (base address, row length
+    and pitch all vary; rows from 16 bytes to several chunks), each many chunks long: the lean row path with
+    its unaligned 16-byte accesses and its units cut by row ends (spliced from two in-row loads in the gather,
+    stored in pieces by the scatter).  Gather (whole and in ranges) and scatter against the oracle, whole image
+    and whole arena, at the three chunk sizes."""
+    ds, orc, gu = _mods()
+    rng = np.random.default_rng(2718)
+    arena = rng.integers(0, 256, size=96 << 20, dtype=np.uint8)
+    shards, at = [], 0
+    shapes = [(16, 24), (17, 23), (18, 27), (31, 33), (33, 48), (47, 47 * 3), (100, 150), (510, 765), (1000, 1500),
+              (4094, 6141), (5504, 22016 + 2), (16384 + 6, 16384 + 38), (40000, 40002)]
+    for k, (run, pitch) in enumerate(shapes):
+        for dtype, es in (("u8", 1), ("bf16", 2), ("f32", 4), ("i64", 8)):
+            if run % es or pitch % es:
+                continue
+            m = int(rng.integers(0, 16 // es)) * es if es < 16 else 0
+            rows = max(3, (int(rng.integers(70, 200)) * 1024) // run)
+            start = (at + 255) // 256 * 256 + m
+            shards.append(Shard(f"r{k}_{dtype}", dtype, (rows, run // es), (pitch // es, 1), start, 100 * k + es))
+            at = start + (rows - 1) * pitch + run
+    assert at < arena.size
+    w = _adhoc(arena, shards, 256)
+    want, offs, tab = gu.oracle_image(w)
+    for chunk_bytes in (16384, 8192, 32768):
+        ds.ds_config_set("chunk_bytes", chunk_bytes)
+        print(f"[case] row alignments, chunk {chunk_bytes}", flush=True)
+        dw = gu.DeviceWorkload(w)
+        try:
+            got = dw.pack()
+            assert gu.first_mismatch(got, want) is None, (chunk_bytes, gu.first_mismatch(got, want))
+            for lo, hi in ((16, dw.total - 48), (dw.total // 3 // 16 * 16, dw.total // 2 // 16 * 16)):
+                part = dw.pack(lo, hi)
+                assert gu.first_mismatch(part, want[lo:hi]) is None, (chunk_bytes, lo, hi)
+            dw.arena.fill_(0x5A)
+            dw.unpack(want)
+            keep = w.arena.copy()
+            w.arena[:] = 0x5A
+            orc.unpack(tab, len(shards), want)
+            bad = gu.first_mismatch(dw.arena_host(), w.arena)
+            w.arena[:] = keep
+            assert bad is None, (chunk_bytes, bad)
+        finally:
+            dw.close()
+            ds.ds_config_set("chunk_bytes", 16384)
+
+
 def test_views_whose_strides_do_not_nest():
     """Views that address no element twice although a larger stride lies inside the reach of a smaller one
     (shape (3,2) with strides (2,3) addresses 0,3,2,5,4,7): the plan accepts them after writing the addresses
