@@ -748,6 +748,55 @@ def test_flush_io_error_does_not_stall_the_snapshot():
         dw.close()
 
 
+def test_flush_to_several_files_with_one_that_fails(tmp_path):
+    """One of the files of a plan of several cannot be written (/dev/full: ENOSPC): the flush reports DS_EIO
+    with the errno, every ring slot still goes back (pieces of a slot that lie in other files included), so
+    the snapshot runs to its end, and the next flush of the same plan into good files is byte-exact."""
+    import os
+    if not os.path.exists("/dev/full"):
+        pytest.skip("no /dev/full here")
+    ds, orc, gu, torch = _mods()
+    w = W.fragmentation(1200, max_bytes=1 << 16, seed=96)
+    n = len(w.shards)
+    print("[case] several files, one fails", flush=True)
+    arena = torch.from_numpy(w.arena).to("cuda")
+    file_of = [min(3, (4 * i) // n) for i in range(n)]
+    descs = ds.make_descs(w.shards, arena.data_ptr())
+    regions, total = ds.ds_layout_assign_files(descs, file_of, n, 4, w.align)
+    plan = ds.ds_plan_create_files(descs, file_of, n, 4, w.align, ds.DS_PLAN_STRICT | ds.DS_PLAN_CHECK_MEMORY)
+    eng = ds.ds_engine_create(4 * MiB, 1 * MiB, 4 * MiB, 2, 0, 0, 1)       # ring smaller than the image
+    s = torch.cuda.current_stream().cuda_stream
+    good = [str(tmp_path / f"f{k}.img") for k in range(4)]
+    try:
+        for fflags in (0, ds.DS_FILE_DIRECT, ds.DS_FILE_URING):
+            ev = ds.ds_snapshot_async(eng, plan, s)
+            fl = ds.ds_flush_start_files(ev, [good[0], "/dev/full", good[2], good[3]], 3, fflags)
+            ds.ds_event_wait_on_stream(ev, s)
+            with pytest.raises(ds.DsError) as e:
+                ds.ds_flush_wait(fl)
+            assert e.value.code == ds.DS_EIO and ds.ds_last_errno() == 28
+            ds.ds_event_wait(ev)                  # the snapshot itself completed
+            ds.ds_event_destroy(ev)
+        with pytest.raises(ds.DsError) as e:      # a file that cannot be created: nothing is started
+            ds.ds_flush_start_files(ev := ds.ds_snapshot_async(eng, plan, s), [good[0], str(tmp_path / "no" / "dir"),
+                                                                             good[2], good[3]], 2, 0)
+        assert e.value.code == ds.DS_EIO and ds.ds_last_errno() == 2
+        fl = ds.ds_flush_start_files(ev, good, 2, ds.DS_FILE_DIRECT)       # the same snapshot, now into good files
+        ds.ds_event_wait_on_stream(ev, s)
+        assert ds.ds_flush_wait(fl)[0] == total
+        ds.ds_event_wait(ev)
+        ds.ds_event_destroy(ev)
+        for f in range(4):
+            sub = [sh for sh, g in zip(w.shards, file_of) if g == f]
+            t = orc.table(sub, w.arena.ctypes.data)
+            assert orc.layout(t, len(sub), w.align) == regions[f]
+            assert open(good[f], "rb").read() == orc.pack(t, len(sub), regions[f], threads=4).tobytes(), f
+    finally:
+        ds.ds_engine_destroy(eng)
+        torch.cuda.synchronize()
+        ds.ds_plan_destroy(plan)
+
+
 def test_timeline_trace_of_a_snapshot():
     """An engine with DS_ENGINE_TRACE times every chunk copy: the records cover the
     image exactly once per tier, every copy starts after the gather that filled its
