@@ -771,7 +771,8 @@ def rank_files_leg(c: Ctx, L: Loaded, cfg, d):
            "largest_region_bytes": max(regions), "threads": args.file_threads, "d2h_chunk_bytes": cfg["chunk"],
            "stage_slot_bytes": cfg["slot"], "stage_slots": cfg["slots"], "plan_create_ms": round(plan_ms, 3)}
     try:
-        for attempt in ("warm-up", "timed"):
+        best = None                                      # one warm-up, then the better of two timed attempts
+        for attempt in ("warm-up", "timed", "timed"):
             for path in paths:                           # new files every time: truncating the warm-up's would
                 if os.path.exists(path):                 # be charged to the request
                     os.remove(path)
@@ -788,6 +789,9 @@ def rank_files_leg(c: Ctx, L: Loaded, cfg, d):
             ds.ds_event_wait(ev)
             st = ds.ds_event_stats(ev)
             ds.ds_event_destroy(ev)
+            if attempt == "timed" and (best is None or cap_ms < best[0]):
+                best = (cap_ms, st, files_s)
+        cap_ms, st, files_s = best
         res.update({"file_bytes": nbytes, "request_to_all_captured_ms": round(cap_ms, 3),
                     "capture_ms_device_events": round(st["capture_ms"], 3),
                     "gather_launches": st["n_pack_launches"],
@@ -809,20 +813,27 @@ def rank_files_leg(c: Ctx, L: Loaded, cfg, d):
         for r in readers:
             ds.ds_ckpt_close(r)
         res["files_to_gpu_GBps"] = round(L.payload / load_s / 1e9, 2)
-        # the same state as ONE file, same engine
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        ev = ds.ds_snapshot_async(eng, L.plan, c.stream)
-        ck = ds.ds_ckpt_create(one, L.plan, file_flags)
-        ds.ds_ckpt_flush_snapshot(ck, ev, args.file_threads)
-        ds.ds_event_wait_on_stream(ev, c.stream)
-        ds.ds_event_wait_captured(ev)
-        cap1_ms = (time.perf_counter() - t0) * 1e3
-        nbytes1, _ = ds.ds_ckpt_finish(ck)
-        one_s = time.perf_counter() - t0
-        ds.ds_event_wait(ev)
-        st1 = ds.ds_event_stats(ev)
-        ds.ds_event_destroy(ev)
+        # the same state as ONE file, same engine, the better of two attempts
+        best = None
+        for attempt in ("timed", "timed"):
+            if os.path.exists(one):
+                os.remove(one)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            ev = ds.ds_snapshot_async(eng, L.plan, c.stream)
+            ck = ds.ds_ckpt_create(one, L.plan, file_flags)
+            ds.ds_ckpt_flush_snapshot(ck, ev, args.file_threads)
+            ds.ds_event_wait_on_stream(ev, c.stream)
+            ds.ds_event_wait_captured(ev)
+            cap1_ms = (time.perf_counter() - t0) * 1e3
+            nbytes1, _ = ds.ds_ckpt_finish(ck)
+            one_s = time.perf_counter() - t0
+            ds.ds_event_wait(ev)
+            st1 = ds.ds_event_stats(ev)
+            ds.ds_event_destroy(ev)
+            if best is None or cap1_ms < best[0]:
+                best = (cap1_ms, st1, one_s)
+        cap1_ms, st1, one_s = best
         res["same_state_as_one_file"] = {"request_to_captured_ms": round(cap1_ms, 3),
                                          "capture_ms_device_events": round(st1["capture_ms"], 3),
                                          "snapshot_to_file_GBps": round(nbytes1 / one_s / 1e9, 2)}
