@@ -1170,9 +1170,10 @@ def main() -> int:
     ap.add_argument("--experiments", action="store_true",
                     help="the capture variants in full (more grid limits, the rank's state as several plans and "
                          "several checkpoint files); the default run measures a compact set of them")
-    ap.add_argument("--variant", type=int, default=0, choices=[0, 1, 2, 3, 4],
+    ap.add_argument("--variant", type=int, default=0, choices=[0, 1, 2, 3, 4, 5],
                     help="kernel variant (ds_config_set): 0 default, 1 plain accesses, 2 non-temporal global accesses, "
-                         "3 default accesses with work-group i on chunk i")
+                         "3 default accesses with work-group i on chunk i, 4 no aligned-load route, "
+                         "5 four wavefronts per SIMD also for plans of mostly general chunks")
     ap.add_argument("--timeline", default=None, metavar="FILE",
                     help="also trace one snapshot step by step (gather launches, every chunk copy) and write the "
                          "timeline to FILE as text")

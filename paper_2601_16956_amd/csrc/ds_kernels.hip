@@ -776,9 +776,14 @@ __device__ __forceinline__ bool lean_chunk(const LeanArgs &a, uint32_t ci, uint6
 //
 // A lean chunk is exactly 256 threads x UNROLL x 16 bytes; the general path always works in passes of
 // 256 x 4 units.
-template <bool PACK, int UNROLL, bool NTL, bool NTS, bool BUFST>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 4))) void ds_move_kernel(LeanArgs la,
-                                                                                                 MoveArgs ma) {
+//
+// WAVES = 5 is the instantiation for plans in which most chunks are general (tables of thousands of tiny
+// tensors): that path is bound by its chain of dependent loads, not by HBM, and a fifth wavefront per SIMD
+// hides more of it (measured on tables where every chunk is general: +8 to +10 % both ways), while the lean
+// path loses 2 to 5 % there.
+template <bool PACK, int UNROLL, bool NTL, bool NTS, bool BUFST, int WAVES>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, WAVES))) void ds_move_kernel(LeanArgs la,
+                                                                                                     MoveArgs ma) {
   __shared__ GenLds s_gen;
   const uint32_t n_lean = lean_items(la);
   const uint32_t n_iter = n_lean + ma.n_extra;
@@ -801,13 +806,13 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 4))) voi
   }
 }
 
-template <bool PACK, bool NTL, bool NTS, bool BUFST>
+template <bool PACK, bool NTL, bool NTS, bool BUFST, int WAVES = 4>
 int launch_move(uint32_t chunk_log2, const LeanArgs &la, const MoveArgs &ma, uint32_t grid_limit, hipStream_t stream) {
   uint32_t grid = (la.xcd_span ? la.xcd_span * 8 : la.n_chunks) + ma.n_extra;
   if (grid == 0) return DS_OK;
   if (grid_limit && grid > grid_limit) grid = grid_limit;
 #define DS_MOVE(UN) \
-  hipLaunchKernelGGL((ds_move_kernel<PACK, UN, NTL, NTS, BUFST>), dim3(grid), dim3(256), 0, stream, la, ma)
+  hipLaunchKernelGGL((ds_move_kernel<PACK, UN, NTL, NTS, BUFST, WAVES>), dim3(grid), dim3(256), 0, stream, la, ma)
   switch (chunk_log2) {
     case 13: DS_MOVE(2); break;
     case 14: DS_MOVE(4); break;
@@ -1074,7 +1079,11 @@ int launch_move_with(const ds_plan *plan, const DeviceTables &tb, bool pack, uin
     return pack ? launch_move<true, true, true, false>(lg, la, ma, grid_limit, stream)
                 : launch_move<false, true, true, false>(lg, la, ma, grid_limit, stream);
   }
-  // default: non-temporal accesses, and the lean gather writes the image with "sc0 sc1 nt" buffer stores
+  // default: non-temporal accesses, and the lean gather writes the image with "sc0 sc1 nt" buffer stores;
+  // five wavefronts per SIMD instead of four where most of the plan's chunks take the general path
+  if (plan->n_general * 2 > n_total && variant != 5)
+    return pack ? launch_move<true, true, true, true, 5>(lg, la, ma, grid_limit, stream)
+                : launch_move<false, true, true, false, 5>(lg, la, ma, grid_limit, stream);
   return pack ? launch_move<true, true, true, true>(lg, la, ma, grid_limit, stream)
               : launch_move<false, true, true, false>(lg, la, ma, grid_limit, stream);
 }

@@ -219,7 +219,7 @@ int ds_config_set(const char *key, uint64_t value) {
     return DS_OK;
   }
   if (!std::strcmp(key, "variant")) {
-    if (value > 4) return DS_EINVAL;
+    if (value > 5) return DS_EINVAL;
     g_variant.store(value);
     return DS_OK;
   }

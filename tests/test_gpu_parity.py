@@ -64,7 +64,7 @@ def test_unpack_matches_oracle(name):
 
 
 @pytest.mark.parametrize("chunk_bytes", [8192, 16384, 32768])
-@pytest.mark.parametrize("variant", [0, 1, 2, 3])
+@pytest.mark.parametrize("variant", [0, 1, 2, 3, 4, 5])
 def test_chunk_sizes_and_kernel_variants(chunk_bytes, variant):
     ds, orc, gu = _mods()
     w = W.fragmentation(1500, max_bytes=1 << 19, seed=77)
@@ -650,6 +650,47 @@ def test_contiguous_tensors_at_every_byte_alignment():
         finally:
             dw.close()
             ds.ds_config_set("chunk_bytes", 16384)
+
+
+def test_plans_of_mostly_general_chunks():
+    """A table of thousands of tiny tensors (every 16 KiB chunk holds tile boundaries): such a plan is launched
+    with five wavefronts per SIMD instead of four (variant 5 keeps four).  Both launches against the oracle,
+    gather and scatter, whole image and whole arena."""
+    ds, orc, gu = _mods()
+    rng = np.random.default_rng(555)
+    arena = rng.integers(0, 256, size=48 << 20, dtype=np.uint8)
+    shards, at = [], 0
+    for k in range(30000):
+        dtype, es = [("u8", 1), ("bf16", 2), ("f32", 4), ("i64", 8)][k % 4]
+        n = int(rng.integers(1, 1100 // es))
+        start = (at + 7) // 8 * 8 + int(rng.integers(0, 8 // es)) * es
+        shards.append(Shard(f"t{k}", dtype, (n,), (1,), start, k))
+        at = start + n * es
+    assert at < arena.size
+    w = _adhoc(arena, shards, 512)
+    want, offs, tab = gu.oracle_image(w)
+    old_v = ds.ds_config_get("variant")
+    try:
+        for variant in (0, 5):
+            ds.ds_config_set("variant", variant)
+            print(f"[case] mostly general chunks, variant {variant}", flush=True)
+            dw = gu.DeviceWorkload(w)
+            try:
+                assert dw.info["n_general_chunks"] * 2 > dw.info["n_chunks"]
+                got = dw.pack()
+                assert gu.first_mismatch(got, want) is None, (variant, gu.first_mismatch(got, want))
+                dw.arena.fill_(0x5A)
+                dw.unpack(want)
+                keep = w.arena.copy()
+                w.arena[:] = 0x5A
+                orc.unpack(tab, len(shards), want)
+                bad = gu.first_mismatch(dw.arena_host(), w.arena)
+                w.arena[:] = keep
+                assert bad is None, (variant, bad)
+            finally:
+                dw.close()
+    finally:
+        ds.ds_config_set("variant", old_v)
 
 
 def test_row_views_at_every_byte_alignment():

@@ -161,7 +161,7 @@ def test_config_keys():
     with pytest.raises(ds.DsError):
         ds.ds_config_set("no_such_key", 1)
     with pytest.raises(ds.DsError):
-        ds.ds_config_set("variant", 5)
+        ds.ds_config_set("variant", 6)
     assert ds.ds_config_get("grid_limit") == 0
     ds.ds_config_set("grid_limit", 64)
     assert ds.ds_config_get("grid_limit") == 64
