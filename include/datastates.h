@@ -668,7 +668,8 @@ int ds_image_compress(const void *image_dev, uint64_t nbytes, uint64_t block_byt
  *                   under it do not mark chunks for the gather's aligned-load route (tensors at
  *                   addresses that are not multiples of 16 are then read with unaligned loads),
  *                   5 = default, but a plan in which most chunks take the general path is launched
- *                   with four wavefronts per SIMD like any other (by default it gets five)
+ *                   with four wavefronts per SIMD like any other (by default it gets five for the
+ *                   gather and six for the scatter)
  *   "grid_limit"    work-groups per launch of ds_pack / ds_unpack (each then walks several chunks);
  *                   0 = one per chunk (default).  Engines have their own pack_grid_limit
  *   "drop_pinned_cache"   (set only) a non-zero value frees the pinned ring and the device staging the

@@ -777,10 +777,11 @@ __device__ __forceinline__ bool lean_chunk(const LeanArgs &a, uint32_t ci, uint6
 // A lean chunk is exactly 256 threads x UNROLL x 16 bytes; the general path always works in passes of
 // 256 x 4 units.
 //
-// WAVES = 5 is the instantiation for plans in which most chunks are general (tables of thousands of tiny
-// tensors): that path is bound by its chain of dependent loads, not by HBM, and a fifth wavefront per SIMD
-// hides more of it (measured on tables where every chunk is general: +8 to +10 % both ways), while the lean
-// path loses 2 to 5 % there.
+// WAVES = 6 is the instantiation for plans in which most chunks are general (tables of thousands of tiny
+// tensors): that path is bound by its chain of dependent loads, not by HBM, and more wavefronts per SIMD hide
+// more of it -- five for the gather, whose registers allow no more, six for the scatter (measured on tables
+// where every chunk is general: +8 to +10 % both ways with five, another +6 to +10 % for the scatter of tiny
+// tensors with six), while the lean path loses 2 to 5 % there.
 template <bool PACK, int UNROLL, bool NTL, bool NTS, bool BUFST, int WAVES>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, WAVES))) void ds_move_kernel(LeanArgs la,
                                                                                                      MoveArgs ma) {
@@ -1080,10 +1081,11 @@ int launch_move_with(const ds_plan *plan, const DeviceTables &tb, bool pack, uin
                 : launch_move<false, true, true, false>(lg, la, ma, grid_limit, stream);
   }
   // default: non-temporal accesses, and the lean gather writes the image with "sc0 sc1 nt" buffer stores;
-  // five wavefronts per SIMD instead of four where most of the plan's chunks take the general path
+  // as many wavefronts per SIMD as the registers allow, up to six, instead of four where most of the plan's
+  // chunks take the general path
   if (plan->n_general * 2 > n_total && variant != 5)
-    return pack ? launch_move<true, true, true, true, 5>(lg, la, ma, grid_limit, stream)
-                : launch_move<false, true, true, false, 5>(lg, la, ma, grid_limit, stream);
+    return pack ? launch_move<true, true, true, true, 6>(lg, la, ma, grid_limit, stream)
+                : launch_move<false, true, true, false, 6>(lg, la, ma, grid_limit, stream);
   return pack ? launch_move<true, true, true, true>(lg, la, ma, grid_limit, stream)
               : launch_move<false, true, true, false>(lg, la, ma, grid_limit, stream);
 }
