@@ -329,8 +329,9 @@ int ds_event_wait(ds_event *ev);
 /*
  * Consumer side (Sec. V-A3: the stream is exposed chunk by chunk, each an
  * address and a length): blocks until the next chunk of the image is resident in the ring,
- * then returns its host address, its offset in the file and its length.
- * Chunks come in file order.  DS_EOF after the last.  The memory stays valid
+ * then returns its host address, its offset in the image (which is the offset in
+ * the file for a plan of one file; ds_plan_file maps it for a plan of several)
+ * and its length.  Chunks come in image order.  DS_EOF after the last.  The memory stays valid
  * until ds_snapshot_release_chunk.  Not used with DS_ENGINE_AUTO_RELEASE.
  */
 int ds_snapshot_next_chunk(ds_event *ev, const void **host_ptr, uint64_t *file_off, uint64_t *len);
