@@ -4,8 +4,9 @@ while the compute stream runs back-to-back 8192^3 bf16 GEMMs and a mutating upda
 Sec. IV-B: the state is immutable during forward/backward).  A consumer thread copies every chunk out of the
 ring; every host image must equal the CPU oracle's image of the mirror state at that snapshot's request, so a
 torn snapshot -- an update that overtook a gather, a ring slot or a piece of staging reused too early -- shows as
-a mismatch.  Three engines: the benchmark's (ring 2 GiB of 128 MiB slots, staging 2 x 2 GiB, one copy stream), a ring smaller than the image, and
-ring and staging both smaller than the image, which forces chunked double-buffering on both sides."""
+a mismatch.  Three engines: the benchmark's (ring 2 GiB of 128 MiB slots, staging 2 x 2 GiB, one copy stream),
+a ring smaller than the image, and ring and staging both smaller than the image, which forces chunked
+double-buffering on both sides."""
 import ctypes
 import os
 import threading
