@@ -107,9 +107,22 @@ def test_rank_files_by_hand_and_against_the_single_file_layout():
     #   file 2: the 33-byte shard at 0                                                -> region 48
     offs, regions, begins = fmt.rank_files([20, 5, 0, 16, 33], [1, 0, 1, 0, 2], 3, 16)
     assert offs == [0, 0, 32, 16, 0] and regions == [32, 32, 48] and begins == [0, 32, 64]
-    # a file nobody names is empty and takes no room in the image
-    offs, regions, begins = fmt.rank_files([20, 5], [2, 0], 4, 16)
-    assert offs == [0, 0] and regions == [16, 0, 32, 0] and begins == [0, 16, 16, 48]
+    # the same and two more tables, from the fixture (a file nobody names is empty and takes no room in the
+    # image); the library's layout is held to the same numbers
+    for case in json.load(open(os.path.join(HERE, "golden", "rank_files_hand.json")))["cases"]:
+        got = fmt.rank_files(case["bytes"], case["file_of"], case["n_files"], case["align"])
+        assert got == (case["offsets_in_file"], case["regions"], case["image_begins"]), case["comment"]
+        n = len(case["bytes"])
+        d = (ds.ds_shard_desc * n)()
+        for i, b in enumerate(case["bytes"]):
+            d[i].base, d[i].dtype, d[i].ndim = 0x10000, ds.DS_U8, 1
+            d[i].shape[0], d[i].strides[0] = b, 1
+        lib_regions, lib_total = ds.ds_layout_assign_files(d, case["file_of"], n, case["n_files"], case["align"])
+        assert lib_regions == case["regions"] and lib_total == sum(case["regions"])
+        assert [d[i].file_offset for i in range(n)] == case["offsets_in_file"]
+        plan = ds.ds_plan_create_files(d, case["file_of"], n, case["n_files"], case["align"], ds.DS_PLAN_HOST_ONLY)
+        assert [ds.ds_plan_file(plan, f) for f in range(case["n_files"])] == list(zip(case["image_begins"], case["regions"]))
+        ds.ds_plan_destroy(plan)
     for bad in ([0, 3], [-1, 0]):
         with pytest.raises(fmt.FormatError):
             fmt.rank_files([1, 1], bad, 3, 16)
